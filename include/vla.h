@@ -1,0 +1,174 @@
+/*
+ * vla.h -- C-ABI of the MI355X (gfx950) library for the batched VLA policy rollout step and
+ * the PPO/GRPO log-probability recompute.
+ *
+ * The operations follow the paper's statement of the problem:
+ *   - generation: at every simulator step the policy infers an action (chunk) from the current
+ *     observation, a_t ~ pi_theta(. | o_t), for all parallel environments (sections III-A,
+ *     III-C); an atomic action is M tokens, one per action dimension, a chunk is C atomic
+ *     actions (section III-B);
+ *   - token-level log-probabilities pi(d_{t,i,j} | o_t, d_{t,i,:j-1}) (section IV-C.1);
+ *   - the recompute of log pi_theta on stored (o_t, a_t) that the importance ratio
+ *     rho = pi_theta / pi_theta_old of the PPO and GRPO objectives needs (appendix I-B, I-C);
+ *   - a lightweight value head attached to the language model (section IV-C.2).
+ * The decoder itself is a Llama-style pre-norm transformer (RMSNorm, rotary with half-split
+ * pairing, multi-head causal attention without biases, SwiGLU); action tokens are the last
+ * n_bins = 256 vocabulary ids and every distribution is over those 256 bins only.
+ *
+ * Conventions for every function below
+ *   - Pointers marked DEVICE are device memory owned by the caller; pointers marked HOST are
+ *     host memory.  The three hot calls never allocate or free device memory.
+ *   - All device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream).  No call synchronises; outputs are valid once the caller has
+ *     synchronised the stream.  Calls that share a KV buffer or workspace must be ordered by
+ *     the caller (same stream, or events).
+ *   - Return value: VLA_OK (0) or a negative error code.  On error nothing has been enqueued
+ *     (except for VLA_EHIP, which reports a failed launch) and vla_last_error() returns a
+ *     thread-local, NUL-terminated HOST string describing it.  No exception crosses the ABI.
+ *   - "dtype" below means the storage type selected by vla_config.dtype: float (VLA_DTYPE_F32)
+ *     or bfloat16 (VLA_DTYPE_BF16).  Weight matrices, patch embeddings, slot embeddings and the
+ *     KV cache use it; norm gains, the value head, noise and every output are fp32.
+ *     Accumulation, the residual stream, norms, softmax and the action-bin head are fp32.
+ *   - Weight matrices are row-major [out, in].
+ */
+#ifndef VLA_H
+#define VLA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VLA_VERSION 1
+
+#define VLA_OK          0
+#define VLA_EINVAL     (-1)  /* null pointer, negative or zero size, bad enum              */
+#define VLA_ESHAPE     (-2)  /* exceeds max_batch / max_seq, or unsupported dimensions      */
+#define VLA_EWORKSPACE (-3)  /* workspace (or KV buffer) smaller than required              */
+#define VLA_EDTYPE     (-4)  /* unknown dtype                                               */
+#define VLA_EHIP       (-5)  /* a HIP call or kernel launch failed                          */
+
+#define VLA_DTYPE_F32  0
+#define VLA_DTYPE_BF16 1
+
+#define VLA_MODE_AR             0  /* autoregressive: token j+1 conditioned on tokens 1..j   */
+#define VLA_MODE_PARALLEL_CHUNK 1  /* all A slots in one forward, bidirectional among slots  */
+
+#define VLA_ENTRY_PREFILL   0
+#define VLA_ENTRY_DECODE    1
+#define VLA_ENTRY_RECOMPUTE 2
+
+#define VLA_N_BINS 256
+
+typedef struct vla_config {
+    int32_t n_layers, hidden, n_heads, ffn, vocab;
+    int32_t n_bins;      /* must be 256; bin k is token id vocab - 256 + k                   */
+    int32_t dtype;       /* VLA_DTYPE_*                                                      */
+    float   rms_eps;     /* RMSNorm epsilon                                                  */
+    float   rope_theta;  /* rotary base                                                      */
+    int32_t max_batch;   /* capacity: sequences per call                                     */
+    int32_t max_seq;     /* capacity: positions per sequence (prefix + action rows); also the
+                            position stride of the KV buffer                                 */
+} vla_config;
+
+/* DEVICE pointers.  attn_norm, ffn_norm: fp32 [hidden].  wq, wk, wv, wo: dtype [hidden, hidden].
+ * w_gate, w_up: dtype [ffn, hidden].  w_down: dtype [hidden, ffn]. */
+typedef struct vla_layer_weights {
+    const void *attn_norm, *wq, *wk, *wv, *wo, *ffn_norm, *w_gate, *w_up, *w_down;
+} vla_layer_weights;
+
+/* embed, lm_head: DEVICE dtype [vocab, hidden] (only the last 256 rows of lm_head are read).
+ * final_norm: DEVICE fp32 [hidden].  value_w: DEVICE fp32 [hidden] or NULL (no value head).
+ * layers: HOST array of n_layers entries, copied by vla_create. */
+typedef struct vla_weights {
+    const void *embed, *lm_head, *final_norm, *value_w;
+    float value_b;
+    const vla_layer_weights *layers;
+} vla_weights;
+
+typedef struct vla_model vla_model;
+
+int vla_version(void);
+
+/* HOST string describing the calling thread's last error ("" if none). */
+const char *vla_last_error(void);
+
+/* Create a host-side model object.  It stores the configuration and the weight POINTERS only;
+ * the weights stay owned by the caller and must outlive the model.  Checks the dimensions:
+ * hidden = n_heads * head_dim with head_dim a multiple of 8 and at most 256; n_bins = 256
+ * <= vocab; positive sizes.  Touches no device. */
+int vla_create(const vla_config *cfg, const vla_weights *weights, vla_model **out);
+int vla_destroy(vla_model *model);
+
+/* Bytes of the caller-allocated KV buffer for B sequences of up to max_pos positions
+ * (max_pos <= cfg->max_seq; the buffer is always laid out with cfg->max_seq positions per
+ * sequence, so the same B must be used by every call sharing it).  Layout is opaque.
+ * Returns 0 on invalid arguments (see vla_last_error). */
+size_t vla_kv_bytes(const vla_config *cfg, int B, int max_pos);
+
+/* Bytes of workspace the given entry point needs for B sequences, prefix length S and A action
+ * tokens (for VLA_ENTRY_RECOMPUTE, B is the number of stored rollouts N; the call processes
+ * them in micro-batches, so the size stops growing beyond an internal micro-batch).  The
+ * workspace holds no state between calls.  Returns 0 on invalid arguments. */
+size_t vla_workspace_bytes(const vla_config *cfg, int entry, int B, int S, int A);
+
+/* Prefill (sections III-A, III-C: the observation o_t enters the policy).  For each of B
+ * environments, the prefix rows x_p = patch[p] (p < P), x_{P+t} = embed[ids[t]] run through all
+ * decoder layers with causal attention; K and V of every prefix row are written to `kv`.
+ *   kv        DEVICE, >= vla_kv_bytes(cfg, B, P+T)        ws  DEVICE workspace, ws_bytes long
+ *   patch     DEVICE dtype [B, P, hidden] (P may be 0)     ids DEVICE int32 [B, T] in [0, vocab)
+ *   h_last    DEVICE fp32 [B, hidden] out: final-norm output of the last prefix row
+ *   value     DEVICE fp32 [B] out or NULL: value_w . h_last + value_b (section IV-C.2)
+ * Requires P + T >= 1, B <= max_batch, P + T <= max_seq. */
+int vla_prefill(vla_model *model, void *kv, void *ws, size_t ws_bytes,
+                const void *patch, const int32_t *ids, int B, int P, int T,
+                float *h_last, float *value, void *stream);
+
+/* Decode A action tokens per environment after vla_prefill on the same kv with the same B
+ * (section III-C generation; token factorisation of section IV-C.1).
+ *   mode VLA_MODE_AR: token 1 is read from h_last; for j = 1..A-1 token id vocab-256+bin_j is
+ *     embedded at position S+j-1 and run through the decoder against the cache (its K, V are
+ *     appended); token j+1 is read from that row.  The sampled bin feeds the next forward on
+ *     the device.  The last token is not fed back.
+ *   mode VLA_MODE_PARALLEL_CHUNK: one forward over A slot rows with inputs slot_embed[s] at
+ *     positions S+s; slot rows attend to all S prefix rows and all A slot rows; slot s is read
+ *     from its own row.  h_last is ignored.
+ *   For every token: y = z / temperature over the 256 bins, bin = argmax_k (y_k + gumbel_k)
+ *   (lowest k wins ties; gumbel NULL = greedy), logp = y_bin - logsumexp(y),
+ *   entropy = -sum_k p_k log p_k (nats).
+ *   h_last     DEVICE fp32 [B, hidden] from vla_prefill    S   prefix length P+T of that prefill
+ *   slot_embed DEVICE dtype [A, hidden] (mode 1) or NULL   temperature > 0
+ *   gumbel     DEVICE fp32 [B, A, 256] or NULL
+ *   bins       DEVICE int32 [B, A] out                     logp, entropy DEVICE fp32 [B, A] out
+ *   logits     DEVICE fp32 [B, A, 256] out or NULL: untempered z, for parity checks
+ * Requires A >= 1 and S + A - 1 <= max_seq (mode 0), S + A <= max_seq (mode 1). */
+int vla_decode_actions(vla_model *model, void *kv, void *ws, size_t ws_bytes,
+                       const float *h_last, int B, int S, int A, int mode,
+                       const void *slot_embed, float temperature, const float *gumbel,
+                       int32_t *bins, float *logp, float *entropy, float *logits, void *stream);
+
+/* Log-probability recompute for the policy update (appendix I-B: rho needs log pi_theta of
+ * the stored actions under the current weights).  Teacher-forced forward over N stored
+ * rollouts without a persistent KV cache.
+ *   mode VLA_MODE_AR: rows = prefix, then the stored tokens 1..A-1 (S + A - 1 rows, causal);
+ *     token j is read from row S + j - 2 (1-based j).
+ *   mode VLA_MODE_PARALLEL_CHUNK: rows = prefix, then the A slot inputs; prefix rows causal,
+ *     slot rows see all rows.
+ *   bins   DEVICE int32 [N, A], each in [0, 256): the stored actions
+ *   logp   DEVICE fp32 [N, A] out: log-prob of the stored bin at the given temperature
+ *   entropy DEVICE fp32 [N, A] out      value DEVICE fp32 [N] out or NULL (last prefix row)
+ *   logits DEVICE fp32 [N, A, 256] out or NULL
+ * N may exceed max_batch: rollouts are processed in internal micro-batches and the result does
+ * not depend on the split. */
+int vla_logprob_recompute(vla_model *model, void *ws, size_t ws_bytes,
+                          const void *patch, const int32_t *ids, const int32_t *bins,
+                          int N, int P, int T, int A, int mode, const void *slot_embed,
+                          float temperature, float *logp, float *entropy, float *value,
+                          float *logits, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VLA_H */

@@ -1,0 +1,175 @@
+"""ctypes binding of libvla.so: the same entry points as include/vla.h, argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch appears here solely as the owner
+of device memory (``tensor.data_ptr()``) and of the stream the work is enqueued on.  If the library
+has not been built this module raises on first use -- there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libvla.so")
+
+VLA_OK, VLA_EINVAL, VLA_ESHAPE, VLA_EWORKSPACE, VLA_EDTYPE, VLA_EHIP = 0, -1, -2, -3, -4, -5
+VLA_DTYPE_F32, VLA_DTYPE_BF16 = 0, 1
+VLA_MODE_AR, VLA_MODE_PARALLEL_CHUNK = 0, 1
+VLA_ENTRY_PREFILL, VLA_ENTRY_DECODE, VLA_ENTRY_RECOMPUTE = 0, 1, 2
+VLA_N_BINS = 256
+
+
+class vla_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32),
+                ("ffn", C.c_int32), ("vocab", C.c_int32), ("n_bins", C.c_int32),
+                ("dtype", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float),
+                ("max_batch", C.c_int32), ("max_seq", C.c_int32)]
+
+
+class vla_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm",
+                                          "w_gate", "w_up", "w_down")]
+
+
+class vla_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("value_w", C.c_void_p), ("value_b", C.c_float),
+                ("layers", C.POINTER(vla_layer_weights))]
+
+
+class VlaError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libvla error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libvla.so (built in-tree by ``paper_2510_06710_amd.build``); fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(f"{_LIB_PATH} is not built; run `python -m paper_2510_06710_amd.build`")
+        L = C.CDLL(_LIB_PATH)
+        vp, i32, f32, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
+        L.vla_version.restype = C.c_int
+        L.vla_last_error.restype = C.c_char_p
+        L.vla_create.argtypes = [C.POINTER(vla_config), C.POINTER(vla_weights), C.POINTER(vp)]
+        L.vla_destroy.argtypes = [vp]
+        L.vla_kv_bytes.argtypes = [C.POINTER(vla_config), i32, i32]
+        L.vla_kv_bytes.restype = sz
+        L.vla_workspace_bytes.argtypes = [C.POINTER(vla_config), i32, i32, i32, i32]
+        L.vla_workspace_bytes.restype = sz
+        L.vla_prefill.argtypes = [vp, vp, vp, sz, vp, vp, i32, i32, i32, vp, vp, vp]
+        L.vla_decode_actions.argtypes = [vp, vp, vp, sz, vp, i32, i32, i32, i32, vp, f32, vp, vp, vp, vp, vp, vp]
+        L.vla_logprob_recompute.argtypes = [vp, vp, sz, vp, vp, vp, i32, i32, i32, i32, i32, vp, f32,
+                                            vp, vp, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def vla_last_error() -> str:
+    return lib().vla_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != VLA_OK:
+        raise VlaError(rc, vla_last_error())
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) address of a tensor, None for None."""
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def vla_version() -> int:
+    return lib().vla_version()
+
+
+def vla_kv_bytes(cfg: vla_config, B: int, max_pos: int) -> int:
+    n = lib().vla_kv_bytes(C.byref(cfg), B, max_pos)
+    if n == 0:
+        raise VlaError(VLA_EINVAL, vla_last_error())
+    return n
+
+
+def vla_workspace_bytes(cfg: vla_config, entry: int, B: int, S: int, A: int) -> int:
+    n = lib().vla_workspace_bytes(C.byref(cfg), entry, B, S, A)
+    if n == 0:
+        raise VlaError(VLA_EINVAL, vla_last_error())
+    return n
+
+
+def vla_create(cfg: vla_config, weights: vla_weights) -> int:
+    out = C.c_void_p()
+    _check(lib().vla_create(C.byref(cfg), C.byref(weights), C.byref(out)))
+    return out.value
+
+
+def vla_destroy(model: int) -> None:
+    _check(lib().vla_destroy(model))
+
+
+def vla_prefill(model, kv, ws, patch, ids, B, P, T, h_last, value=None, stream=None) -> None:
+    _check(lib().vla_prefill(model, _ptr(kv), _ptr(ws), ws.numel() * ws.element_size(), _ptr(patch),
+                             _ptr(ids), B, P, T, _ptr(h_last), _ptr(value), _stream(stream)))
+
+
+def vla_decode_actions(model, kv, ws, h_last, B, S, A, mode, slot_embed, temperature, gumbel, bins,
+                       logp, entropy, logits=None, stream=None) -> None:
+    _check(lib().vla_decode_actions(model, _ptr(kv), _ptr(ws), ws.numel() * ws.element_size(),
+                                    _ptr(h_last), B, S, A, mode, _ptr(slot_embed), temperature,
+                                    _ptr(gumbel), _ptr(bins), _ptr(logp), _ptr(entropy), _ptr(logits),
+                                    _stream(stream)))
+
+
+def vla_logprob_recompute(model, ws, patch, ids, bins, N, P, T, A, mode, slot_embed, temperature,
+                          logp, entropy, value=None, logits=None, stream=None) -> None:
+    _check(lib().vla_logprob_recompute(model, _ptr(ws), ws.numel() * ws.element_size(), _ptr(patch),
+                                       _ptr(ids), _ptr(bins), N, P, T, A, mode, _ptr(slot_embed),
+                                       temperature, _ptr(logp), _ptr(entropy), _ptr(value),
+                                       _ptr(logits), _stream(stream)))
+
+
+def make_config(shape, max_batch: int, max_seq: int) -> vla_config:
+    """``shape`` is any object with the decoder fields (n_layers, hidden, ..., dtype "f32"/"bf16")."""
+    return vla_config(shape.n_layers, shape.hidden, shape.n_heads, shape.ffn, shape.vocab, shape.n_bins,
+                      VLA_DTYPE_F32 if shape.dtype == "f32" else VLA_DTYPE_BF16, shape.rms_eps,
+                      shape.rope_theta, max_batch, max_seq)
+
+
+class DeviceModel:
+    """Keeps device weight tensors alive and owns the library's model handle.  ``layers`` is a list
+    of dicts of device tensors with the nine per-layer names of ``vla_layer_weights``."""
+
+    def __init__(self, cfg: vla_config, embed, lm_head, final_norm, layers, value_w=None, value_b=0.0):
+        self.cfg = cfg
+        self._keep = (embed, lm_head, final_norm, layers, value_w)
+        arr = (vla_layer_weights * len(layers))()
+        for a, d in zip(arr, layers):
+            for name, _ in vla_layer_weights._fields_:
+                setattr(a, name, d[name].data_ptr())
+        self._layers = arr
+        w = vla_weights(embed.data_ptr(), lm_head.data_ptr(), final_norm.data_ptr(), _ptr(value_w),
+                        float(value_b), arr)
+        self.handle = vla_create(cfg, w)
+
+    def close(self):
+        if self.handle:
+            vla_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

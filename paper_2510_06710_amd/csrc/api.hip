@@ -1,0 +1,390 @@
+// C-ABI entry points of libvla: argument validation, workspace planning and the host-side
+// sequencing of kernels.  All arithmetic lives in the kernels; this file only enqueues them.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "vla_internal.h"
+
+// ------------------------------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+
+void vla_set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int vla_check_launch(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        vla_set_error("launch of %s failed: %s", what, hipGetErrorString(e));
+        return VLA_EHIP;
+    }
+    return 0;
+}
+
+struct vla_model {
+    vla_config cfg;
+    vla_weights w;
+    std::vector<vla_layer_weights> layers;
+};
+
+// ------------------------------------------------------------------------------------------ config
+static int check_config(const vla_config *c) {
+    if (!c) { vla_set_error("config is NULL"); return VLA_EINVAL; }
+    if (c->dtype != VLA_DTYPE_F32 && c->dtype != VLA_DTYPE_BF16) {
+        vla_set_error("unknown dtype %d", c->dtype);
+        return VLA_EDTYPE;
+    }
+    if (c->n_layers <= 0 || c->hidden <= 0 || c->n_heads <= 0 || c->ffn <= 0 || c->vocab <= 0 ||
+        c->max_batch <= 0 || c->max_seq <= 0 || !(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) {
+        vla_set_error("config has a non-positive size, eps or theta");
+        return VLA_EINVAL;
+    }
+    if (c->n_bins != VLA_N_BINS) { vla_set_error("n_bins = %d unsupported (must be 256)", c->n_bins); return VLA_ESHAPE; }
+    if (c->vocab < VLA_N_BINS) { vla_set_error("vocab %d smaller than the 256 action bins", c->vocab); return VLA_ESHAPE; }
+    if (c->hidden % c->n_heads != 0) { vla_set_error("hidden %d not divisible by n_heads %d", c->hidden, c->n_heads); return VLA_ESHAPE; }
+    int d = c->hidden / c->n_heads;
+    if (d % 16 != 0 || d > 256) { vla_set_error("head_dim %d unsupported (multiple of 16, at most 256)", d); return VLA_ESHAPE; }
+    if (c->max_seq > 8192) { vla_set_error("max_seq %d unsupported (at most 8192)", c->max_seq); return VLA_ESHAPE; }
+    if (c->hidden > 8192) { vla_set_error("hidden %d unsupported (at most 8192)", c->hidden); return VLA_ESHAPE; }
+    return VLA_OK;
+}
+
+static inline size_t elt_size(const vla_config &c) { return c.dtype == VLA_DTYPE_F32 ? 4 : 2; }
+static inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+static size_t kv_layer_elems(const vla_config &c, int n_seq) {
+    return (size_t)n_seq * c.hidden * c.max_seq;
+}
+
+// ------------------------------------------------------------------------------------------ workspace
+struct Workspace {
+    float *X;        // residual stream fp32 [M, H]
+    void *Nrm;       // norm output, storage dtype [M, H]
+    void *QKV;       // [M, 3H]
+    void *AO;        // attention output [M, H]
+    void *ACT;       // SwiGLU output [M, F]
+    float2 *rope;    // [R, d/2]
+    float *Hb;       // final-norm rows fp32 [head_rows, H]
+    void *kvs_k, *kvs_v;   // one-layer KV scratch (recompute)
+    void *vt;        // scratch of the MFMA prefill attention
+    size_t total;
+};
+
+// Lays the workspace out from `base` (may be NULL to only size it).
+static Workspace plan_workspace(const vla_config &c, char *base, int n_seq, int R, int n_keys,
+                                int head_rows, bool kv_scratch) {
+    Workspace w;
+    size_t off = 0, es = elt_size(c);
+    size_t M = (size_t)n_seq * R, H = c.hidden, F = c.ffn;
+    auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += align_up(bytes); return (void *)p; };
+    w.X = (float *)take(M * H * 4);
+    w.Nrm = take(M * H * es);
+    w.QKV = take(M * 3 * H * es);
+    w.AO = take(M * H * es);
+    w.ACT = take(M * F * es);
+    w.rope = (float2 *)take((size_t)R * (H / c.n_heads / 2) * sizeof(float2));
+    w.Hb = (float *)take((size_t)head_rows * H * 4);
+    w.kvs_k = kv_scratch ? take(kv_layer_elems(c, n_seq) * es) : nullptr;
+    w.kvs_v = kv_scratch ? take(kv_layer_elems(c, n_seq) * es) : nullptr;
+    size_t vtb = (c.dtype == VLA_DTYPE_BF16 && R > 1)
+                     ? attention_prefill_scratch_bytes(n_seq, c.n_heads, c.hidden / c.n_heads, n_keys) : 0;
+    w.vt = vtb ? take(vtb) : nullptr;
+    w.total = off;
+    return w;
+}
+
+static int recompute_micro_batch(const vla_config &c, int N) { return N < c.max_batch ? N : c.max_batch; }
+
+// ------------------------------------------------------------------------------------------ forward
+template <typename T>
+static int run_gemm(const vla_config &c, GemmArgs g, hipStream_t st) {
+    if (c.dtype == VLA_DTYPE_BF16) {
+        int r = try_gemm_bf16_mfma(g, st);
+        if (r != 0) return r < 0 ? r : 0;
+    }
+    return launch_gemm_generic<T>(g, st);
+}
+
+// All decoder layers over n_seq x R new rows held in ws.X; K, V of the new rows go to `kv`
+// (layer l of it, or layer 0 when `kv` is a one-layer scratch).
+template <typename T>
+static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &ra, const KvView &kv,
+                      bool kv_single_layer, hipStream_t st) {
+    const vla_config &c = m->cfg;
+    int H = c.hidden, F = c.ffn, M = ra.n_seq * ra.R, d = H / c.n_heads, rc;
+    if ((rc = launch_rope_table(ws.rope, ra.R, ra.pos0, d, c.rope_theta, st))) return rc;
+    for (int l = 0; l < c.n_layers; l++) {
+        const vla_layer_weights &lw = m->layers[l];
+        int kl = kv_single_layer ? 0 : l;
+        if ((rc = launch_rmsnorm<T>((T *)ws.Nrm, ws.X, (const float *)lw.attn_norm, M, H, c.rms_eps, st))) return rc;
+        GemmArgs g{};
+        g.A = ws.Nrm; g.W[0] = lw.wq; g.W[1] = lw.wk; g.W[2] = lw.wv; g.n_seg = 3; g.segN = H;
+        g.C = ws.QKV; g.M = M; g.K = H; g.epilogue = EPI_STORE;
+        if ((rc = run_gemm<T>(c, g, st))) return rc;
+        if ((rc = launch_rope_kv_write<T>((T *)ws.QKV, ws.rope, kv, kl, ra, H, st))) return rc;
+        int done = 0;
+        if (c.dtype == VLA_DTYPE_BF16) {
+            done = (ra.R == 1)
+                       ? try_attention_decode_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.QKV, kv, kl, ra, H, st)
+                       : try_attention_prefill_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.QKV, kv, kl, ra, H, ws.vt, st);
+            if (done < 0) return done;
+        }
+        if (!done && (rc = launch_attention_generic<T>((T *)ws.AO, (const T *)ws.QKV, kv, kl, ra, H, st))) return rc;
+        g = GemmArgs{};
+        g.A = ws.AO; g.W[0] = lw.wo; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = H; g.epilogue = EPI_RESIDUAL;
+        if ((rc = run_gemm<T>(c, g, st))) return rc;
+        if ((rc = launch_rmsnorm<T>((T *)ws.Nrm, ws.X, (const float *)lw.ffn_norm, M, H, c.rms_eps, st))) return rc;
+        g = GemmArgs{};
+        g.A = ws.Nrm; g.W[0] = lw.w_gate; g.W[1] = lw.w_up; g.n_seg = 2; g.segN = F; g.C = ws.ACT; g.M = M; g.K = H;
+        g.epilogue = EPI_SWIGLU;
+        if ((rc = run_gemm<T>(c, g, st))) return rc;
+        g = GemmArgs{};
+        g.A = ws.ACT; g.W[0] = lw.w_down; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = F; g.epilogue = EPI_RESIDUAL;
+        if ((rc = run_gemm<T>(c, g, st))) return rc;
+    }
+    return 0;
+}
+
+static KvView kv_view(const vla_config &c, void *kv, int n_seq, int n_layers) {
+    KvView v;
+    v.layer_elems = kv_layer_elems(c, n_seq);
+    v.k = kv;
+    v.v = (char *)kv + (size_t)n_layers * v.layer_elems * elt_size(c);
+    v.n_seq = n_seq; v.n_heads = c.n_heads; v.d = c.hidden / c.n_heads; v.pos_stride = c.max_seq;
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------ entry bodies
+template <typename T>
+static int prefill_impl(vla_model *m, void *kvbuf, void *wsbuf, const void *patch, const int32_t *ids, int B,
+                        int P, int T_, float *h_last, float *value, hipStream_t st) {
+    const vla_config &c = m->cfg;
+    int S = P + T_, H = c.hidden, rc;
+    Workspace ws = plan_workspace(c, (char *)wsbuf, B, S, S, 0, false);
+    if ((rc = launch_embed_prefix<T>(ws.X, (const T *)patch, ids, (const T *)m->w.embed, B, P, T_, S, H, c.vocab, st))) return rc;
+    RowsArgs ra{B, S, 0, 0x7fffffff};
+    KvView kv = kv_view(c, kvbuf, B, c.n_layers);
+    if ((rc = run_layers<T>(m, ws, ra, kv, false, st))) return rc;
+    if ((rc = launch_final_norm_rows(h_last, ws.X, (const float *)m->w.final_norm, B, S, S - 1, 1, H, c.rms_eps, st))) return rc;
+    if (value && (rc = launch_value_head(value, h_last, (const float *)m->w.value_w, m->w.value_b, B, H, H, st))) return rc;
+    return 0;
+}
+
+template <typename T>
+static int decode_impl(vla_model *m, void *kvbuf, void *wsbuf, const float *h_last, int B, int S, int A, int mode,
+                       const void *slot_embed, float temperature, const float *gumbel, int32_t *bins, float *logp,
+                       float *entropy, float *logits, hipStream_t st) {
+    const vla_config &c = m->cfg;
+    int H = c.hidden, rc;
+    const T *head = (const T *)m->w.lm_head + (size_t)(c.vocab - VLA_N_BINS) * H;
+    KvView kv = kv_view(c, kvbuf, B, c.n_layers);
+    if (mode == VLA_MODE_AR) {
+        Workspace ws = plan_workspace(c, (char *)wsbuf, B, 1, S + A, B, false);
+        const float *h = h_last;
+        for (int j = 0; j < A; j++) {
+            bool more = j + 1 < A;
+            if ((rc = launch_head_sample<T>(h, head, B, H, temperature, gumbel, nullptr, bins, logp, entropy, logits, A, j,
+                                            more ? ws.X : nullptr, (const T *)m->w.embed, c.vocab, st))) return rc;
+            if (!more) break;
+            RowsArgs ra{B, 1, S + j, 0x7fffffff};
+            if ((rc = run_layers<T>(m, ws, ra, kv, false, st))) return rc;
+            if ((rc = launch_final_norm_rows(ws.Hb, ws.X, (const float *)m->w.final_norm, B, 1, 0, 1, H, c.rms_eps, st))) return rc;
+            h = ws.Hb;
+        }
+    } else {
+        Workspace ws = plan_workspace(c, (char *)wsbuf, B, A, S + A, B * A, false);
+        if ((rc = launch_embed_slots<T>(ws.X, (const T *)slot_embed, B, A, A, 0, H, st))) return rc;
+        RowsArgs ra{B, A, S, S};
+        if ((rc = run_layers<T>(m, ws, ra, kv, false, st))) return rc;
+        if ((rc = launch_final_norm_rows(ws.Hb, ws.X, (const float *)m->w.final_norm, B, A, 0, A, H, c.rms_eps, st))) return rc;
+        if ((rc = launch_head_sample<T>(ws.Hb, head, B * A, H, temperature, gumbel, nullptr, bins, logp, entropy, logits, 1, 0,
+                                        nullptr, (const T *)nullptr, c.vocab, st))) return rc;
+    }
+    return 0;
+}
+
+template <typename T>
+static int recompute_impl(vla_model *m, void *wsbuf, const void *patch, const int32_t *ids, const int32_t *bins, int N,
+                          int P, int T_, int A, int mode, const void *slot_embed, float temperature, float *logp,
+                          float *entropy, float *value, float *logits, hipStream_t st) {
+    const vla_config &c = m->cfg;
+    int S = P + T_, H = c.hidden, rc;
+    int R = (mode == VLA_MODE_AR) ? S + A - 1 : S + A;
+    int first = (mode == VLA_MODE_AR) ? S - 1 : S;          // row that predicts action token 1
+    int mb = recompute_micro_batch(c, N);
+    const T *head = (const T *)m->w.lm_head + (size_t)(c.vocab - VLA_N_BINS) * H;
+    Workspace ws = plan_workspace(c, (char *)wsbuf, mb, R, R, mb * (A + 1), true);
+    for (int n0 = 0; n0 < N; n0 += mb) {
+        int n = (N - n0 < mb) ? N - n0 : mb;
+        const T *pp = (const T *)patch + (size_t)n0 * P * H;
+        if ((rc = launch_embed_prefix<T>(ws.X, pp, ids + (size_t)n0 * T_, (const T *)m->w.embed, n, P, T_, R, H, c.vocab, st))) return rc;
+        if (mode == VLA_MODE_AR) {
+            if ((rc = launch_embed_tokens<T>(ws.X, bins + (size_t)n0 * A, A, A - 1, (const T *)m->w.embed, n, R, S, H, c.vocab, st))) return rc;
+        } else {
+            if ((rc = launch_embed_slots<T>(ws.X, (const T *)slot_embed, n, A, R, S, H, st))) return rc;
+        }
+        RowsArgs ra{n, R, 0, (mode == VLA_MODE_AR) ? 0x7fffffff : S};
+        KvView kv;
+        kv.layer_elems = kv_layer_elems(c, mb);
+        kv.k = ws.kvs_k; kv.v = ws.kvs_v; kv.n_seq = n; kv.n_heads = c.n_heads; kv.d = H / c.n_heads; kv.pos_stride = c.max_seq;
+        if ((rc = run_layers<T>(m, ws, ra, kv, true, st))) return rc;
+        if ((rc = launch_final_norm_rows(ws.Hb, ws.X, (const float *)m->w.final_norm, n, R, first, A, H, c.rms_eps, st))) return rc;
+        size_t o = (size_t)n0 * A;
+        if ((rc = launch_head_sample<T>(ws.Hb, head, n * A, H, temperature, nullptr, bins + o, nullptr, logp + o, entropy + o,
+                                        logits ? logits + o * VLA_N_BINS : nullptr, 1, 0, nullptr, (const T *)nullptr, c.vocab, st))) return rc;
+        if (value) {
+            float *hv = ws.Hb + (size_t)mb * A * H;
+            if ((rc = launch_final_norm_rows(hv, ws.X, (const float *)m->w.final_norm, n, R, S - 1, 1, H, c.rms_eps, st))) return rc;
+            if ((rc = launch_value_head(value + n0, hv, (const float *)m->w.value_w, m->w.value_b, n, H, H, st))) return rc;
+        }
+    }
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------ C ABI
+extern "C" {
+
+int vla_version(void) { return VLA_VERSION; }
+
+const char *vla_last_error(void) { return g_err; }
+
+int vla_create(const vla_config *cfg, const vla_weights *w, vla_model **out) {
+    if (!out) { vla_set_error("out is NULL"); return VLA_EINVAL; }
+    *out = nullptr;
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!w || !w->embed || !w->lm_head || !w->final_norm || !w->layers) {
+        vla_set_error("weights, embed, lm_head, final_norm or layers is NULL");
+        return VLA_EINVAL;
+    }
+    for (int l = 0; l < cfg->n_layers; l++) {
+        const vla_layer_weights &lw = w->layers[l];
+        if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.ffn_norm || !lw.w_gate || !lw.w_up || !lw.w_down) {
+            vla_set_error("layer %d has a NULL weight pointer", l);
+            return VLA_EINVAL;
+        }
+    }
+    vla_model *m = new (std::nothrow) vla_model;
+    if (!m) { vla_set_error("out of host memory"); return VLA_EINVAL; }
+    m->cfg = *cfg;
+    m->w = *w;
+    m->layers.assign(w->layers, w->layers + cfg->n_layers);
+    m->w.layers = m->layers.data();
+    *out = m;
+    return VLA_OK;
+}
+
+int vla_destroy(vla_model *m) {
+    if (!m) { vla_set_error("model is NULL"); return VLA_EINVAL; }
+    delete m;
+    return VLA_OK;
+}
+
+size_t vla_kv_bytes(const vla_config *cfg, int B, int max_pos) {
+    if (check_config(cfg)) return 0;
+    if (B <= 0 || max_pos <= 0) { vla_set_error("B and max_pos must be positive"); return 0; }
+    if (B > cfg->max_batch || max_pos > cfg->max_seq) {
+        vla_set_error("B %d / max_pos %d exceed capacity %d / %d", B, max_pos, cfg->max_batch, cfg->max_seq);
+        return 0;
+    }
+    return 2 * (size_t)cfg->n_layers * kv_layer_elems(*cfg, B) * elt_size(*cfg);
+}
+
+size_t vla_workspace_bytes(const vla_config *cfg, int entry, int B, int S, int A) {
+    if (check_config(cfg)) return 0;
+    if (B <= 0 || S <= 0 || A < 0) { vla_set_error("B, S must be positive and A non-negative"); return 0; }
+    int a = A > 0 ? A : 1;
+    switch (entry) {
+        case VLA_ENTRY_PREFILL:
+            if (B > cfg->max_batch || S > cfg->max_seq) { vla_set_error("B or S exceeds capacity"); return 0; }
+            return plan_workspace(*cfg, nullptr, B, S, S, 0, false).total;
+        case VLA_ENTRY_DECODE: {
+            if (B > cfg->max_batch || S + a > cfg->max_seq + 1) { vla_set_error("B or S + A exceeds capacity"); return 0; }
+            size_t ar = plan_workspace(*cfg, nullptr, B, 1, S + a, B, false).total;
+            size_t ch = (S + a <= cfg->max_seq) ? plan_workspace(*cfg, nullptr, B, a, S + a, B * a, false).total : 0;
+            return ar > ch ? ar : ch;
+        }
+        case VLA_ENTRY_RECOMPUTE: {
+            if (S + a > cfg->max_seq + 1) { vla_set_error("S + A exceeds capacity"); return 0; }
+            int mb = recompute_micro_batch(*cfg, B);
+            int R = (S + a <= cfg->max_seq) ? S + a : S + a - 1;
+            return plan_workspace(*cfg, nullptr, mb, R, R, mb * (a + 1), true).total;
+        }
+        default:
+            vla_set_error("unknown entry %d", entry);
+            return 0;
+    }
+}
+
+int vla_prefill(vla_model *m, void *kv, void *ws, size_t ws_bytes, const void *patch, const int32_t *ids, int B, int P,
+                int T, float *h_last, float *value, void *stream) {
+    if (!m || !kv || !ws || !h_last) { vla_set_error("model, kv, ws or h_last is NULL"); return VLA_EINVAL; }
+    if (B <= 0 || P < 0 || T < 0 || P + T < 1) { vla_set_error("need B >= 1, P, T >= 0, P + T >= 1"); return VLA_EINVAL; }
+    if ((P > 0 && !patch) || (T > 0 && !ids)) { vla_set_error("patch / ids is NULL"); return VLA_EINVAL; }
+    if (value && !m->w.value_w) { vla_set_error("value requested but the model has no value head"); return VLA_EINVAL; }
+    const vla_config &c = m->cfg;
+    if (B > c.max_batch || P + T > c.max_seq) {
+        vla_set_error("B %d / S %d exceed capacity %d / %d", B, P + T, c.max_batch, c.max_seq);
+        return VLA_ESHAPE;
+    }
+    size_t need = plan_workspace(c, nullptr, B, P + T, P + T, 0, false).total;
+    if (ws_bytes < need) { vla_set_error("workspace %zu bytes, need %zu", ws_bytes, need); return VLA_EWORKSPACE; }
+    hipStream_t st = (hipStream_t)stream;
+    return c.dtype == VLA_DTYPE_F32 ? prefill_impl<float>(m, kv, ws, patch, ids, B, P, T, h_last, value, st)
+                                    : prefill_impl<bf16_t>(m, kv, ws, patch, ids, B, P, T, h_last, value, st);
+}
+
+int vla_decode_actions(vla_model *m, void *kv, void *ws, size_t ws_bytes, const float *h_last, int B, int S, int A,
+                       int mode, const void *slot_embed, float temperature, const float *gumbel, int32_t *bins,
+                       float *logp, float *entropy, float *logits, void *stream) {
+    if (!m || !kv || !ws || !bins || !logp || !entropy) { vla_set_error("model, kv, ws, bins, logp or entropy is NULL"); return VLA_EINVAL; }
+    if (mode != VLA_MODE_AR && mode != VLA_MODE_PARALLEL_CHUNK) { vla_set_error("unknown mode %d", mode); return VLA_EINVAL; }
+    if (B <= 0 || S <= 0 || A <= 0) { vla_set_error("B, S, A must be positive"); return VLA_EINVAL; }
+    if (!(temperature > 0.f)) { vla_set_error("temperature must be positive"); return VLA_EINVAL; }
+    if (mode == VLA_MODE_AR && !h_last) { vla_set_error("h_last is NULL"); return VLA_EINVAL; }
+    if (mode == VLA_MODE_PARALLEL_CHUNK && !slot_embed) { vla_set_error("slot_embed is NULL"); return VLA_EINVAL; }
+    const vla_config &c = m->cfg;
+    int rows = (mode == VLA_MODE_AR) ? S + A - 1 : S + A;
+    if (B > c.max_batch || rows > c.max_seq) {
+        vla_set_error("B %d / positions %d exceed capacity %d / %d", B, rows, c.max_batch, c.max_seq);
+        return VLA_ESHAPE;
+    }
+    size_t need = (mode == VLA_MODE_AR) ? plan_workspace(c, nullptr, B, 1, S + A, B, false).total
+                                        : plan_workspace(c, nullptr, B, A, S + A, B * A, false).total;
+    if (ws_bytes < need) { vla_set_error("workspace %zu bytes, need %zu", ws_bytes, need); return VLA_EWORKSPACE; }
+    hipStream_t st = (hipStream_t)stream;
+    return c.dtype == VLA_DTYPE_F32
+               ? decode_impl<float>(m, kv, ws, h_last, B, S, A, mode, slot_embed, temperature, gumbel, bins, logp, entropy, logits, st)
+               : decode_impl<bf16_t>(m, kv, ws, h_last, B, S, A, mode, slot_embed, temperature, gumbel, bins, logp, entropy, logits, st);
+}
+
+int vla_logprob_recompute(vla_model *m, void *ws, size_t ws_bytes, const void *patch, const int32_t *ids,
+                          const int32_t *bins, int N, int P, int T, int A, int mode, const void *slot_embed,
+                          float temperature, float *logp, float *entropy, float *value, float *logits, void *stream) {
+    if (!m || !ws || !bins || !logp || !entropy) { vla_set_error("model, ws, bins, logp or entropy is NULL"); return VLA_EINVAL; }
+    if (mode != VLA_MODE_AR && mode != VLA_MODE_PARALLEL_CHUNK) { vla_set_error("unknown mode %d", mode); return VLA_EINVAL; }
+    if (N <= 0 || P < 0 || T < 0 || P + T < 1 || A <= 0) { vla_set_error("need N, A >= 1, P, T >= 0, P + T >= 1"); return VLA_EINVAL; }
+    if ((P > 0 && !patch) || (T > 0 && !ids)) { vla_set_error("patch / ids is NULL"); return VLA_EINVAL; }
+    if (!(temperature > 0.f)) { vla_set_error("temperature must be positive"); return VLA_EINVAL; }
+    if (mode == VLA_MODE_PARALLEL_CHUNK && !slot_embed) { vla_set_error("slot_embed is NULL"); return VLA_EINVAL; }
+    if (value && !m->w.value_w) { vla_set_error("value requested but the model has no value head"); return VLA_EINVAL; }
+    const vla_config &c = m->cfg;
+    int S = P + T, R = (mode == VLA_MODE_AR) ? S + A - 1 : S + A;
+    if (R > c.max_seq) { vla_set_error("rows per rollout %d exceed max_seq %d", R, c.max_seq); return VLA_ESHAPE; }
+    int mb = recompute_micro_batch(c, N);
+    size_t need = plan_workspace(c, nullptr, mb, R, R, mb * (A + 1), true).total;
+    if (ws_bytes < need) { vla_set_error("workspace %zu bytes, need %zu", ws_bytes, need); return VLA_EWORKSPACE; }
+    hipStream_t st = (hipStream_t)stream;
+    return c.dtype == VLA_DTYPE_F32
+               ? recompute_impl<float>(m, ws, patch, ids, bins, N, P, T, A, mode, slot_embed, temperature, logp, entropy, value, logits, st)
+               : recompute_impl<bf16_t>(m, ws, patch, ids, bins, N, P, T, A, mode, slot_embed, temperature, logp, entropy, value, logits, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+// Internal declarations shared by the translation units of libvla (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/vla.h"
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+#define VLA_WAVE 64
+
+// ------------------------------------------------------------------------------------------
+// KV buffer view.  One layer of K is [n_seq][n_heads][d/8][pos_stride][8] (eight consecutive
+// head dims of one position are contiguous: the 16-byte unit both the streaming decode kernel
+// and the MFMA operand loads want); one layer of V is [n_seq][n_heads][pos_stride][d].
+// ------------------------------------------------------------------------------------------
+struct KvView {
+    void *k, *v;            // base of layer 0
+    size_t layer_elems;     // elements per layer (same for K and V)
+    int n_seq, n_heads, d, pos_stride;
+};
+
+struct RowsArgs {           // one forward over n_seq sequences x R new rows each
+    int n_seq, R, pos0;     // row r of a sequence sits at absolute position pos0 + r
+    int full_from;          // rows at positions >= full_from attend to all pos0 + R keys,
+                            // rows below attend causally (keys 0..position)
+};
+
+enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+
+struct GemmArgs {
+    const void *A;          // [M, K] row-major (lda = K), storage dtype (or fp32 for fp32 models)
+    const void *W[3];       // up to three weight segments, each [segN, K] row-major
+    int n_seg, segN;        // N = n_seg * segN (EPI_SWIGLU: W[0] = gate, W[1] = up, N = segN)
+    void *C;                // EPI_STORE / EPI_SWIGLU: storage dtype [M, N]; EPI_RESIDUAL: fp32 [M, N] +=
+    int M, K;
+    int epilogue;
+};
+
+// ---- generic (any shape, fp32 or bf16 storage) kernels: kernels_generic.hip -----------------
+template <typename T>
+int launch_embed_prefix(float *X, const T *patch, const int32_t *ids, const T *embed, int n_seq, int P,
+                        int T_, int row_stride_rows, int H, int vocab, hipStream_t st);
+template <typename T>
+int launch_embed_tokens(float *X, const int32_t *bins, int bins_stride, int n_tok, const T *embed,
+                        int n_seq, int rows_per_seq, int row0, int H, int vocab, hipStream_t st);
+template <typename T>
+int launch_embed_slots(float *X, const T *slot_embed, int n_seq, int A, int rows_per_seq, int row0,
+                       int H, hipStream_t st);
+template <typename T>
+int launch_rmsnorm(T *out, const float *X, const float *gain, int M, int H, float eps, hipStream_t st);
+int launch_final_norm_rows(float *out, const float *X, const float *gain, int n_seq, int rows_per_seq,
+                           int row0, int n_rows, int H, float eps, hipStream_t st);
+template <typename T>
+int launch_gemm_generic(const GemmArgs &g, hipStream_t st);
+int launch_rope_table(float2 *table, int R, int pos0, int d, float theta, hipStream_t st);
+template <typename T>
+int launch_rope_kv_write(T *qkv, const float2 *table, const KvView &kv, int layer, const RowsArgs &ra,
+                         int H, hipStream_t st);
+template <typename T>
+int launch_attention_generic(T *out, const T *qkv, const KvView &kv, int layer, const RowsArgs &ra,
+                             int H, hipStream_t st);
+// Row i of h produces output index o = i * out_stride + out_off: bins_out[o], logp[o], ent[o],
+// logits[o * 256 ..]; it reads gumbel[o * 256 ..] (if any) and given_bins[o] (if any: then the
+// log-prob is that of the given bin and nothing is sampled).  If X_next is not NULL the embedding
+// of token vocab - 256 + bin is written to X_next[i * H ..] as fp32.
+template <typename T>
+int launch_head_sample(const float *h, const T *lm_head_bins, int n_rows, int H, float temperature,
+                       const float *gumbel, const int32_t *given_bins, int32_t *bins_out, float *logp,
+                       float *ent, float *logits, int out_stride, int out_off, float *X_next,
+                       const T *embed, int vocab, hipStream_t st);
+int launch_value_head(float *value, const float *h, const float *w, float b, int n, int H, int h_stride,
+                      hipStream_t st);
+
+// ---- gfx950 fast paths (bf16, aligned shapes); each returns 1 if it handled the call, 0 if the
+// shape is outside what it supports (caller then uses the generic kernel), <0 on launch error ----
+int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st);
+int try_attention_prefill_bf16(bf16_t *out, const bf16_t *qkv, const KvView &kv, int layer,
+                               const RowsArgs &ra, int H, void *vt_scratch, hipStream_t st);
+int try_attention_decode_bf16(bf16_t *out, const bf16_t *qkv, const KvView &kv, int layer,
+                              const RowsArgs &ra, int H, hipStream_t st);
+size_t attention_prefill_scratch_bytes(int n_seq, int n_heads, int d, int n_keys);
+
+int vla_check_launch(const char *what);
+void vla_set_error(const char *fmt, ...);

@@ -1,0 +1,116 @@
+"""GPU parity: the library (through the C ABI) against the CPU oracle on the same seeded inputs,
+at sizes the oracle finishes in seconds: the tiny fp32 workload, bf16 and ragged variants of it,
+parallel-chunk mode, the recompute entry point and the degenerate cases."""
+import numpy as np
+import pytest
+import torch
+
+import vla_inputs as vi
+from parity import (GpuCase, compare_recompute, compare_rollout, oracle_recompute, oracle_rollout)
+
+pytestmark = pytest.mark.gpu
+
+TINY = vi.WORKLOADS["cfg1_tiny_fp32"]
+RAGGED = vi.Workload("ragged", vi.ModelShape(n_layers=3, hidden=96, n_heads=3, ffn=100, vocab=300, dtype="f32"),
+                     batch=3, n_patches=5, n_instr=3, n_action=4)
+
+
+def _print(name, stats):
+    print(f"\n[parity] {name}: {stats}", flush=True)
+
+
+@pytest.mark.parametrize("sampled", [True, False])
+def test_cfg1_tiny_fp32_rollout(sampled):
+    ref = oracle_rollout(TINY, 0, sampled=sampled)
+    gpu = GpuCase(TINY, 0).rollout(sampled=sampled)
+    assert np.max(np.abs(gpu["h_last"] - ref["h_last"])) < 1e-4
+    st = compare_rollout(gpu, ref, "f32", autoregressive=True)
+    _print(f"cfg1 sampled={sampled}", st)
+    assert st["compared"] >= 8 * 7 - 7 * st["near_ties"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("tau", [1.0, 1.6])
+def test_ragged_shapes_rollout(dtype, tau):
+    wl = vi.scaled(RAGGED, dtype=dtype, temperature=tau)
+    ref = oracle_rollout(wl, 1)
+    gpu = GpuCase(wl, 1).rollout()
+    _print(f"ragged {dtype} tau={tau}", compare_rollout(gpu, ref, dtype, autoregressive=True))
+
+
+def test_tiny_bf16_rollout():
+    wl = vi.scaled(TINY, dtype="bf16")
+    ref = oracle_rollout(wl, 2)
+    gpu = GpuCase(wl, 2).rollout()
+    _print("tiny bf16", compare_rollout(gpu, ref, "bf16", autoregressive=True))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_parallel_chunk_rollout(dtype):
+    wl = vi.scaled(TINY, dtype=dtype, n_action=56, mode=1, batch=4)
+    ref = oracle_rollout(wl, 3)
+    gpu = GpuCase(wl, 3).rollout()
+    _print(f"chunk {dtype}", compare_rollout(gpu, ref, dtype, autoregressive=False))
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_recompute(mode, dtype):
+    wl = vi.scaled(TINY, dtype=dtype, batch=5, mode=mode, kind="recompute", temperature=1.6)
+    bins = vi.stored_bins(wl, 4).numpy()
+    ref = oracle_recompute(wl, 4, bins)
+    case = GpuCase(wl, 4)
+    gpu = case.recompute(bins)
+    _print(f"recompute mode={mode} {dtype}", compare_recompute(gpu, ref, dtype))
+    # micro-batching must not change the result: capacity 2 forces splits 2 + 2 + 1
+    split = GpuCase(wl, 4, max_batch=2).recompute(bins)
+    for k in ("logp", "ent", "value", "logits"):
+        assert np.array_equal(split[k], gpu[k]), k
+
+
+def test_rollout_then_recompute_gives_rho_one_on_gpu():
+    """Importance ratio of appendix I-B with theta = theta_old: exp(logp_new - logp_old) = 1."""
+    case = GpuCase(TINY, 5)
+    out = case.rollout()
+    rc = case.recompute(out["bins"])
+    assert np.max(np.abs(np.exp(rc["logp"] - out["logp"]) - 1.0)) < 1e-4
+    assert np.max(np.abs(rc["logits"] - out["logits"])) < 1e-4
+    assert np.max(np.abs(rc["value"] - out["value"])) < 1e-5
+
+
+@pytest.mark.parametrize("B,P,T,A", [(1, 0, 1, 1), (2, 0, 3, 2), (1, 4, 0, 3), (8, 48, 16, 1)])
+def test_degenerate_sizes(B, P, T, A):
+    wl = vi.scaled(TINY, batch=B, n_patches=P, n_instr=T, n_action=A)
+    ref = oracle_rollout(wl, 6)
+    gpu = GpuCase(wl, 6).rollout()
+    compare_rollout(gpu, ref, "f32", autoregressive=True)
+    if P + T > 0:
+        rc_ref = oracle_recompute(wl, 6, ref["bins"])
+        rc = GpuCase(wl, 6).recompute(ref["bins"])
+        compare_recompute(rc, rc_ref, "f32")
+
+
+def test_capacity_larger_than_problem_and_subset_of_envs():
+    """max_batch / max_seq above the problem size; environments 3..5 only (slices regenerate)."""
+    ref = oracle_rollout(TINY, 7, env0=3, envs=3)
+    gpu = GpuCase(TINY, 7, max_batch=16, max_seq=100).rollout(env0=3, envs=3)
+    compare_rollout(gpu, ref, "f32", autoregressive=True)
+
+
+def test_deterministic_and_no_state_between_calls():
+    case = GpuCase(TINY, 8)
+    a = case.rollout()
+    case.rollout(sampled=False)
+    b = case.rollout()
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
+def test_greedy_matches_argmax_of_returned_logits_and_stats_are_consistent():
+    gpu = GpuCase(TINY, 9).rollout(sampled=False)
+    z = gpu["logits"].astype(np.float64)
+    assert np.array_equal(gpu["bins"], np.argmax(gpu["logits"], -1))
+    lse = np.log(np.exp(z - z.max(-1, keepdims=True)).sum(-1)) + z.max(-1)
+    lp = z - lse[..., None]
+    assert np.max(np.abs(np.take_along_axis(lp, gpu["bins"][..., None].astype(np.int64), -1)[..., 0] - gpu["logp"])) < 1e-5
+    assert np.max(np.abs(-(np.exp(lp) * lp).sum(-1) - gpu["ent"])) < 1e-5

@@ -1,0 +1,58 @@
+"""Writes tests/golden/oracle_7b.npz: oracle outputs for a few sampled environments / rollouts of
+the 7B-shape workloads (all 32 layers).  Calls only vla_inputs and oracle/; takes 10-20 minutes
+on 8 cores and about 20 GB of host memory.  Run from the repository root:
+
+    python tests/golden/make_golden.py
+
+The environments of the cfg2 (64 envs) and cfg3 (256 envs) workloads share their inputs (every
+tensor is indexed by environment), so one set of rollouts serves both."""
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+import vla_inputs as vi  # noqa: E402
+from oracle.from_inputs import oracle_weights  # noqa: E402
+from parity import oracle_recompute, oracle_rollout  # noqa: E402
+
+SEED = 0
+AR_ENVS = [0, 37, 200]          # 0 and 37 are inside cfg2's 64 envs; all three inside cfg3's 256
+OFT_ENVS = [0, 100]             # cfg4: 128 envs
+RC_ROLLOUTS = [0, 300]          # cfg5: 512 stored rollouts
+
+
+def main():
+    t0 = time.time()
+    w = oracle_weights(vi.SynthModel(vi.SHAPE_7B, SEED), vi.VALUE_BIAS)
+    out = {"seed": np.array(SEED)}
+    wl3 = vi.WORKLOADS["cfg3_7b_b256"]
+    for e in AR_ENVS:
+        r = oracle_rollout(wl3, SEED, env0=e, envs=1, weights=w)
+        for k, v in r.items():
+            out[f"ar_{e}_{k}"] = v
+        print(f"AR env {e} done at {time.time() - t0:.0f}s bins={r['bins']}", flush=True)
+    wl4 = vi.WORKLOADS["cfg4_7b_oft_b128"]
+    for e in OFT_ENVS:
+        r = oracle_rollout(wl4, SEED, env0=e, envs=1, sampled=False, weights=w)
+        for k, v in r.items():
+            out[f"oft_{e}_{k}"] = v
+        print(f"OFT env {e} done at {time.time() - t0:.0f}s", flush=True)
+    wl5 = vi.WORKLOADS["cfg5_7b_recompute_n512"]
+    for e in RC_ROLLOUTS:
+        bins = vi.stored_bins(wl5, SEED, env0=e, envs=1).numpy()
+        r = oracle_recompute(wl5, SEED, bins, env0=e, envs=1, weights=w)
+        out[f"rc_{e}_bins"] = bins
+        for k, v in r.items():
+            out[f"rc_{e}_{k}"] = v
+        print(f"recompute rollout {e} done at {time.time() - t0:.0f}s", flush=True)
+    np.savez_compressed(os.path.join(ROOT, "tests", "golden", "oracle_7b.npz"), **out)
+    print("written", flush=True)
+
+
+if __name__ == "__main__":
+    main()

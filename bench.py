@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched VLA rollout step on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic observations: vla_prefill
+(observation prefix -> KV cache) followed by vla_decode_actions (7 autoregressive action tokens with
+Gumbel-max sampling, or the parallel chunk pass), with every input already resident in HBM.
+Prints one JSON line: env-actions/s plus the roofline of the dominant kernel (measured with HIP
+events recorded by the library around each launch, in a separate instrumented pass) and the CPU
+oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3_7b_b256]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MI355X_HBM_GBPS = 8000.0          # published peak HBM3E bandwidth
+MI355X_BF16_TFLOPS = 2500.0       # published dense bf16 MFMA peak
+
+
+def profile_report(vb):
+    buf = ctypes.create_string_buffer(1 << 16)
+    n = vb.lib().vla_profile_report(buf, len(buf))
+    if n < 0:
+        raise RuntimeError(vb.vla_last_error())
+    out = {}
+    for line in buf.value.decode().splitlines():
+        label, count, ms, work = line.rsplit(" ", 3)
+        out[label] = dict(count=int(count), ms=float(ms), work=float(work))
+    return out
+
+
+def read_traffic(path, kernel):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/*.txt, 'key: value')."""
+    try:
+        vals = {}
+        for line in open(path):
+            if ":" in line and not line.startswith("#"):
+                k, v = line.split(":", 1)
+                vals[k.strip()] = v.strip()
+        if vals.get("kernel") != kernel:
+            return None
+        return float(vals["hbm_bytes_per_launch"])
+    except Exception:
+        return None
+
+
+def cpu_baseline(wl, vi, sample_layers=2):
+    """The CPU oracle as it stands, on 1 environment x `sample_layers` of the model's layers
+    (prefill + decode), scaled linearly to all layers; the head and embedding cost is negligible."""
+    import numpy as np
+    import torch
+    from oracle import vla_oracle as vo
+    from oracle.from_inputs import oracle_config, oracle_weights, to_f64
+
+    shape = vi.scaled(wl, n_layers=sample_layers).shape
+    model = vi.SynthModel(shape, 0)
+    cfg = oracle_config(shape)
+    w = oracle_weights(model, vi.VALUE_BIAS)
+    for l in range(sample_layers):
+        w.layer(l)                                   # generate the weights outside the timed region
+    patch, ids = vi.observation(wl, 0, envs=1)
+    g = to_f64(vi.gumbel_noise(wl, 0, envs=1))
+    slot = to_f64(model.slot_embed(wl.n_action)) if wl.mode == 1 else None
+    t0 = time.perf_counter()
+    kv, h_last, _ = vo.ovla_prefill(cfg, w, to_f64(patch), ids.numpy().astype(np.int64))
+    vo.ovla_decode_actions(cfg, w, kv, h_last, wl.prefix, wl.n_action, wl.mode, slot, wl.temperature, g)
+    dt = time.perf_counter() - t0
+    per_env = dt * wl.shape.n_layers / sample_layers
+    return {"value": 1.0 / per_env, "unit": "env-actions/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"1 env x {sample_layers} of {wl.shape.n_layers} layers (prefill {wl.prefix} rows + "
+                      f"{wl.n_action} action tokens), fp64 numpy, {dt:.1f} s measured, scaled by layers"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg3_7b_b256")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (environments shard "
+              "without any exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import vla_inputs as vi
+    from paper_2510_06710_amd import binding as vb
+    from paper_2510_06710_amd.harness import Rollout
+
+    wl = vi.WORKLOADS[args.workload]
+    if wl.kind != "rollout":
+        print("bench.py times rollout workloads (prefill + decode)", file=sys.stderr)
+        sys.exit(2)
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    B, S, A = wl.batch, wl.prefix, wl.n_action
+    synth = vi.SynthModel(wl.shape, 0, device=dev)
+    run = Rollout(synth, B, S + A + 1, device=dev, value_b=vi.VALUE_BIAS)
+    patch, ids = vi.observation(wl, 0, device=dev)
+    gumbel = vi.gumbel_noise(wl, 0, device=dev)
+    slot = synth.slot_embed(A) if wl.mode == 1 else None
+    stream = torch.cuda.current_stream()
+
+    def prefill():
+        return run.prefill(patch, ids, want_value=True, stream=stream)
+
+    def decode(h_last):
+        return run.decode(h_last, S, A, wl.mode, slot, wl.temperature, gumbel, want_logits=False, stream=stream)
+
+    def step():
+        h_last, _ = prefill()
+        return decode(h_last)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # phase split (one more step, events on the launch stream)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record(stream)
+    h_last, _ = prefill()
+    ev[1].record(stream)
+    decode(h_last)
+    ev[2].record(stream)
+    torch.cuda.synchronize()
+    prefill_ms, decode_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
+
+    # instrumented passes: per-kernel time from HIP events recorded by the library around each launch
+    vb.lib().vla_profile_enable(1)
+    h_last, _ = prefill()
+    torch.cuda.synchronize()
+    prof_prefill = profile_report(vb)
+    vb.lib().vla_profile_enable(1)
+    decode(h_last)
+    torch.cuda.synchronize()
+    prof_decode = profile_report(vb)
+    vb.lib().vla_profile_enable(0)
+
+    shape = wl.shape
+    dom = "gemm_bf16_mfma<swiglu>"          # gate/up projection: the largest share of the step
+    roofline = None
+    if dom in prof_prefill:
+        r = prof_prefill[dom]
+        achieved = r["work"] / (r["ms"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16_mfma_kernel<EPI_SWIGLU> (gate/up projection, prefill)",
+                    "achieved": achieved, "peak": MI355X_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / MI355X_BF16_TFLOPS, "launches": r["count"],
+                    "avg_launch_ms": r["ms"] / r["count"],
+                    "flops_per_launch": r["work"] / r["count"],
+                    "traffic": read_traffic(os.path.join(ROOT, "profiles", "gemm_swiglu_cfg3_traffic.txt"),
+                                            "gemm_bf16_mfma_kernel<2>")}
+    # decode HBM accounting: weights once per forward + each environment's own K, V rows per forward
+    kv_tok = 2 * shape.n_layers * shape.hidden * 2
+    fwd = A - 1 if wl.mode == 0 else 1
+    weight_bytes = shape.layer_params * shape.n_layers * 2
+    if wl.mode == 0:
+        kv_bytes = B * sum(S + j + 1 for j in range(A - 1)) * kv_tok
+    else:
+        kv_bytes = B * (S + A) * kv_tok
+    decode_bytes = fwd * weight_bytes + kv_bytes
+    decode_gbps = decode_bytes / (decode_ms * 1e-3) / 1e9
+    prefill_flops = B * S * 2.0 * shape.layer_params * shape.n_layers
+
+    def table(p):
+        return {k: {"n": v["count"], "ms": round(v["ms"], 3),
+                    "rate": (round(v["work"] / (v["ms"] * 1e-3) / 1e12, 3) if v["work"] and v["ms"] else None)}
+                for k, v in sorted(p.items(), key=lambda kv: -kv[1]["ms"])}
+
+    out = {
+        "metric": "env-actions/sec at batch 256 (7B shape), % HBM/MFMA roofline",
+        "value": B / (ms_per_step * 1e-3), "unit": "env-actions/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "batch": B, "prefix": S, "action_tokens": A,
+                   "mode": "autoregressive" if wl.mode == 0 else "parallel_chunk", "layers": shape.n_layers,
+                   "hidden": shape.hidden, "heads": shape.n_heads, "ffn": shape.ffn, "vocab": shape.vocab},
+        "roofline": roofline,
+        "phases": {"prefill_ms": prefill_ms, "decode_ms": decode_ms,
+                   "decode_only_env_actions_per_s": B / (decode_ms * 1e-3),
+                   "prefill_tokens_per_s": B * S / (prefill_ms * 1e-3),
+                   "decode_tokens_per_s": B * A / (decode_ms * 1e-3),
+                   "prefill_mfma_TFLOPs": prefill_flops / (prefill_ms * 1e-3) / 1e12,
+                   "prefill_mfma_frac": prefill_flops / (prefill_ms * 1e-3) / 1e12 / MI355X_BF16_TFLOPS,
+                   "decode_hbm_GBps": decode_gbps, "decode_hbm_frac": decode_gbps / MI355X_HBM_GBPS,
+                   "decode_algorithmic_GB": decode_bytes / 1e9},
+        "kernels_prefill": table(prof_prefill), "kernels_decode": table(prof_decode),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, vi)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

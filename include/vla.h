@@ -97,7 +97,7 @@ const char *vla_last_error(void);
 
 /* Create a host-side model object.  It stores the configuration and the weight POINTERS only;
  * the weights stay owned by the caller and must outlive the model.  Checks the dimensions:
- * hidden = n_heads * head_dim with head_dim a multiple of 8 and at most 256; n_bins = 256
+ * hidden = n_heads * head_dim with head_dim a multiple of 16 and at most 256; n_bins = 256
  * <= vocab; positive sizes.  Touches no device. */
 int vla_create(const vla_config *cfg, const vla_weights *weights, vla_model **out);
 int vla_destroy(vla_model *model);
@@ -167,6 +167,18 @@ int vla_logprob_recompute(vla_model *model, void *ws, size_t ws_bytes,
                           int N, int P, int T, int A, int mode, const void *slot_embed,
                           float temperature, float *logp, float *entropy, float *value,
                           float *logits, void *stream);
+
+/* ---- profiling (auxiliary; process-wide, not thread safe) --------------------------------------
+ * While enabled, every kernel launch of the three hot calls is bracketed by a pair of HIP events
+ * recorded on the launch stream, tagged with a label and with the launch's algorithmic work (flops
+ * for contractions, bytes for streaming kernels).  Events add a few microseconds per launch, so
+ * timed throughput runs keep profiling off.
+ *   vla_profile_enable(on)   turn recording on (1) or off (0); turning it on clears old records.
+ *   vla_profile_report(buf, n) synchronises the recorded events and writes, into the HOST buffer
+ *     buf of n bytes, one line per label: "label count total_ms total_work" (NUL terminated,
+ *     truncated to n).  Returns the number of labels, or a negative error code. */
+int vla_profile_enable(int on);
+int vla_profile_report(char *buf, size_t n);
 
 #ifdef __cplusplus
 }

@@ -28,6 +28,37 @@ int vla_check_launch(const char *what) {
     return 0;
 }
 
+
+// ------------------------------------------------------------------------------------------ profiling
+struct ProfRecord { const char *label; double work; hipEvent_t e0, e1; };
+static bool g_prof_on = false;
+static std::vector<ProfRecord> g_prof;          // records in use
+static std::vector<hipEvent_t> g_event_pool;    // events kept for reuse
+
+static hipEvent_t prof_event() {
+    if (!g_event_pool.empty()) { hipEvent_t e = g_event_pool.back(); g_event_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+ProfScope::ProfScope(const char *label, double work, hipStream_t s) : slot(-1), st(s) {
+    if (!g_prof_on) return;
+    ProfRecord r{label, work, prof_event(), prof_event()};
+    if (!r.e0 || !r.e1) return;
+    (void)hipEventRecord(r.e0, st);
+    g_prof.push_back(r);
+    slot = (int)g_prof.size() - 1;
+}
+ProfScope::~ProfScope() {
+    if (slot >= 0) (void)hipEventRecord(g_prof[slot].e1, st);
+}
+
+static void prof_clear() {
+    for (auto &r : g_prof) { g_event_pool.push_back(r.e0); g_event_pool.push_back(r.e1); }
+    g_prof.clear();
+}
+
 struct vla_model {
     vla_config cfg;
     vla_weights w;
@@ -385,6 +416,35 @@ int vla_logprob_recompute(vla_model *m, void *ws, size_t ws_bytes, const void *p
     return c.dtype == VLA_DTYPE_F32
                ? recompute_impl<float>(m, ws, patch, ids, bins, N, P, T, A, mode, slot_embed, temperature, logp, entropy, value, logits, st)
                : recompute_impl<bf16_t>(m, ws, patch, ids, bins, N, P, T, A, mode, slot_embed, temperature, logp, entropy, value, logits, st);
+}
+
+int vla_profile_enable(int on) {
+    prof_clear();
+    g_prof_on = on != 0;
+    return VLA_OK;
+}
+
+int vla_profile_report(char *buf, size_t n) {
+    if (!buf || n == 0) { vla_set_error("buf is NULL or empty"); return VLA_EINVAL; }
+    struct Agg { const char *label; long count; double ms, work; };
+    std::vector<Agg> agg;
+    for (auto &r : g_prof) {
+        if (hipEventSynchronize(r.e1) != hipSuccess) { vla_set_error("hipEventSynchronize failed"); return VLA_EHIP; }
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) { vla_set_error("hipEventElapsedTime failed"); return VLA_EHIP; }
+        Agg *a = nullptr;
+        for (auto &x : agg) if (strcmp(x.label, r.label) == 0) { a = &x; break; }
+        if (!a) { agg.push_back(Agg{r.label, 0, 0.0, 0.0}); a = &agg.back(); }
+        a->count++; a->ms += ms; a->work += r.work;
+    }
+    size_t off = 0;
+    buf[0] = 0;
+    for (auto &a : agg) {
+        int w = snprintf(buf + off, n - off, "%s %ld %.6f %.6e\n", a.label, a.count, a.ms, a.work);
+        if (w < 0 || (size_t)w >= n - off) break;
+        off += (size_t)w;
+    }
+    return (int)agg.size();
 }
 
 }  // extern "C"

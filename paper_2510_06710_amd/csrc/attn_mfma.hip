@@ -1,4 +1,200 @@
-// bf16 MFMA prefill attention for gfx950 (placeholder: declines every shape).
+// Multi-row attention on MFMA for prefill, recompute and the parallel action-chunk pass
+// (bf16, head_dim 64 or 128).  Rows at positions >= full_from see every key, rows below are causal.
+//
+// One wave owns 32 consecutive query rows of one (sequence, head) pair and walks the keys in blocks
+// of 32 with an online softmax.  Both products run transposed so that no operand ever needs a
+// cross-lane transpose:
+//   S^T = K . Q^T   (MFMA rows = keys, columns = queries; K is stored [d/8][position][8], which is
+//                    exactly the 16-byte (key, 8 dims) unit the row operand wants);
+//   O^T = V^T . P^T (rows = head dims, columns = queries; the accumulator layout of S^T -- a lane
+//                    holds one query column and 16 keys -- is directly the column operand P^T once
+//                    the MFMA's k slots are assigned to those 16 keys; V^T rows come from a
+//                    transposed copy of V [dim][position] written by a small kernel beforehand).
+// A lane therefore owns a single query for the whole kernel: running max, sum and the rescale of
+// O^T are per-lane scalars, with one lane-xor-32 exchange per key block.
 #include "vla_internal.h"
-size_t attention_prefill_scratch_bytes(int, int, int, int) { return 0; }
-int try_attention_prefill_bf16(bf16_t *, const bf16_t *, const KvView &, int, const RowsArgs &, int, void *, hipStream_t) { return 0; }
+
+namespace {
+
+// V [position][d] of the cache -> VT [d][ps_pad] with zeros for positions >= nk.
+template <int D>
+__global__ void __launch_bounds__(256) v_transpose_kernel(bf16_t *vt, const bf16_t *vc, int nk, int pos_stride,
+                                                         int ps_pad) {
+    __shared__ bf16_t tile[32][D + 8];
+    const int item = blockIdx.y, kb = blockIdx.x;          // (sequence, head), key block of 32
+    const bf16_t *vh = vc + (size_t)item * pos_stride * D;
+    bf16_t *vth = vt + (size_t)item * D * ps_pad;
+    for (int q = threadIdx.x; q < 32 * (D / 8); q += 256) {
+        int r = q / (D / 8), c = q % (D / 8);
+        int pos = kb * 32 + r;
+        bf16x8_t v;
+#pragma unroll
+        for (int e = 0; e < 8; e++) v[e] = (bf16_t)0.f;
+        if (pos < nk) v = *(const bf16x8_t *)(vh + (size_t)pos * D + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; e++) tile[r][c * 8 + e] = v[e];
+    }
+    __syncthreads();
+    for (int q = threadIdx.x; q < D * 4; q += 256) {
+        int dim = q / 4, c = q % 4;
+        bf16x8_t v;
+#pragma unroll
+        for (int e = 0; e < 8; e++) v[e] = tile[c * 8 + e][dim];
+        *(bf16x8_t *)(vth + (size_t)dim * ps_pad + kb * 32 + c * 8) = v;
+    }
+}
+
+template <int D>
+__global__ void __launch_bounds__(256) attn_prefill_kernel(bf16_t *out, const bf16_t *qkv, const bf16_t *kc,
+                                                          const bf16_t *vt, int R, int pos0, int full_from,
+                                                          int n_heads, int pos_stride, int ps_pad, int H,
+                                                          int q_blocks) {
+    constexpr int KS = D / 16;     // k steps of the S^T product
+    constexpr int DB = D / 32;     // 32-row blocks of O^T
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int qb = blockIdx.x * 4 + wave;
+    if (qb >= q_blocks) return;
+    const int item = blockIdx.y;                       // sequence * n_heads + head
+    const int s = item / n_heads, h = item - s * n_heads;
+    const int nk = pos0 + R;
+    const int col = lane & 31, hh = lane >> 5;
+    const int r = min(qb * 32 + col, R - 1);           // this lane's query row (clamped; masked at store)
+    const int qpos = pos0 + r;
+    const int limit = (qpos >= full_from) ? nk : qpos + 1;     // keys [0, limit) are visible
+    // largest limit in the wave decides how many key blocks to walk
+    int wlimit = limit;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) wlimit = max(wlimit, __shfl_xor(wlimit, o, 64));
+    const int n_kb = (wlimit + 31) >> 5;
+
+    const bf16_t *qrow = qkv + ((size_t)s * R + r) * 3 * H + (size_t)h * D;
+    bf16x8_t qf[KS];
+#pragma unroll
+    for (int kk = 0; kk < KS; kk++) qf[kk] = *(const bf16x8_t *)(qrow + kk * 16 + hh * 8);
+
+    const bf16_t *kh = kc + (size_t)item * D * pos_stride;
+    const bf16_t *vth = vt + (size_t)item * D * ps_pad;
+    const float scale = 1.0f / sqrtf((float)D);
+
+    f32x16_t o_acc[DB];
+#pragma unroll
+    for (int b = 0; b < DB; b++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) o_acc[b][i] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    for (int kb = 0; kb < n_kb; kb++) {
+        // ---- S^T block: rows = keys kb*32 .. +31, columns = the wave's 32 queries ---------------
+        const int key_ld = min(kb * 32 + col, nk - 1);          // clamped load, masked below
+        f32x16_t st;
+#pragma unroll
+        for (int i = 0; i < 16; i++) st[i] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KS; kk++) {
+            bf16x8_t kf = *(const bf16x8_t *)(kh + ((size_t)(kk * 2 + hh) * pos_stride + key_ld) * 8);
+            st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st, 0, 0, 0);
+        }
+        // register i of this lane is key kb*32 + 8*(i/4) + 4*hh + i%4 for query `col`
+        float bmax = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            int key = kb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
+            float v = (key < limit) ? st[i] * scale : -INFINITY;
+            st[i] = v;
+            bmax = fmaxf(bmax, v);
+        }
+        bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+        const float m_new = fmaxf(m_run, bmax);
+        // every query sees key 0, so after block 0 m_new is finite
+        const float corr = __expf(m_run - m_new);
+        float psum = 0.f;
+        bf16x8_t pf[2];
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            float p = __expf(st[i] - m_new);
+            psum += p;
+            pf[i >> 3][i & 7] = (bf16_t)p;
+        }
+        psum += __shfl_xor(psum, 32, 64);
+        l_run = l_run * corr + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int b = 0; b < DB; b++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) o_acc[b][i] *= corr;
+        // ---- O^T += V^T . P^T: k slot (hh, e) of product u is key kb*32 + 16u + 8*(e/4) + 4hh + e%4
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            const int key0 = kb * 32 + 16 * u + 4 * hh;
+#pragma unroll
+            for (int b = 0; b < DB; b++) {
+                const bf16_t *vrow = vth + (size_t)(b * 32 + col) * ps_pad + key0;
+                bf16x4_t lo = *(const bf16x4_t *)vrow;
+                bf16x4_t hi = *(const bf16x4_t *)(vrow + 8);
+                bf16x8_t vf;
+#pragma unroll
+                for (int e = 0; e < 4; e++) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
+                o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], o_acc[b], 0, 0, 0);
+            }
+        }
+    }
+    // ---- store: lane holds query `col`, dims b*32 + 8*(i/4) + 4*hh + i%4 -------------------------
+    if (qb * 32 + col < R) {
+        const float inv = 1.0f / l_run;
+        bf16_t *orow = out + ((size_t)s * R + r) * H + (size_t)h * D;
+#pragma unroll
+        for (int b = 0; b < DB; b++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                bf16x4_t o;
+#pragma unroll
+                for (int e = 0; e < 4; e++) o[e] = (bf16_t)(o_acc[b][g * 4 + e] * inv);
+                *(bf16x4_t *)(orow + b * 32 + g * 8 + 4 * hh) = o;
+            }
+    }
+}
+
+inline int round_up32(int v) { return (v + 31) & ~31; }
+
+}  // namespace
+
+size_t attention_prefill_scratch_bytes(int n_seq, int n_heads, int d, int n_keys) {
+    if (d != 64 && d != 128) return 0;
+    return (size_t)n_seq * n_heads * d * round_up32(n_keys) * sizeof(bf16_t);
+}
+
+int try_attention_prefill_bf16(bf16_t *out, const bf16_t *qkv, const KvView &kv, int layer, const RowsArgs &ra,
+                               int H, void *vt_scratch, hipStream_t st) {
+    if ((kv.d != 64 && kv.d != 128) || !vt_scratch || ra.R < 2) return 0;
+    const int nk = ra.pos0 + ra.R, ps_pad = round_up32(nk);
+    const int n_items = ra.n_seq * kv.n_heads;
+    if (n_items == 0) return 1;
+    if (n_items > 65535 * 16) return 0;
+    const bf16_t *kc = (const bf16_t *)kv.k + (size_t)layer * kv.layer_elems;
+    const bf16_t *vc = (const bf16_t *)kv.v + (size_t)layer * kv.layer_elems;
+    bf16_t *vt = (bf16_t *)vt_scratch;
+    const int q_blocks = (ra.R + 31) / 32;
+    int rc;
+    {
+        ProfScope ps("v_transpose", 2.0 * n_items * (double)nk * kv.d * 2.0, st);
+        dim3 grid(ps_pad / 32, n_items);
+        if (kv.d == 128) v_transpose_kernel<128><<<grid, 256, 0, st>>>(vt, vc, nk, kv.pos_stride, ps_pad);
+        else v_transpose_kernel<64><<<grid, 256, 0, st>>>(vt, vc, nk, kv.pos_stride, ps_pad);
+        if ((rc = vla_check_launch("v_transpose"))) return rc;
+    }
+    {
+        // algorithmic flops: 4 * d per (query, visible key) pair
+        double pairs = 0;
+        for (int r = 0; r < ra.R; r++) pairs += (ra.pos0 + r >= ra.full_from) ? nk : ra.pos0 + r + 1;
+        ProfScope ps("attn_prefill", 4.0 * kv.d * pairs * n_items, st);
+        dim3 grid((q_blocks + 3) / 4, n_items);
+        if (kv.d == 128)
+            attn_prefill_kernel<128><<<grid, 256, 0, st>>>(out, qkv, kc, vt, ra.R, ra.pos0, ra.full_from, kv.n_heads,
+                                                          kv.pos_stride, ps_pad, H, q_blocks);
+        else
+            attn_prefill_kernel<64><<<grid, 256, 0, st>>>(out, qkv, kc, vt, ra.R, ra.pos0, ra.full_from, kv.n_heads,
+                                                         kv.pos_stride, ps_pad, H, q_blocks);
+        if ((rc = vla_check_launch("attn_prefill"))) return rc;
+    }
+    return 1;
+}

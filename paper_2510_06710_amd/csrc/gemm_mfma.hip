@@ -209,6 +209,9 @@ int launch(const MfmaGemmParams &p, hipStream_t st) {
         }
         attr_set = true;
     }
+    const double flops = 2.0 * p.M * p.K * (EPI == EPI_SWIGLU ? 2.0 * p.N : (double)p.N);
+    ProfScope ps(EPI == EPI_SWIGLU ? "gemm_bf16_mfma<swiglu>" : EPI == EPI_RESIDUAL ? "gemm_bf16_mfma<residual>"
+                                                                                 : "gemm_bf16_mfma<store>", flops, st);
     gemm_bf16_mfma_kernel<EPI><<<p.tiles_m * p.tiles_n, 256, lds, st>>>(p);
     int rc = vla_check_launch("gemm_bf16_mfma");
     return rc ? rc : 1;
@@ -216,10 +219,11 @@ int launch(const MfmaGemmParams &p, hipStream_t st) {
 
 }  // namespace
 
-// Handles bf16 problems with K a multiple of 64, M >= 128 and N tiles that do not straddle weight
-// segments; anything else is declined (0) and runs on the generic kernel.
+// Handles bf16 problems with K a multiple of 64 and N tiles that do not straddle weight segments
+// (any M: rows beyond M are clamped on load and masked on store, and a row's result does not
+// depend on which tile it falls in); anything else is declined (0) and runs on the generic kernel.
 int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
-    if (g.M < 128 || g.K % BK != 0) return 0;
+    if (g.M < 1 || g.K % BK != 0) return 0;
     MfmaGemmParams p{};
     p.A = (const bf16_t *)g.A;
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];

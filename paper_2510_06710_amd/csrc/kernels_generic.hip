@@ -380,6 +380,7 @@ template <typename T>
 int launch_embed_prefix(float *X, const T *patch, const int32_t *ids, const T *embed, int n_seq, int P,
                         int T_, int rows_per_seq, int H, int vocab, hipStream_t st) {
     if (n_seq * (P + T_) == 0) return 0;
+    ProfScope ps("embed_prefix", 0.0, st);
     embed_prefix_kernel<T><<<n_seq * (P + T_), 256, 0, st>>>(X, patch, ids, embed, P, T_, rows_per_seq, H, vocab);
     return vla_check_launch("embed_prefix");
 }
@@ -387,6 +388,7 @@ template <typename T>
 int launch_embed_tokens(float *X, const int32_t *bins, int bins_stride, int n_tok, const T *embed,
                         int n_seq, int rows_per_seq, int row0, int H, int vocab, hipStream_t st) {
     if (n_seq * n_tok == 0) return 0;
+    ProfScope ps("embed_tokens", 0.0, st);
     embed_tokens_kernel<T><<<n_seq * n_tok, 256, 0, st>>>(X, bins, bins_stride, n_tok, embed, rows_per_seq, row0, H, vocab);
     return vla_check_launch("embed_tokens");
 }
@@ -394,24 +396,28 @@ template <typename T>
 int launch_embed_slots(float *X, const T *slot_embed, int n_seq, int A, int rows_per_seq, int row0,
                        int H, hipStream_t st) {
     if (n_seq * A == 0) return 0;
+    ProfScope ps("embed_slots", 0.0, st);
     embed_slots_kernel<T><<<n_seq * A, 256, 0, st>>>(X, slot_embed, A, rows_per_seq, row0, H);
     return vla_check_launch("embed_slots");
 }
 template <typename T>
 int launch_rmsnorm(T *out, const float *X, const float *gain, int M, int H, float eps, hipStream_t st) {
     if (M == 0) return 0;
+    ProfScope ps("rmsnorm", (double)M * H * (4 + sizeof(T)), st);
     rmsnorm_kernel<T><<<M, 256, 0, st>>>(out, X, gain, H, eps);
     return vla_check_launch("rmsnorm");
 }
 int launch_final_norm_rows(float *out, const float *X, const float *gain, int n_seq, int rows_per_seq,
                            int row0, int n_rows, int H, float eps, hipStream_t st) {
     if (n_seq * n_rows == 0) return 0;
+    ProfScope ps("final_norm_rows", 0.0, st);
     final_norm_rows_kernel<<<n_seq * n_rows, 256, 0, st>>>(out, X, gain, rows_per_seq, row0, n_rows, H, eps);
     return vla_check_launch("final_norm_rows");
 }
 template <typename T>
 int launch_gemm_generic(const GemmArgs &g, hipStream_t st) {
     if (g.M == 0) return 0;
+    ProfScope ps("gemm_generic", 2.0 * g.M * g.K * g.n_seg * g.segN, st);
     int N = (g.epilogue == EPI_SWIGLU) ? g.segN : g.n_seg * g.segN;
     dim3 grid((N + 63) / 64, (g.M + 63) / 64);
     const T *A = (const T *)g.A, *W0 = (const T *)g.W[0], *W1 = (const T *)g.W[1], *W2 = (const T *)g.W[2];
@@ -424,6 +430,7 @@ int launch_gemm_generic(const GemmArgs &g, hipStream_t st) {
     return vla_check_launch("gemm_generic");
 }
 int launch_rope_table(float2 *table, int R, int pos0, int d, float theta, hipStream_t st) {
+    ProfScope ps("rope_table", 0.0, st);
     int n = R * (d / 2);
     if (n == 0) return 0;
     rope_table_kernel<<<(n + 255) / 256, 256, 0, st>>>(table, R, pos0, d, theta);
@@ -432,6 +439,7 @@ int launch_rope_table(float2 *table, int R, int pos0, int d, float theta, hipStr
 template <typename T>
 int launch_rope_kv_write(T *qkv, const float2 *table, const KvView &kv, int layer, const RowsArgs &ra,
                          int H, hipStream_t st) {
+    ProfScope ps("rope_kv_write", (double)ra.n_seq * ra.R * H * 5 * sizeof(T), st);
     size_t total = (size_t)ra.n_seq * ra.R * kv.n_heads * (kv.d / 16);
     if (total == 0) return 0;
     T *kc = (T *)kv.k + (size_t)layer * kv.layer_elems;
@@ -443,6 +451,7 @@ int launch_rope_kv_write(T *qkv, const float2 *table, const KvView &kv, int laye
 template <typename T>
 int launch_attention_generic(T *out, const T *qkv, const KvView &kv, int layer, const RowsArgs &ra,
                              int H, hipStream_t st) {
+    ProfScope ps("attention_generic", 0.0, st);
     size_t total = (size_t)ra.n_seq * kv.n_heads * ra.R;
     if (total == 0) return 0;
     const T *kc = (const T *)kv.k + (size_t)layer * kv.layer_elems;
@@ -458,6 +467,7 @@ int launch_head_sample(const float *h, const T *lm_head_bins, int n_rows, int H,
                        float *ent, float *logits, int out_stride, int out_off, float *X_next,
                        const T *embed, int vocab, hipStream_t st) {
     if (n_rows == 0) return 0;
+    ProfScope ps("head_sample", 2.0 * n_rows * H * VLA_N_BINS, st);
     size_t lds = (size_t)(H + VLA_N_BINS) * sizeof(float);
     head_sample_kernel<T><<<n_rows, 256, lds, st>>>(h, lm_head_bins, H, temperature, gumbel, given_bins,
                                                     bins_out, logp, ent, logits, out_stride, out_off,
@@ -467,6 +477,7 @@ int launch_head_sample(const float *h, const T *lm_head_bins, int n_rows, int H,
 int launch_value_head(float *value, const float *h, const float *w, float b, int n, int H, int h_stride,
                       hipStream_t st) {
     if (n == 0) return 0;
+    ProfScope ps("value_head", 0.0, st);
     value_head_kernel<<<n, 256, 0, st>>>(value, h, w, b, H, h_stride);
     return vla_check_launch("value_head");
 }

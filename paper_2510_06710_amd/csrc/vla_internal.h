@@ -88,3 +88,12 @@ size_t attention_prefill_scratch_bytes(int n_seq, int n_heads, int d, int n_keys
 
 int vla_check_launch(const char *what);
 void vla_set_error(const char *fmt, ...);
+
+// Profiling scope: when profiling is enabled, records an event pair around the launches issued
+// during its lifetime, tagged with `label` (a string literal) and the algorithmic work.
+struct ProfScope {
+    ProfScope(const char *label, double work, hipStream_t st);
+    ~ProfScope();
+    int slot;
+    hipStream_t st;
+};

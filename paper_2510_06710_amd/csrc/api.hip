@@ -105,6 +105,7 @@ struct Workspace {
     float *Hb;       // final-norm rows fp32 [head_rows, H]
     void *kvs_k, *kvs_v;   // one-layer KV scratch (recompute)
     void *vt;        // scratch of the MFMA prefill attention
+    void *skinny;    // split-K partial sums of the decode GEMM (single-row forwards only)
     size_t total;
 };
 
@@ -127,6 +128,8 @@ static Workspace plan_workspace(const vla_config &c, char *base, int n_seq, int 
     size_t vtb = (c.dtype == VLA_DTYPE_BF16 && R > 1)
                      ? attention_prefill_scratch_bytes(n_seq, c.n_heads, c.hidden / c.n_heads, n_keys) : 0;
     w.vt = vtb ? take(vtb) : nullptr;
+    size_t skb = (c.dtype == VLA_DTYPE_BF16 && R == 1 && M <= 256) ? gemm_skinny_scratch_bytes((int)M, (int)(2 * F > 3 * H ? 2 * F : 3 * H)) : 0;
+    w.skinny = skb ? take(skb) : nullptr;
     w.total = off;
     return w;
 }
@@ -134,10 +137,14 @@ static Workspace plan_workspace(const vla_config &c, char *base, int n_seq, int 
 static int recompute_micro_batch(const vla_config &c, int N) { return N < c.max_batch ? N : c.max_batch; }
 
 // ------------------------------------------------------------------------------------------ forward
+// Kernel choice depends on the storage type and on whether the forward has one row per sequence
+// (decode) -- never on M itself, so a row's result is the same whatever batch it is part of.
 template <typename T>
-static int run_gemm(const vla_config &c, GemmArgs g, hipStream_t st) {
+static int run_gemm(const vla_config &c, GemmArgs g, void *skinny_scratch, hipStream_t st) {
     if (c.dtype == VLA_DTYPE_BF16) {
-        int r = try_gemm_bf16_mfma(g, st);
+        int r = skinny_scratch ? try_gemm_bf16_skinny(g, skinny_scratch, st) : 0;
+        if (r != 0) return r < 0 ? r : 0;
+        r = try_gemm_bf16_mfma(g, st);
         if (r != 0) return r < 0 ? r : 0;
     }
     return launch_gemm_generic<T>(g, st);
@@ -158,8 +165,10 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
         GemmArgs g{};
         g.A = ws.Nrm; g.W[0] = lw.wq; g.W[1] = lw.wk; g.W[2] = lw.wv; g.n_seg = 3; g.segN = H;
         g.C = ws.QKV; g.M = M; g.K = H; g.epilogue = EPI_STORE;
-        if ((rc = run_gemm<T>(c, g, st))) return rc;
-        if ((rc = launch_rope_kv_write<T>((T *)ws.QKV, ws.rope, kv, kl, ra, H, st))) return rc;
+        if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
+        if (c.dtype == VLA_DTYPE_BF16) rc = launch_rope_kv_write_bf16((bf16_t *)ws.QKV, ws.rope, kv, kl, ra, H, st);
+        else rc = launch_rope_kv_write<T>((T *)ws.QKV, ws.rope, kv, kl, ra, H, st);
+        if (rc) return rc;
         int done = 0;
         if (c.dtype == VLA_DTYPE_BF16) {
             done = (ra.R == 1)
@@ -170,15 +179,15 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
         if (!done && (rc = launch_attention_generic<T>((T *)ws.AO, (const T *)ws.QKV, kv, kl, ra, H, st))) return rc;
         g = GemmArgs{};
         g.A = ws.AO; g.W[0] = lw.wo; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = H; g.epilogue = EPI_RESIDUAL;
-        if ((rc = run_gemm<T>(c, g, st))) return rc;
+        if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
         if ((rc = launch_rmsnorm<T>((T *)ws.Nrm, ws.X, (const float *)lw.ffn_norm, M, H, c.rms_eps, st))) return rc;
         g = GemmArgs{};
         g.A = ws.Nrm; g.W[0] = lw.w_gate; g.W[1] = lw.w_up; g.n_seg = 2; g.segN = F; g.C = ws.ACT; g.M = M; g.K = H;
         g.epilogue = EPI_SWIGLU;
-        if ((rc = run_gemm<T>(c, g, st))) return rc;
+        if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
         g = GemmArgs{};
         g.A = ws.ACT; g.W[0] = lw.w_down; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = F; g.epilogue = EPI_RESIDUAL;
-        if ((rc = run_gemm<T>(c, g, st))) return rc;
+        if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
     }
     return 0;
 }

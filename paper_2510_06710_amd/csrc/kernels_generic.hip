@@ -286,8 +286,8 @@ __global__ void __launch_bounds__(256) attention_generic_kernel(T *out, const T 
 }
 
 // ---------------------------------------------------------------------------------- head + sampler
-// One 256-thread block per row.  Logits over the 256 action bins, then wave 0 reduces the softmax
-// statistics and the Gumbel-max choice with four bins per lane (bins lane, lane+64, +128, +192).
+// One 256-thread block per row.  Logits over the 256 action bins (one bin per thread), then wave 0
+// reduces the softmax statistics and the Gumbel-max choice with four bins per lane (bins lane, lane+64, +128, +192).
 template <typename T>
 __global__ void __launch_bounds__(256) head_sample_kernel(const float *h, const T *Wb, int H, float temperature,
                                                          const float *gumbel, const int32_t *given,
@@ -304,13 +304,22 @@ __global__ void __launch_bounds__(256) head_sample_kernel(const float *h, const 
     const float *hr = h + (size_t)row * H;
     for (int i = threadIdx.x; i < H; i += 256) hs[i] = hr[i];
     __syncthreads();
-    for (int kk = 0; kk < 64; kk++) {
-        int k = wave * 64 + kk;
+    {   // thread k owns bin k: its weight row is walked in 16-byte pieces, h is broadcast from LDS
+        const int k = threadIdx.x;
         const T *w = Wb + (size_t)k * H;
-        float acc = 0.f;
-        for (int i = lane; i < H; i += 64) acc += hs[i] * to_f(w[i]);
-        acc = wave_sum(acc);
-        if (lane == 0) z[k] = acc;
+        constexpr int V = 16 / sizeof(T);
+        float a0 = 0.f, a1 = 0.f;
+        int i = 0;
+        if (H % V == 0) {
+            typedef T vec_t __attribute__((ext_vector_type(V)));
+            for (; i + 2 * V <= H; i += 2 * V) {
+                vec_t w0 = *(const vec_t *)(w + i), w1 = *(const vec_t *)(w + i + V);
+#pragma unroll
+                for (int e = 0; e < V; e++) { a0 += hs[i + e] * to_f(w0[e]); a1 += hs[i + V + e] * to_f(w1[e]); }
+            }
+        }
+        for (; i < H; i++) a0 += hs[i] * to_f(w[i]);
+        z[k] = a0 + a1;
     }
     __syncthreads();
     if (logits) logits[o * VLA_N_BINS + threadIdx.x] = z[threadIdx.x];

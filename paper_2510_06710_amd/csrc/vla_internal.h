@@ -80,6 +80,10 @@ int launch_value_head(float *value, const float *h, const float *w, float b, int
 // ---- gfx950 fast paths (bf16, aligned shapes); each returns 1 if it handled the call, 0 if the
 // shape is outside what it supports (caller then uses the generic kernel), <0 on launch error ----
 int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st);
+int launch_rope_kv_write_bf16(bf16_t *qkv, const float2 *table, const KvView &kv, int layer, const RowsArgs &ra,
+                              int H, hipStream_t st);
+int try_gemm_bf16_skinny(const GemmArgs &g, void *scratch, hipStream_t st);
+size_t gemm_skinny_scratch_bytes(int M, int max_n);
 int try_attention_prefill_bf16(bf16_t *out, const bf16_t *qkv, const KvView &kv, int layer,
                                const RowsArgs &ra, int H, void *vt_scratch, hipStream_t st);
 int try_attention_decode_bf16(bf16_t *out, const bf16_t *qkv, const KvView &kv, int layer,

@@ -15,6 +15,13 @@ RAGGED = vi.Workload("ragged", vi.ModelShape(n_layers=3, hidden=96, n_heads=3, f
                      batch=3, n_patches=5, n_instr=3, n_action=4)
 
 
+# bf16 shape whose dimensions satisfy the MFMA / streaming kernels' alignment (K % 64, N % 128,
+# head_dim 128), so the small tests also cover those kernels; batch sizes span the three row-block
+# variants of the decode GEMM and a ragged last tile of the large GEMM.
+ALIGNED = vi.Workload("aligned", vi.ModelShape(n_layers=2, hidden=256, n_heads=2, ffn=512, vocab=640, dtype="bf16"),
+                      batch=5, n_patches=40, n_instr=9, n_action=4)
+
+
 def _print(name, stats):
     print(f"\n[parity] {name}: {stats}", flush=True)
 
@@ -36,6 +43,23 @@ def test_ragged_shapes_rollout(dtype, tau):
     ref = oracle_rollout(wl, 1)
     gpu = GpuCase(wl, 1).rollout()
     _print(f"ragged {dtype} tau={tau}", compare_rollout(gpu, ref, dtype, autoregressive=True))
+
+
+@pytest.mark.parametrize("B", [5, 70, 130])
+def test_aligned_bf16_rollout_fast_kernels(B):
+    wl = vi.scaled(ALIGNED, batch=B)
+    ref = oracle_rollout(wl, 10)
+    gpu = GpuCase(wl, 10).rollout()
+    _print(f"aligned bf16 B={B}", compare_rollout(gpu, ref, "bf16", autoregressive=True))
+
+
+def test_aligned_bf16_chunk_and_recompute_fast_kernels():
+    wl = vi.scaled(ALIGNED, batch=6, n_action=40, mode=1)
+    ref = oracle_rollout(wl, 11)
+    case = GpuCase(wl, 11)
+    _print("aligned chunk", compare_rollout(case.rollout(), ref, "bf16", autoregressive=False))
+    _print("aligned chunk recompute", compare_recompute(case.recompute(ref["bins"]),
+                                                        oracle_recompute(wl, 11, ref["bins"]), "bf16"))
 
 
 def test_tiny_bf16_rollout():

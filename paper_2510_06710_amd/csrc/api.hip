@@ -2,6 +2,7 @@
 // sequencing of kernels.  All arithmetic lives in the kernels; this file only enqueues them.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -137,14 +138,23 @@ static Workspace plan_workspace(const vla_config &c, char *base, int n_seq, int 
 static int recompute_micro_batch(const vla_config &c, int N) { return N < c.max_batch ? N : c.max_batch; }
 
 // ------------------------------------------------------------------------------------------ forward
+// Triage knob: VLA_FORCE_GENERIC is a bit mask that sends a step to the shape-generic kernel even
+// when a gfx950 fast path applies (1 large GEMM, 2 decode GEMM, 4 multi-row attention, 8 decode
+// attention, 16 rotary/KV write).  Read once.
+static int force_generic() {
+    static int v = -1;
+    if (v < 0) { const char *e = getenv("VLA_FORCE_GENERIC"); v = e ? atoi(e) : 0; }
+    return v;
+}
+
 // Kernel choice depends on the storage type and on whether the forward has one row per sequence
 // (decode) -- never on M itself, so a row's result is the same whatever batch it is part of.
 template <typename T>
 static int run_gemm(const vla_config &c, GemmArgs g, void *skinny_scratch, hipStream_t st) {
     if (c.dtype == VLA_DTYPE_BF16) {
-        int r = skinny_scratch ? try_gemm_bf16_skinny(g, skinny_scratch, st) : 0;
+        int r = (skinny_scratch && !(force_generic() & 2)) ? try_gemm_bf16_skinny(g, skinny_scratch, st) : 0;
         if (r != 0) return r < 0 ? r : 0;
-        r = try_gemm_bf16_mfma(g, st);
+        r = (force_generic() & 1) ? 0 : try_gemm_bf16_mfma(g, st);
         if (r != 0) return r < 0 ? r : 0;
     }
     return launch_gemm_generic<T>(g, st);
@@ -166,14 +176,15 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
         g.A = ws.Nrm; g.W[0] = lw.wq; g.W[1] = lw.wk; g.W[2] = lw.wv; g.n_seg = 3; g.segN = H;
         g.C = ws.QKV; g.M = M; g.K = H; g.epilogue = EPI_STORE;
         if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
-        if (c.dtype == VLA_DTYPE_BF16) rc = launch_rope_kv_write_bf16((bf16_t *)ws.QKV, ws.rope, kv, kl, ra, H, st);
+        if (c.dtype == VLA_DTYPE_BF16 && !(force_generic() & 16)) rc = launch_rope_kv_write_bf16((bf16_t *)ws.QKV, ws.rope, kv, kl, ra, H, st);
         else rc = launch_rope_kv_write<T>((T *)ws.QKV, ws.rope, kv, kl, ra, H, st);
         if (rc) return rc;
         int done = 0;
         if (c.dtype == VLA_DTYPE_BF16) {
-            done = (ra.R == 1)
-                       ? try_attention_decode_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.QKV, kv, kl, ra, H, st)
-                       : try_attention_prefill_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.QKV, kv, kl, ra, H, ws.vt, st);
+            if (ra.R == 1)
+                done = (force_generic() & 8) ? 0 : try_attention_decode_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.QKV, kv, kl, ra, H, st);
+            else
+                done = (force_generic() & 4) ? 0 : try_attention_prefill_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.QKV, kv, kl, ra, H, ws.vt, st);
             if (done < 0) return done;
         }
         if (!done && (rc = launch_attention_generic<T>((T *)ws.AO, (const T *)ws.QKV, kv, kl, ra, H, st))) return rc;

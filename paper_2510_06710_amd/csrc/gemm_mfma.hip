@@ -15,6 +15,8 @@
 //
 // Epilogues: store bf16; add into the fp32 residual stream; SwiGLU (tile rows interleave 64 gate and
 // 64 up rows per wave so that silu(gate) * up pairs two accumulators of the same lane).
+#include <stdlib.h>
+
 #include "vla_internal.h"
 
 namespace {
@@ -28,6 +30,7 @@ struct MfmaGemmParams {
     void *C;
     int M, N, K, segN;
     int tiles_m, tiles_n;
+    int dbg;
 };
 
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
@@ -120,31 +123,88 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     }
     const int khalf = lane >> 5;
 
+    // Software pipeline (one wave per SIMD, so nothing else hides LDS latency): the fragments of
+    // k-step ks+1 are read while the MFMAs of k-step ks run; the next K tile's global loads are issued
+    // at the top of the tile, written to the other LDS stage during k-step 2, and after one barrier
+    // the first fragments of the next tile are read under the MFMAs of k-step 3.
+    bf16x8_t af[2][4], wf[2][4];
+    auto frag_load = [&](int buf, const char *base, int ks) {
+        const int c = ks * 2 + khalf;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            af[buf][i] = *(const bf16x8_t *)(base + a_off[i] + ((c ^ a_sw[i]) << 4));
+            wf[buf][i] = *(const bf16x8_t *)(base + w_off[i] + ((c ^ w_sw[i]) << 4));
+        }
+    };
+    auto mfma_step = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
+    };
+
     const int ktiles = K / BK;
     gload(0);
     lstore(0);
     __syncthreads();
+    frag_load(0, lds, 0);
     for (int kt = 0; kt < ktiles; kt++) {
         const int s = kt & 1;
-        if (kt + 1 < ktiles) gload((kt + 1) * BK);
+        // the last tile re-stages itself into the idle buffer: a branch-free body schedules better
+        const int kn = p.dbg ? 0 : min(kt + 1, ktiles - 1);
         const char *base = lds + s * 2 * TILE_BYTES;
+        // Each region below pairs its memory instructions one by one with MFMAs (sched_group_barrier:
+        // 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write), so the matrix pipe keeps issuing
+        // while LDS and global traffic trickles in between.
+        gload(kn * BK);
+        frag_load(1, base, 1);
+        mfma_step(0);
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
-            bf16x8_t af[4], wf[4];
-            int c = ks * 2 + khalf;
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                af[i] = *(const bf16x8_t *)(base + a_off[i] + ((c ^ a_sw[i]) << 4));
-                wf[i] = *(const bf16x8_t *)(base + w_off[i] + ((c ^ w_sw[i]) << 4));
-            }
-#pragma unroll
-            for (int j = 0; j < 4; j++)
-#pragma unroll
-                for (int i = 0; i < 4; i++)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[j][i], 0, 0, 0);
+        for (int i = 0; i < 8; i++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
-        if (kt + 1 < ktiles) lstore(s ^ 1);
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        frag_load(0, base, 2);
+        mfma_step(1);
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        frag_load(1, base, 3);
+        lstore(s ^ 1);
+        mfma_step(0);
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
+        frag_load(0, lds + (s ^ 1) * 2 * TILE_BYTES, 0);
+        mfma_step(1);
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     // ---- epilogue: lane holds activation row m = .. + lane % 32 and, per accumulator register r,
@@ -229,6 +289,7 @@ int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
     p.C = g.C; p.M = g.M; p.K = g.K; p.segN = g.segN;
     p.tiles_m = (g.M + BM - 1) / BM;
+    { const char *e = getenv("VLA_GEMM_DBG"); p.dbg = e ? atoi(e) : 0; }
     if (g.epilogue == EPI_SWIGLU) {
         if (g.segN % 128 != 0) return 0;
         p.N = g.segN;

@@ -12,10 +12,11 @@ def to_f64(t) -> np.ndarray:
     return t.detach().to("cpu").float().numpy().astype(np.float64)
 
 
-def oracle_config(shape) -> OracleConfig:
+def oracle_config(shape, operand_dtype: str = "exact") -> OracleConfig:
     return OracleConfig(n_layers=shape.n_layers, hidden=shape.hidden, n_heads=shape.n_heads,
                         ffn=shape.ffn, vocab=shape.vocab, n_bins=shape.n_bins,
-                        rms_eps=shape.rms_eps, rope_theta=shape.rope_theta)
+                        rms_eps=shape.rms_eps, rope_theta=shape.rope_theta,
+                        operand_dtype=operand_dtype)
 
 
 def oracle_weights(model, value_b: float, cache_layers: bool = True) -> OracleWeights:

@@ -99,7 +99,8 @@ static size_t kv_layer_elems(const vla_config &c, int n_seq) {
 struct Workspace {
     float *X;        // residual stream fp32 [M, H]
     void *Nrm;       // norm output, storage dtype [M, H]
-    void *QKV;       // [M, 3H]
+    float *QKV;      // QKV projection, fp32 [M, 3H] (rounded only after the rotation)
+    void *Q;         // rotated q, storage dtype [M, H]
     void *AO;        // attention output [M, H]
     void *ACT;       // SwiGLU output [M, F]
     float2 *rope;    // [R, d/2]
@@ -119,7 +120,8 @@ static Workspace plan_workspace(const vla_config &c, char *base, int n_seq, int 
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += align_up(bytes); return (void *)p; };
     w.X = (float *)take(M * H * 4);
     w.Nrm = take(M * H * es);
-    w.QKV = take(M * 3 * H * es);
+    w.QKV = (float *)take(M * 3 * H * 4);
+    w.Q = take(M * H * es);
     w.AO = take(M * H * es);
     w.ACT = take(M * F * es);
     w.rope = (float2 *)take((size_t)R * (H / c.n_heads / 2) * sizeof(float2));
@@ -163,6 +165,15 @@ static int run_gemm(const vla_config &c, GemmArgs g, void *skinny_scratch, hipSt
 // All decoder layers over n_seq x R new rows held in ws.X; K, V of the new rows go to `kv`
 // (layer l of it, or layer 0 when `kv` is a one-layer scratch).
 template <typename T>
+static int run_rmsnorm(const vla_config &c, void *out, const float *X, const void *gain, int M, hipStream_t st) {
+    if (c.dtype == VLA_DTYPE_BF16 && !(force_generic() & 16)) {
+        int r = try_rmsnorm_bf16((bf16_t *)out, X, (const float *)gain, M, c.hidden, c.rms_eps, st);
+        if (r != 0) return r < 0 ? r : 0;
+    }
+    return launch_rmsnorm<T>((T *)out, X, (const float *)gain, M, c.hidden, c.rms_eps, st);
+}
+
+template <typename T>
 static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &ra, const KvView &kv,
                       bool kv_single_layer, hipStream_t st) {
     const vla_config &c = m->cfg;
@@ -171,27 +182,27 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
     for (int l = 0; l < c.n_layers; l++) {
         const vla_layer_weights &lw = m->layers[l];
         int kl = kv_single_layer ? 0 : l;
-        if ((rc = launch_rmsnorm<T>((T *)ws.Nrm, ws.X, (const float *)lw.attn_norm, M, H, c.rms_eps, st))) return rc;
+        if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.attn_norm, M, st))) return rc;
         GemmArgs g{};
         g.A = ws.Nrm; g.W[0] = lw.wq; g.W[1] = lw.wk; g.W[2] = lw.wv; g.n_seg = 3; g.segN = H;
         g.C = ws.QKV; g.M = M; g.K = H; g.epilogue = EPI_STORE;
         if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
-        if (c.dtype == VLA_DTYPE_BF16 && !(force_generic() & 16)) rc = launch_rope_kv_write_bf16((bf16_t *)ws.QKV, ws.rope, kv, kl, ra, H, st);
-        else rc = launch_rope_kv_write<T>((T *)ws.QKV, ws.rope, kv, kl, ra, H, st);
+        if (c.dtype == VLA_DTYPE_BF16 && !(force_generic() & 16)) rc = launch_rope_kv_write_bf16((bf16_t *)ws.Q, ws.QKV, ws.rope, kv, kl, ra, H, st);
+        else rc = launch_rope_kv_write<T>((T *)ws.Q, ws.QKV, ws.rope, kv, kl, ra, H, st);
         if (rc) return rc;
         int done = 0;
         if (c.dtype == VLA_DTYPE_BF16) {
             if (ra.R == 1)
-                done = (force_generic() & 8) ? 0 : try_attention_decode_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.QKV, kv, kl, ra, H, st);
+                done = (force_generic() & 8) ? 0 : try_attention_decode_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.Q, kv, kl, ra, H, st);
             else
-                done = (force_generic() & 4) ? 0 : try_attention_prefill_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.QKV, kv, kl, ra, H, ws.vt, st);
+                done = (force_generic() & 4) ? 0 : try_attention_prefill_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.Q, kv, kl, ra, H, ws.vt, st);
             if (done < 0) return done;
         }
-        if (!done && (rc = launch_attention_generic<T>((T *)ws.AO, (const T *)ws.QKV, kv, kl, ra, H, st))) return rc;
+        if (!done && (rc = launch_attention_generic<T>((T *)ws.AO, (const T *)ws.Q, kv, kl, ra, H, st))) return rc;
         g = GemmArgs{};
         g.A = ws.AO; g.W[0] = lw.wo; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = H; g.epilogue = EPI_RESIDUAL;
         if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
-        if ((rc = launch_rmsnorm<T>((T *)ws.Nrm, ws.X, (const float *)lw.ffn_norm, M, H, c.rms_eps, st))) return rc;
+        if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.ffn_norm, M, st))) return rc;
         g = GemmArgs{};
         g.A = ws.Nrm; g.W[0] = lw.w_gate; g.W[1] = lw.w_up; g.n_seg = 2; g.segN = F; g.C = ws.ACT; g.M = M; g.K = H;
         g.epilogue = EPI_SWIGLU;

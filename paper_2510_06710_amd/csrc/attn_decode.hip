@@ -27,7 +27,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 template <int D>
-__global__ void __launch_bounds__(256) attn_decode_kernel(bf16_t *out, const bf16_t *qkv, const bf16_t *kc,
+__global__ void __launch_bounds__(256) attn_decode_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
                                                          const bf16_t *vc, int n_items, int n_heads, int nk,
                                                          int pos_stride, int H) {
     constexpr int DC = D / 8;        // 16-byte chunks per head vector
@@ -38,7 +38,7 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(bf16_t *out, const bf1
     const int item = blockIdx.x * 4 + wave;
     if (item >= n_items) return;                       // whole wave leaves; no block barrier below
     const int s = item / n_heads, h = item - s * n_heads;
-    const bf16_t *q = qkv + (size_t)s * 3 * H + (size_t)h * D;
+    const bf16_t *q = qbuf + (size_t)s * H + (size_t)h * D;
     const float scale = 1.0f / sqrtf((float)D);
     for (int i = lane; i < D; i += 64) qs[wave][i] = (float)q[i] * scale;
     __builtin_amdgcn_wave_barrier();
@@ -112,7 +112,7 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(bf16_t *out, const bf1
 
 }  // namespace
 
-int try_attention_decode_bf16(bf16_t *out, const bf16_t *qkv, const KvView &kv, int layer, const RowsArgs &ra,
+int try_attention_decode_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, int layer, const RowsArgs &ra,
                               int H, hipStream_t st) {
     const int nk = ra.pos0 + 1;
     if (ra.R != 1 || nk > MAXCH * 64 || (kv.d != 64 && kv.d != 128)) return 0;
@@ -124,9 +124,9 @@ int try_attention_decode_bf16(bf16_t *out, const bf16_t *qkv, const KvView &kv, 
     ProfScope ps("attn_decode", 2.0 * n_items * (double)nk * kv.d * 2.0, st);
     const int grid = (n_items + 3) / 4;
     if (kv.d == 128)
-        attn_decode_kernel<128><<<grid, 256, 0, st>>>(out, qkv, kc, vc, n_items, kv.n_heads, nk, kv.pos_stride, H);
+        attn_decode_kernel<128><<<grid, 256, 0, st>>>(out, q, kc, vc, n_items, kv.n_heads, nk, kv.pos_stride, H);
     else
-        attn_decode_kernel<64><<<grid, 256, 0, st>>>(out, qkv, kc, vc, n_items, kv.n_heads, nk, kv.pos_stride, H);
+        attn_decode_kernel<64><<<grid, 256, 0, st>>>(out, q, kc, vc, n_items, kv.n_heads, nk, kv.pos_stride, H);
     int rc = vla_check_launch("attn_decode");
     return rc ? rc : 1;
 }

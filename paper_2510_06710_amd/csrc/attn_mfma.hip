@@ -45,7 +45,7 @@ __global__ void __launch_bounds__(256) v_transpose_kernel(bf16_t *vt, const bf16
 }
 
 template <int D>
-__global__ void __launch_bounds__(256) attn_prefill_kernel(bf16_t *out, const bf16_t *qkv, const bf16_t *kc,
+__global__ void __launch_bounds__(256) attn_prefill_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
                                                           const bf16_t *vt, int R, int pos0, int full_from,
                                                           int n_heads, int pos_stride, int ps_pad, int H,
                                                           int q_blocks) {
@@ -67,7 +67,7 @@ __global__ void __launch_bounds__(256) attn_prefill_kernel(bf16_t *out, const bf
     for (int o = 32; o > 0; o >>= 1) wlimit = max(wlimit, __shfl_xor(wlimit, o, 64));
     const int n_kb = (wlimit + 31) >> 5;
 
-    const bf16_t *qrow = qkv + ((size_t)s * R + r) * 3 * H + (size_t)h * D;
+    const bf16_t *qrow = qbuf + ((size_t)s * R + r) * H + (size_t)h * D;
     bf16x8_t qf[KS];
 #pragma unroll
     for (int kk = 0; kk < KS; kk++) qf[kk] = *(const bf16x8_t *)(qrow + kk * 16 + hh * 8);
@@ -107,13 +107,17 @@ __global__ void __launch_bounds__(256) attn_prefill_kernel(bf16_t *out, const bf
         const float m_new = fmaxf(m_run, bmax);
         // every query sees key 0, so after block 0 m_new is finite
         const float corr = __expf(m_run - m_new);
+        // p is split into a bf16 head and a bf16 tail (two products below), so the probabilities
+        // enter P.V with ~16 significant bits instead of 8
         float psum = 0.f;
-        bf16x8_t pf[2];
+        bf16x8_t pf[2], pl[2];
 #pragma unroll
         for (int i = 0; i < 16; i++) {
             float p = __expf(st[i] - m_new);
             psum += p;
-            pf[i >> 3][i & 7] = (bf16_t)p;
+            bf16_t ph = (bf16_t)p;
+            pf[i >> 3][i & 7] = ph;
+            pl[i >> 3][i & 7] = (bf16_t)(p - (float)ph);
         }
         psum += __shfl_xor(psum, 32, 64);
         l_run = l_run * corr + psum;
@@ -135,6 +139,7 @@ __global__ void __launch_bounds__(256) attn_prefill_kernel(bf16_t *out, const bf
 #pragma unroll
                 for (int e = 0; e < 4; e++) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
                 o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], o_acc[b], 0, 0, 0);
+                o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pl[u], o_acc[b], 0, 0, 0);
             }
         }
     }
@@ -163,7 +168,7 @@ size_t attention_prefill_scratch_bytes(int n_seq, int n_heads, int d, int n_keys
     return (size_t)n_seq * n_heads * d * round_up32(n_keys) * sizeof(bf16_t);
 }
 
-int try_attention_prefill_bf16(bf16_t *out, const bf16_t *qkv, const KvView &kv, int layer, const RowsArgs &ra,
+int try_attention_prefill_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, int layer, const RowsArgs &ra,
                                int H, void *vt_scratch, hipStream_t st) {
     if ((kv.d != 64 && kv.d != 128) || !vt_scratch || ra.R < 2) return 0;
     const int nk = ra.pos0 + ra.R, ps_pad = round_up32(nk);
@@ -189,10 +194,10 @@ int try_attention_prefill_bf16(bf16_t *out, const bf16_t *qkv, const KvView &kv,
         ProfScope ps("attn_prefill", 4.0 * kv.d * pairs * n_items, st);
         dim3 grid((q_blocks + 3) / 4, n_items);
         if (kv.d == 128)
-            attn_prefill_kernel<128><<<grid, 256, 0, st>>>(out, qkv, kc, vt, ra.R, ra.pos0, ra.full_from, kv.n_heads,
+            attn_prefill_kernel<128><<<grid, 256, 0, st>>>(out, q, kc, vt, ra.R, ra.pos0, ra.full_from, kv.n_heads,
                                                           kv.pos_stride, ps_pad, H, q_blocks);
         else
-            attn_prefill_kernel<64><<<grid, 256, 0, st>>>(out, qkv, kc, vt, ra.R, ra.pos0, ra.full_from, kv.n_heads,
+            attn_prefill_kernel<64><<<grid, 256, 0, st>>>(out, q, kc, vt, ra.R, ra.pos0, ra.full_from, kv.n_heads,
                                                          kv.pos_stride, ps_pad, H, q_blocks);
         if ((rc = vla_check_launch("attn_prefill"))) return rc;
     }

@@ -3,11 +3,24 @@
 
 namespace {
 
-// Rotary on q and k plus the KV-cache write, bf16.  One thread per (row, head, 8-dim chunk c of the
-// first half): it owns dims [8c, 8c+8) and [d/2 + 8c, d/2 + 8c + 8) of q, k and v.  q is rotated in
-// place inside the QKV buffer; k goes to the [d/8][position][8] layout, v to [position][d].
-__global__ void __launch_bounds__(256) rope_kv_write_bf16_kernel(bf16_t *qkv, const float2 *table, bf16_t *kc,
-                                                                bf16_t *vc, size_t total, int R, int pos0,
+// Rotary on q and k plus the KV-cache write.  Input: the fp32 [M, 3H] QKV projection (rounded to bf16
+// only after the rotation).  One thread per (row, head, 8-dim chunk c of the first half): it owns dims
+// [8c, 8c+8) and [d/2 + 8c, d/2 + 8c + 8) of q, k and v.  q goes to its own bf16 [M, H] buffer, k to
+// the [d/8][position][8] layout, v to [position][d].
+__device__ __forceinline__ void load8(const float *p, float *o) {
+    f32x4_t a = *(const f32x4_t *)p, b = *(const f32x4_t *)(p + 4);
+#pragma unroll
+    for (int e = 0; e < 4; e++) { o[e] = a[e]; o[4 + e] = b[e]; }
+}
+__device__ __forceinline__ bf16x8_t pack8(const float *v) {
+    bf16x8_t o;
+#pragma unroll
+    for (int e = 0; e < 8; e++) o[e] = (bf16_t)v[e];
+    return o;
+}
+
+__global__ void __launch_bounds__(256) rope_kv_write_bf16_kernel(bf16_t *q_out, const float *qkv, const float2 *table,
+                                                                bf16_t *kc, bf16_t *vc, size_t total, int R, int pos0,
                                                                 int n_heads, int d, int pos_stride, int H) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
@@ -17,47 +30,97 @@ __global__ void __launch_bounds__(256) rope_kv_write_bf16_kernel(bf16_t *qkv, co
     const size_t m = idx / ((size_t)chunks * n_heads);
     const int s = (int)(m / R), r = (int)(m % R);
     const int pos = pos0 + r;
-    bf16_t *q = qkv + m * 3 * (size_t)H + (size_t)h * d + c * 8;
-    bf16_t *k = q + H, *v = q + 2 * (size_t)H;
-    bf16x8_t qa = *(const bf16x8_t *)q, qb = *(const bf16x8_t *)(q + half);
-    bf16x8_t ka = *(const bf16x8_t *)k, kb = *(const bf16x8_t *)(k + half);
-    bf16x8_t va = *(const bf16x8_t *)v, vb = *(const bf16x8_t *)(v + half);
-    const f32x4_t *tb = (const f32x4_t *)(table + (size_t)r * half + c * 8);     // 8 x (cos, sin)
-    bf16x8_t qlo, qhi, klo, khi;
+    const float *q = qkv + m * 3 * (size_t)H + (size_t)h * d + c * 8;
+    const float *k = q + H, *v = q + 2 * (size_t)H;
+    float qa[8], qb[8], ka[8], kb[8], va[8], vb[8], cs[16];
+    load8(q, qa); load8(q + half, qb);
+    load8(k, ka); load8(k + half, kb);
+    load8(v, va); load8(v + half, vb);
+    const float *tb = (const float *)(table + (size_t)r * half + c * 8);     // 8 x (cos, sin)
+    load8(tb, cs); load8(tb + 8, cs + 8);
+    float qlo[8], qhi[8], klo[8], khi[8];
 #pragma unroll
-    for (int e2 = 0; e2 < 4; e2++) {
-        f32x4_t cs = tb[e2];                          // (cos, sin) of dims 2*e2 and 2*e2 + 1
-#pragma unroll
-        for (int u = 0; u < 2; u++) {
-            const int e = 2 * e2 + u;
-            const float co = cs[2 * u], si = cs[2 * u + 1];
-            const float a = (float)qa[e], b = (float)qb[e], x = (float)ka[e], y = (float)kb[e];
-            qlo[e] = (bf16_t)(a * co - b * si);
-            qhi[e] = (bf16_t)(b * co + a * si);
-            klo[e] = (bf16_t)(x * co - y * si);
-            khi[e] = (bf16_t)(y * co + x * si);
-        }
+    for (int e = 0; e < 8; e++) {
+        const float co = cs[2 * e], si = cs[2 * e + 1];
+        qlo[e] = qa[e] * co - qb[e] * si;
+        qhi[e] = qb[e] * co + qa[e] * si;
+        klo[e] = ka[e] * co - kb[e] * si;
+        khi[e] = kb[e] * co + ka[e] * si;
     }
-    *(bf16x8_t *)q = qlo;
-    *(bf16x8_t *)(q + half) = qhi;
+    bf16_t *qo = q_out + m * (size_t)H + (size_t)h * d + c * 8;
+    *(bf16x8_t *)qo = pack8(qlo);
+    *(bf16x8_t *)(qo + half) = pack8(qhi);
     const size_t head = (size_t)s * n_heads + h;
-    *(bf16x8_t *)(kc + ((head * (d >> 3) + c) * pos_stride + pos) * 8) = klo;
-    *(bf16x8_t *)(kc + ((head * (d >> 3) + (half >> 3) + c) * pos_stride + pos) * 8) = khi;
+    *(bf16x8_t *)(kc + ((head * (d >> 3) + c) * pos_stride + pos) * 8) = pack8(klo);
+    *(bf16x8_t *)(kc + ((head * (d >> 3) + (half >> 3) + c) * pos_stride + pos) * 8) = pack8(khi);
     bf16_t *vdst = vc + (head * pos_stride + pos) * d + c * 8;
-    *(bf16x8_t *)vdst = va;
-    *(bf16x8_t *)(vdst + half) = vb;
+    *(bf16x8_t *)vdst = pack8(va);
+    *(bf16x8_t *)(vdst + half) = pack8(vb);
+}
+
+// RMSNorm to bf16 with the row held in registers: H = 1024 * V4 floats, 256 threads, each thread owns
+// V4 float4 pieces (piece j covers elements 4 * (j * 256 + t) ..): one read of x, one write of the output.
+template <int V4>
+__global__ void __launch_bounds__(256) rmsnorm_bf16_kernel(bf16_t *out, const float *X, const float *gain, int H,
+                                                          float eps) {
+    __shared__ float red[4];
+    const int t = threadIdx.x;
+    const f32x4_t *x = (const f32x4_t *)(X + (size_t)blockIdx.x * H);
+    f32x4_t v[V4];
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < V4; j++) {
+        v[j] = x[j * 256 + t];
+#pragma unroll
+        for (int e = 0; e < 4; e++) ss += v[j][e] * v[j][e];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    if ((t & 63) == 0) red[t >> 6] = ss;
+    __syncthreads();
+    ss = red[0] + red[1] + red[2] + red[3];
+    const float r = 1.0f / sqrtf(ss / (float)H + eps);
+    const f32x4_t *g = (const f32x4_t *)gain;
+    bf16x4_t *o = (bf16x4_t *)(out + (size_t)blockIdx.x * H);
+#pragma unroll
+    for (int j = 0; j < V4; j++) {
+        f32x4_t gg = g[j * 256 + t];
+        bf16x4_t w;
+#pragma unroll
+        for (int e = 0; e < 4; e++) w[e] = (bf16_t)(v[j][e] * r * gg[e]);
+        o[j * 256 + t] = w;
+    }
 }
 
 }  // namespace
 
-int launch_rope_kv_write_bf16(bf16_t *qkv, const float2 *table, const KvView &kv, int layer, const RowsArgs &ra,
-                              int H, hipStream_t st) {
+// Returns 1 if handled (H a multiple of 1024, at most 8192), 0 otherwise.
+int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int H, float eps, hipStream_t st) {
+    if (H % 1024 != 0 || H > 8192) return 0;
+    if (M == 0) return 1;
+    ProfScope ps("rmsnorm", (double)M * H * 6.0, st);
+    switch (H / 1024) {
+        case 1: rmsnorm_bf16_kernel<1><<<M, 256, 0, st>>>(out, X, gain, H, eps); break;
+        case 2: rmsnorm_bf16_kernel<2><<<M, 256, 0, st>>>(out, X, gain, H, eps); break;
+        case 3: rmsnorm_bf16_kernel<3><<<M, 256, 0, st>>>(out, X, gain, H, eps); break;
+        case 4: rmsnorm_bf16_kernel<4><<<M, 256, 0, st>>>(out, X, gain, H, eps); break;
+        case 5: rmsnorm_bf16_kernel<5><<<M, 256, 0, st>>>(out, X, gain, H, eps); break;
+        case 6: rmsnorm_bf16_kernel<6><<<M, 256, 0, st>>>(out, X, gain, H, eps); break;
+        case 7: rmsnorm_bf16_kernel<7><<<M, 256, 0, st>>>(out, X, gain, H, eps); break;
+        default: rmsnorm_bf16_kernel<8><<<M, 256, 0, st>>>(out, X, gain, H, eps); break;
+    }
+    int rc = vla_check_launch("rmsnorm_bf16");
+    return rc ? rc : 1;
+}
+
+int launch_rope_kv_write_bf16(bf16_t *q_out, const float *qkv, const float2 *table, const KvView &kv, int layer,
+                              const RowsArgs &ra, int H, hipStream_t st) {
     const size_t total = (size_t)ra.n_seq * ra.R * kv.n_heads * (kv.d / 16);
     if (total == 0) return 0;
-    ProfScope ps("rope_kv_write", (double)ra.n_seq * ra.R * H * 5 * 2.0, st);
+    ProfScope ps("rope_kv_write", (double)ra.n_seq * ra.R * H * (3 * 4.0 + 3 * 2.0), st);
     bf16_t *kc = (bf16_t *)kv.k + (size_t)layer * kv.layer_elems;
     bf16_t *vc = (bf16_t *)kv.v + (size_t)layer * kv.layer_elems;
-    rope_kv_write_bf16_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(qkv, table, kc, vc, total, ra.R, ra.pos0,
+    rope_kv_write_bf16_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(q_out, qkv, table, kc, vc, total, ra.R, ra.pos0,
                                                                               kv.n_heads, kv.d, kv.pos_stride, H);
     return vla_check_launch("rope_kv_write_bf16");
 }

@@ -13,7 +13,7 @@
 // Global loads are 16 bytes per lane and write LDS linearly (lane t -> 16 * t), the swizzle being
 // applied on the global side.
 //
-// Epilogues: store bf16; add into the fp32 residual stream; SwiGLU (tile rows interleave 64 gate and
+// Epilogues: store fp32 (QKV, rounded only after the rotation); add into the fp32 residual stream; SwiGLU (tile rows interleave 64 gate and
 // 64 up rows per wave so that silu(gate) * up pairs two accumulators of the same lane).
 #include <stdlib.h>
 
@@ -242,15 +242,15 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
                     *dst = v;
                 }
         } else {
-            bf16_t *out = (bf16_t *)p.C + (size_t)m * p.N + tn * BN + wn * 128;
+            float *out = (float *)p.C + (size_t)m * p.N + tn * BN + wn * 128;
 #pragma unroll
             for (int j = 0; j < 4; j++)
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
-                    bf16x4_t o;
+                    f32x4_t v;
 #pragma unroll
-                    for (int e = 0; e < 4; e++) o[e] = (bf16_t)acc[j][i][g * 4 + e];
-                    *(bf16x4_t *)(out + j * 32 + g * 8 + nquad) = o;
+                    for (int e = 0; e < 4; e++) v[e] = acc[j][i][g * 4 + e];
+                    *(f32x4_t *)(out + j * 32 + g * 8 + nquad) = v;
                 }
         }
     }

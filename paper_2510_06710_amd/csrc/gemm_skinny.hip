@@ -179,13 +179,13 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(SkinnyParams p) {
                 *dst = v;
             }
         } else {
-            bf16_t *out = (bf16_t *)p.C + (size_t)m * p.N + n_out;
+            float *out = (float *)p.C + (size_t)m * p.N + n_out;
 #pragma unroll
             for (int g = 0; g < 4; g++) {
-                bf16x4_t o;
+                f32x4_t v;
 #pragma unroll
-                for (int e = 0; e < 4; e++) o[e] = (bf16_t)acc[0][i][g * 4 + e];
-                *(bf16x4_t *)(out + g * 8 + nquad) = o;
+                for (int e = 0; e < 4; e++) v[e] = acc[0][i][g * 4 + e];
+                *(f32x4_t *)(out + g * 8 + nquad) = v;
             }
         }
     }
@@ -219,12 +219,13 @@ __global__ void skinny_reduce_kernel(void *C, const float *P, int splits, int M,
 #pragma unroll
         for (int e = 0; e < 4; e++) v[e] += s[e];
         *dst = v;
-    } else {
+    } else if (EPI == EPI_SWIGLU) {
         bf16x4_t o;
 #pragma unroll
-        for (int e = 0; e < 4; e++)
-            o[e] = (bf16_t)(EPI == EPI_SWIGLU ? s[e] / (1.0f + __expf(-s[e])) * u[e] : s[e]);
+        for (int e = 0; e < 4; e++) o[e] = (bf16_t)(s[e] / (1.0f + __expf(-s[e])) * u[e]);
         *(bf16x4_t *)((bf16_t *)C + i) = o;
+    } else {
+        *(f32x4_t *)((float *)C + i) = s;
     }
 }
 

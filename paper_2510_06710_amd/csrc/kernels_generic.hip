@@ -171,7 +171,7 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(const T *A, const T *
                 float g = acc[i][j];
                 ((T *)Cv)[o] = from_f<T>(g / (1.0f + expf(-g)) * acu[i][j]);
             } else {
-                ((T *)Cv)[o] = from_f<T>(acc[i][j]);
+                ((float *)Cv)[o] = acc[i][j];
             }
         }
     }
@@ -189,12 +189,12 @@ __global__ void rope_table_kernel(float2 *table, int R, int pos0, int d, float t
     table[idx] = make_float2((float)cos(phi), (float)sin(phi));
 }
 
-// Rotate q and k of every new row (pairs (i, i + d/2)), leave q in place inside the QKV buffer,
-// write k and v into the KV layout.  One thread per (row, head, 8-dim chunk c of the first half):
-// it owns dims [8c, 8c+8) and [d/2 + 8c, d/2 + 8c + 8).
+// Rotate q and k of every new row (pairs (i, i + d/2)) from the fp32 QKV projection, write q to its
+// own [M, H] buffer and k, v into the KV layout.  One thread per (row, head, 8-dim chunk c of the first
+// half): it owns dims [8c, 8c+8) and [d/2 + 8c, d/2 + 8c + 8).
 template <typename T>
-__global__ void rope_kv_write_kernel(T *qkv, const float2 *table, T *kc, T *vc, int n_seq, int R, int pos0,
-                                     int n_heads, int d, int pos_stride, int H) {
+__global__ void rope_kv_write_kernel(T *q_out, const float *qkv, const float2 *table, T *kc, T *vc, int n_seq,
+                                     int R, int pos0, int n_heads, int d, int pos_stride, int H) {
     int chunks = d / 16;
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t total = (size_t)n_seq * R * n_heads * chunks;
@@ -205,9 +205,10 @@ __global__ void rope_kv_write_kernel(T *qkv, const float2 *table, T *kc, T *vc, 
     int s = m / R, r = m % R;
     int pos = pos0 + r;
     int half = d / 2;
-    T *q = qkv + m * 3 * (size_t)H + (size_t)h * d;
-    T *k = q + H;
-    T *v = q + 2 * (size_t)H;
+    const float *q = qkv + m * 3 * (size_t)H + (size_t)h * d;
+    const float *k = q + H;
+    const float *v = q + 2 * (size_t)H;
+    T *qo = q_out + m * (size_t)H + (size_t)h * d;
     size_t head = (size_t)s * n_heads + h;
     T *kdst_lo = kc + ((head * (d / 8) + c) * pos_stride + pos) * 8;
     T *kdst_hi = kc + ((head * (d / 8) + (half / 8) + c) * pos_stride + pos) * 8;
@@ -216,14 +217,14 @@ __global__ void rope_kv_write_kernel(T *qkv, const float2 *table, T *kc, T *vc, 
     for (int e = 0; e < 8; e++) {
         int i = c * 8 + e;
         float2 cs = table[(size_t)r * half + i];
-        float qa = to_f(q[i]), qb = to_f(q[i + half]);
-        float ka = to_f(k[i]), kb = to_f(k[i + half]);
-        q[i] = from_f<T>(qa * cs.x - qb * cs.y);
-        q[i + half] = from_f<T>(qb * cs.x + qa * cs.y);
+        float qa = q[i], qb = q[i + half];
+        float ka = k[i], kb = k[i + half];
+        qo[i] = from_f<T>(qa * cs.x - qb * cs.y);
+        qo[i + half] = from_f<T>(qb * cs.x + qa * cs.y);
         kdst_lo[e] = from_f<T>(ka * cs.x - kb * cs.y);
         kdst_hi[e] = from_f<T>(kb * cs.x + ka * cs.y);
-        vdst[i] = v[i];
-        vdst[i + half] = v[i + half];
+        vdst[i] = from_f<T>(v[i]);
+        vdst[i + half] = from_f<T>(v[i + half]);
     }
 }
 
@@ -231,7 +232,7 @@ __global__ void rope_kv_write_kernel(T *qkv, const float2 *table, T *kc, T *vc, 
 // One wave per (sequence, head, new row): scores over the allowed keys into LDS, softmax, then
 // the weighted sum of V rows with each lane owning head dims lane, lane+64, ...
 template <typename T>
-__global__ void __launch_bounds__(256) attention_generic_kernel(T *out, const T *qkv, const T *kc,
+__global__ void __launch_bounds__(256) attention_generic_kernel(T *out, const T *qbuf, const T *kc,
                                                                const T *vc, int n_seq, int R, int pos0,
                                                                int full_from, int n_heads, int d,
                                                                int pos_stride, int H) {
@@ -249,7 +250,7 @@ __global__ void __launch_bounds__(256) attention_generic_kernel(T *out, const T 
     size_t m = (size_t)s * R + r;
     int pos = pos0 + r;
     int nk = (pos >= full_from) ? (pos0 + R) : (pos + 1);
-    const T *q = qkv + m * 3 * (size_t)H + (size_t)h * d;
+    const T *q = qbuf + m * (size_t)H + (size_t)h * d;
     for (int i = lane; i < d; i += 64) qs[i] = to_f(q[i]);
     __builtin_amdgcn_wave_barrier();
     size_t head = (size_t)s * n_heads + h;
@@ -446,19 +447,19 @@ int launch_rope_table(float2 *table, int R, int pos0, int d, float theta, hipStr
     return vla_check_launch("rope_table");
 }
 template <typename T>
-int launch_rope_kv_write(T *qkv, const float2 *table, const KvView &kv, int layer, const RowsArgs &ra,
-                         int H, hipStream_t st) {
+int launch_rope_kv_write(T *q_out, const float *qkv, const float2 *table, const KvView &kv, int layer,
+                         const RowsArgs &ra, int H, hipStream_t st) {
     ProfScope ps("rope_kv_write", (double)ra.n_seq * ra.R * H * 5 * sizeof(T), st);
     size_t total = (size_t)ra.n_seq * ra.R * kv.n_heads * (kv.d / 16);
     if (total == 0) return 0;
     T *kc = (T *)kv.k + (size_t)layer * kv.layer_elems;
     T *vc = (T *)kv.v + (size_t)layer * kv.layer_elems;
     rope_kv_write_kernel<T><<<(unsigned)((total + 255) / 256), 256, 0, st>>>(
-        qkv, table, kc, vc, ra.n_seq, ra.R, ra.pos0, kv.n_heads, kv.d, kv.pos_stride, H);
+        q_out, qkv, table, kc, vc, ra.n_seq, ra.R, ra.pos0, kv.n_heads, kv.d, kv.pos_stride, H);
     return vla_check_launch("rope_kv_write");
 }
 template <typename T>
-int launch_attention_generic(T *out, const T *qkv, const KvView &kv, int layer, const RowsArgs &ra,
+int launch_attention_generic(T *out, const T *q, const KvView &kv, int layer, const RowsArgs &ra,
                              int H, hipStream_t st) {
     ProfScope ps("attention_generic", 0.0, st);
     size_t total = (size_t)ra.n_seq * kv.n_heads * ra.R;
@@ -467,7 +468,7 @@ int launch_attention_generic(T *out, const T *qkv, const KvView &kv, int layer, 
     const T *vc = (const T *)kv.v + (size_t)layer * kv.layer_elems;
     size_t lds = (size_t)4 * (kv.pos_stride + kv.d) * sizeof(float);
     attention_generic_kernel<T><<<(unsigned)((total + 3) / 4), 256, lds, st>>>(
-        out, qkv, kc, vc, ra.n_seq, ra.R, ra.pos0, ra.full_from, kv.n_heads, kv.d, kv.pos_stride, H);
+        out, q, kc, vc, ra.n_seq, ra.R, ra.pos0, ra.full_from, kv.n_heads, kv.d, kv.pos_stride, H);
     return vla_check_launch("attention_generic");
 }
 template <typename T>
@@ -499,8 +500,8 @@ int launch_value_head(float *value, const float *h, const float *w, float b, int
     template int launch_embed_slots<T>(float *, const T *, int, int, int, int, int, hipStream_t);             \
     template int launch_rmsnorm<T>(T *, const float *, const float *, int, int, float, hipStream_t);          \
     template int launch_gemm_generic<T>(const GemmArgs &, hipStream_t);                                       \
-    template int launch_rope_kv_write<T>(T *, const float2 *, const KvView &, int, const RowsArgs &, int,     \
-                                         hipStream_t);                                                        \
+    template int launch_rope_kv_write<T>(T *, const float *, const float2 *, const KvView &, int,             \
+                                         const RowsArgs &, int, hipStream_t);                                                        \
     template int launch_attention_generic<T>(T *, const T *, const KvView &, int, const RowsArgs &, int,      \
                                              hipStream_t);                                                    \
     template int launch_head_sample<T>(const float *, const T *, int, int, float, const float *,              \

@@ -37,7 +37,7 @@ struct GemmArgs {
     const void *A;          // [M, K] row-major (lda = K), storage dtype (or fp32 for fp32 models)
     const void *W[3];       // up to three weight segments, each [segN, K] row-major
     int n_seg, segN;        // N = n_seg * segN (EPI_SWIGLU: W[0] = gate, W[1] = up, N = segN)
-    void *C;                // EPI_STORE / EPI_SWIGLU: storage dtype [M, N]; EPI_RESIDUAL: fp32 [M, N] +=
+    void *C;                // EPI_STORE: fp32 [M, N]; EPI_SWIGLU: storage dtype [M, N]; EPI_RESIDUAL: fp32 [M, N] +=
     int M, K;
     int epilogue;
 };
@@ -59,11 +59,13 @@ int launch_final_norm_rows(float *out, const float *X, const float *gain, int n_
 template <typename T>
 int launch_gemm_generic(const GemmArgs &g, hipStream_t st);
 int launch_rope_table(float2 *table, int R, int pos0, int d, float theta, hipStream_t st);
+// qkv is the fp32 [M, 3H] output of the QKV projection (never rounded before the rotation); the
+// rotated q goes to q_out [M, H] in the storage dtype, k and v to the KV layout.
 template <typename T>
-int launch_rope_kv_write(T *qkv, const float2 *table, const KvView &kv, int layer, const RowsArgs &ra,
-                         int H, hipStream_t st);
+int launch_rope_kv_write(T *q_out, const float *qkv, const float2 *table, const KvView &kv, int layer,
+                         const RowsArgs &ra, int H, hipStream_t st);
 template <typename T>
-int launch_attention_generic(T *out, const T *qkv, const KvView &kv, int layer, const RowsArgs &ra,
+int launch_attention_generic(T *out, const T *q, const KvView &kv, int layer, const RowsArgs &ra,
                              int H, hipStream_t st);
 // Row i of h produces output index o = i * out_stride + out_off: bins_out[o], logp[o], ent[o],
 // logits[o * 256 ..]; it reads gumbel[o * 256 ..] (if any) and given_bins[o] (if any: then the
@@ -80,13 +82,14 @@ int launch_value_head(float *value, const float *h, const float *w, float b, int
 // ---- gfx950 fast paths (bf16, aligned shapes); each returns 1 if it handled the call, 0 if the
 // shape is outside what it supports (caller then uses the generic kernel), <0 on launch error ----
 int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st);
-int launch_rope_kv_write_bf16(bf16_t *qkv, const float2 *table, const KvView &kv, int layer, const RowsArgs &ra,
-                              int H, hipStream_t st);
+int launch_rope_kv_write_bf16(bf16_t *q_out, const float *qkv, const float2 *table, const KvView &kv, int layer,
+                              const RowsArgs &ra, int H, hipStream_t st);
+int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int H, float eps, hipStream_t st);
 int try_gemm_bf16_skinny(const GemmArgs &g, void *scratch, hipStream_t st);
 size_t gemm_skinny_scratch_bytes(int M, int max_n);
-int try_attention_prefill_bf16(bf16_t *out, const bf16_t *qkv, const KvView &kv, int layer,
+int try_attention_prefill_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, int layer,
                                const RowsArgs &ra, int H, void *vt_scratch, hipStream_t st);
-int try_attention_decode_bf16(bf16_t *out, const bf16_t *qkv, const KvView &kv, int layer,
+int try_attention_decode_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, int layer,
                               const RowsArgs &ra, int H, hipStream_t st);
 size_t attention_prefill_scratch_bytes(int n_seq, int n_heads, int d, int n_keys);
 

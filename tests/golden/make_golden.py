@@ -1,8 +1,10 @@
-"""Writes tests/golden/oracle_7b.npz: oracle outputs for a few sampled environments / rollouts of
-the 7B-shape workloads (all 32 layers).  Calls only vla_inputs and oracle/; takes 10-20 minutes
-on 8 cores and about 20 GB of host memory.  Run from the repository root:
+"""Writes tests/golden/oracle_7b.npz (exact fp64 intermediates) or, with ``--operands bf16``,
+tests/golden/oracle_7b_bf16ops.npz (stored tensors rounded to bf16, see oracle/vla_oracle.py):
+oracle outputs for a few sampled environments / rollouts of the 7B-shape workloads (all 32 layers).
+Calls only vla_inputs and oracle/; takes 30-45 minutes on 8 cores and about 20 GB of host memory.
+Run from the repository root:
 
-    python tests/golden/make_golden.py
+    python tests/golden/make_golden.py [--operands bf16]
 
 The environments of the cfg2 (64 envs) and cfg3 (256 envs) workloads share their inputs (every
 tensor is indexed by environment), so one set of rollouts serves both."""
@@ -27,30 +29,35 @@ RC_ROLLOUTS = [0, 300]          # cfg5: 512 stored rollouts
 
 
 def main():
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--operands", default="exact", choices=["exact", "bf16"])
+    mode = ap.parse_args().operands
     t0 = time.time()
     w = oracle_weights(vi.SynthModel(vi.SHAPE_7B, SEED), vi.VALUE_BIAS)
     out = {"seed": np.array(SEED)}
     wl3 = vi.WORKLOADS["cfg3_7b_b256"]
     for e in AR_ENVS:
-        r = oracle_rollout(wl3, SEED, env0=e, envs=1, weights=w)
+        r = oracle_rollout(wl3, SEED, env0=e, envs=1, weights=w, operand_dtype=mode)
         for k, v in r.items():
             out[f"ar_{e}_{k}"] = v
         print(f"AR env {e} done at {time.time() - t0:.0f}s bins={r['bins']}", flush=True)
     wl4 = vi.WORKLOADS["cfg4_7b_oft_b128"]
     for e in OFT_ENVS:
-        r = oracle_rollout(wl4, SEED, env0=e, envs=1, sampled=False, weights=w)
+        r = oracle_rollout(wl4, SEED, env0=e, envs=1, sampled=False, weights=w, operand_dtype=mode)
         for k, v in r.items():
             out[f"oft_{e}_{k}"] = v
         print(f"OFT env {e} done at {time.time() - t0:.0f}s", flush=True)
     wl5 = vi.WORKLOADS["cfg5_7b_recompute_n512"]
     for e in RC_ROLLOUTS:
         bins = vi.stored_bins(wl5, SEED, env0=e, envs=1).numpy()
-        r = oracle_recompute(wl5, SEED, bins, env0=e, envs=1, weights=w)
+        r = oracle_recompute(wl5, SEED, bins, env0=e, envs=1, weights=w, operand_dtype=mode)
         out[f"rc_{e}_bins"] = bins
         for k, v in r.items():
             out[f"rc_{e}_{k}"] = v
         print(f"recompute rollout {e} done at {time.time() - t0:.0f}s", flush=True)
-    np.savez_compressed(os.path.join(ROOT, "tests", "golden", "oracle_7b.npz"), **out)
+    name = "oracle_7b.npz" if mode == "exact" else "oracle_7b_bf16ops.npz"
+    np.savez_compressed(os.path.join(ROOT, "tests", "golden", name), **out)
     print("written", flush=True)
 
 

@@ -48,9 +48,20 @@ def test_ragged_shapes_rollout(dtype, tau):
 @pytest.mark.parametrize("B", [5, 70, 130])
 def test_aligned_bf16_rollout_fast_kernels(B):
     wl = vi.scaled(ALIGNED, batch=B)
-    ref = oracle_rollout(wl, 10)
     gpu = GpuCase(wl, 10).rollout()
-    _print(f"aligned bf16 B={B}", compare_rollout(gpu, ref, "bf16", autoregressive=True))
+    for mode in ("bf16", "exact"):      # oracle on the same bf16-stored tensors, and the exact one
+        ref = oracle_rollout(wl, 10, operand_dtype=mode)
+        _print(f"aligned bf16 B={B} vs {mode} oracle", compare_rollout(gpu, ref, "bf16", autoregressive=True))
+
+
+def test_hidden_1024_bf16_register_resident_norm():
+    """hidden = 1024 takes the vectorised RMSNorm (rows held in registers) as the 7B shape does."""
+    wl = vi.Workload("h1024", vi.ModelShape(n_layers=2, hidden=1024, n_heads=8, ffn=1024, vocab=512, dtype="bf16"),
+                     batch=3, n_patches=20, n_instr=5, n_action=3)
+    gpu = GpuCase(wl, 12).rollout()
+    for mode in ("bf16", "exact"):
+        ref = oracle_rollout(wl, 12, operand_dtype=mode)
+        _print(f"hidden 1024 bf16 vs {mode} oracle", compare_rollout(gpu, ref, "bf16", autoregressive=True))
 
 
 def test_aligned_bf16_chunk_and_recompute_fast_kernels():

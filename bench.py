@@ -53,7 +53,7 @@ def read_traffic(path, kernel):
         return None
 
 
-def cpu_baseline(wl, vi, sample_layers=2):
+def cpu_baseline(wl, vi, sample_layers=8):
     """The CPU oracle as it stands, on 1 environment x `sample_layers` of the model's layers
     (prefill + decode), scaled linearly to all layers; the head and embedding cost is negligible."""
     import numpy as np
@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg3_7b_b256")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one 1 GiB plain copy kernel (reference for rocprofv3 --pmc traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (environments shard "
@@ -122,6 +124,13 @@ def main():
     def step():
         h_last, _ = prefill()
         return decode(h_last)
+
+    if args.calibration_copy:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        vb.vla_calibration_copy(a, b, 1 << 30, stream)
+        torch.cuda.synchronize()
+        del a, b
 
     for _ in range(args.warmup):
         step()

@@ -180,6 +180,11 @@ int vla_logprob_recompute(vla_model *model, void *ws, size_t ws_bytes,
 int vla_profile_enable(int on);
 int vla_profile_report(char *buf, size_t n);
 
+/* Calibration aid for hardware-counter runs: a plain copy kernel (`bytes` must be a multiple of 16;
+ * dst, src DEVICE, 16-byte aligned) that reads and writes exactly `bytes` bytes, so that HBM
+ * traffic counters collected around the hot kernels can be scaled by what they read for it. */
+int vla_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -66,6 +66,9 @@ def lib() -> C.CDLL:
         L.vla_decode_actions.argtypes = [vp, vp, vp, sz, vp, i32, i32, i32, i32, vp, f32, vp, vp, vp, vp, vp, vp]
         L.vla_logprob_recompute.argtypes = [vp, vp, sz, vp, vp, vp, i32, i32, i32, i32, i32, vp, f32,
                                             vp, vp, vp, vp, vp]
+        L.vla_profile_enable.argtypes = [i32]
+        L.vla_profile_report.argtypes = [C.c_char_p, sz]
+        L.vla_calibration_copy.argtypes = [vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -138,6 +141,10 @@ def vla_logprob_recompute(model, ws, patch, ids, bins, N, P, T, A, mode, slot_em
                                        _ptr(ids), _ptr(bins), N, P, T, A, mode, _ptr(slot_embed),
                                        temperature, _ptr(logp), _ptr(entropy), _ptr(value),
                                        _ptr(logits), _stream(stream)))
+
+
+def vla_calibration_copy(dst, src, nbytes: int, stream=None) -> None:
+    _check(lib().vla_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
 
 
 def make_config(shape, max_batch: int, max_seq: int) -> vla_config:

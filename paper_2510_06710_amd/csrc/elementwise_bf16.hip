@@ -92,7 +92,17 @@ __global__ void __launch_bounds__(256) rmsnorm_bf16_kernel(bf16_t *out, const fl
     }
 }
 
+__global__ void __launch_bounds__(256) calibration_copy_kernel(f32x4_t *dst, const f32x4_t *src, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 }  // namespace
+
+extern "C" int vla_calibration_copy(void *dst, const void *src, size_t bytes, void *stream) {
+    if (!dst || !src || bytes == 0 || bytes % 16 != 0) { vla_set_error("calibration copy: NULL pointer or size not a multiple of 16"); return VLA_EINVAL; }
+    calibration_copy_kernel<<<4096, 256, 0, (hipStream_t)stream>>>((f32x4_t *)dst, (const f32x4_t *)src, bytes / 16);
+    return vla_check_launch("calibration_copy");
+}
 
 // Returns 1 if handled (H a multiple of 1024, at most 8192), 0 otherwise.
 int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int H, float eps, hipStream_t st) {

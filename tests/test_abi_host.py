@@ -22,7 +22,8 @@ def test_library_exports_every_declared_symbol():
     L = vb.lib()
     names = header_symbols()
     assert {"vla_prefill", "vla_decode_actions", "vla_logprob_recompute", "vla_create", "vla_destroy",
-            "vla_kv_bytes", "vla_workspace_bytes", "vla_last_error", "vla_version"} <= set(names)
+            "vla_kv_bytes", "vla_workspace_bytes", "vla_last_error", "vla_version", "vla_profile_enable",
+            "vla_profile_report", "vla_calibration_copy"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
     assert vb.vla_version() == 1

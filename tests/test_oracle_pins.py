@@ -76,20 +76,31 @@ def _rope(u, pos, theta):
     return out
 
 
-def brute_rows(cfg, w, rows, positions, allowed):
-    """rows: list of H-vectors (python lists); allowed[r][c] bool.  Returns residual rows."""
+def bf16_scalar(x):
+    """Round one Python float to bfloat16 (nearest, ties to even) through its fp32 bit pattern."""
+    import struct
+    (u,) = struct.unpack("<I", struct.pack("<f", x))
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return struct.unpack("<f", struct.pack("<I", u))[0]
+
+
+def brute_rows(cfg, w, rows, positions, allowed, rnd=None):
+    """rows: list of H-vectors (python lists); allowed[r][c] bool.  Returns residual rows.
+    rnd: optional scalar rounding applied to the stored tensors (norm outputs, rotated q, k, v,
+    attention output, SwiGLU output)."""
     H, nh, d = cfg.hidden, cfg.n_heads, cfg.head_dim
+    st = (lambda v: [rnd(t) for t in v]) if rnd else (lambda v: v)
     x = [list(r) for r in rows]
     R = len(x)
     for l in range(cfg.n_layers):
         lw = {k: v.tolist() for k, v in w.layer(l).items()}
         q, k, v = [], [], []
         for r in range(R):
-            n = _norm(x[r], lw["attn_norm"], cfg.rms_eps)
+            n = st(_norm(x[r], lw["attn_norm"], cfg.rms_eps))
             qr, kr, vr = _matvec(lw["wq"], n), _matvec(lw["wk"], n), _matvec(lw["wv"], n)
-            q.append([_rope(qr[h * d:(h + 1) * d], positions[r], cfg.rope_theta) for h in range(nh)])
-            k.append([_rope(kr[h * d:(h + 1) * d], positions[r], cfg.rope_theta) for h in range(nh)])
-            v.append([vr[h * d:(h + 1) * d] for h in range(nh)])
+            q.append([st(_rope(qr[h * d:(h + 1) * d], positions[r], cfg.rope_theta)) for h in range(nh)])
+            k.append([st(_rope(kr[h * d:(h + 1) * d], positions[r], cfg.rope_theta)) for h in range(nh)])
+            v.append([st(vr[h * d:(h + 1) * d]) for h in range(nh)])
         for r in range(R):
             o = []
             for h in range(nh):
@@ -103,12 +114,12 @@ def brute_rows(cfg, w, rows, positions, allowed):
                     for i in range(d):
                         acc[i] += pc / z * v[c][h][i]
                 o.extend(acc)
-            att = _matvec(lw["wo"], o)
+            att = _matvec(lw["wo"], st(o))
             x[r] = [a + b for a, b in zip(x[r], att)]
         for r in range(R):
-            n = _norm(x[r], lw["ffn_norm"], cfg.rms_eps)
+            n = st(_norm(x[r], lw["ffn_norm"], cfg.rms_eps))
             g, u = _matvec(lw["w_gate"], n), _matvec(lw["w_up"], n)
-            act = [gi / (1.0 + math.exp(-gi)) * ui for gi, ui in zip(g, u)]
+            act = st([gi / (1.0 + math.exp(-gi)) * ui for gi, ui in zip(g, u)])
             dn = _matvec(lw["w_down"], act)
             x[r] = [a + b for a, b in zip(x[r], dn)]
     return x
@@ -126,7 +137,7 @@ def brute_head(cfg, w, xrow, tau):
     return h, z, y, logp, ent
 
 
-def brute_rollout_ar(cfg, w, patch_b, ids_b, A, tau, g_b):
+def brute_rollout_ar(cfg, w, patch_b, ids_b, A, tau, g_b, rnd=None):
     """One environment, autoregressive, every token recomputed from scratch."""
     S = patch_b.shape[0] + ids_b.shape[0]
     rows = [r.tolist() for r in patch_b] + [w.embed[i].tolist() for i in ids_b]
@@ -134,7 +145,7 @@ def brute_rollout_ar(cfg, w, patch_b, ids_b, A, tau, g_b):
     for j in range(A):
         R = len(rows)
         allowed = [[c <= r for c in range(R)] for r in range(R)]
-        x = brute_rows(cfg, w, rows, list(range(R)), allowed)
+        x = brute_rows(cfg, w, rows, list(range(R)), allowed, rnd)
         _, z, y, logp, ent = brute_head(cfg, w, x[-1], tau)
         t = [np.float32(yv) + (np.float32(g_b[j][k]) if g_b is not None else np.float32(0))
              for k, yv in enumerate(y)]
@@ -162,6 +173,39 @@ def test_cached_rollout_matches_scalar_brute_force(tau, sampled):
             assert np.max(np.abs(logits[b, j] - np.array(rz))) < 1e-10
     # attention must not be near uniform for this to pin anything: logits spread out
     assert np.std(logits) > 0.3
+
+
+def test_round_bf16_against_torch_and_known_values():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(50_000) * np.exp(rng.uniform(-30, 30, 50_000))
+    assert np.array_equal(vo.round_bf16(x), torch.from_numpy(x).float().bfloat16().double().numpy())
+    assert np.array_equal(vo.round_bf16(x[:200]), np.array([bf16_scalar(v) for v in x[:200]]))
+    # ties to even at the 8-bit mantissa: 1 + 2^-8 -> 1, 1 + 3*2^-8 -> 1 + 2^-6, just above a tie -> up
+    assert vo.round_bf16(np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -20])).tolist() == \
+        [1.0, 1.015625, 1.0078125]
+    assert vo.round_bf16(np.array([0.0, -2.5, 3.140625])).tolist() == [0.0, -2.5, 3.140625]
+
+
+def test_bf16_stored_mode_matches_scalar_brute_force_with_the_same_roundings():
+    """The "bf16" operand mode rounds exactly the stored tensors: norm outputs, rotated q, k, v,
+    attention output, SwiGLU output -- and nothing else."""
+    wl = small_workload(B=2, P=3, T=2, A=3)
+    cfg, w, patch, ids = setup(wl, seed=3, sigma_boost=12.0)
+    cfg.operand_dtype = "bf16"
+    g = to_f64(vi.gumbel_noise(wl, 3))
+    kv, h_last, _ = vo.ovla_prefill(cfg, w, patch, ids)
+    bins, logp, ent, logits, _ = vo.ovla_decode_actions(cfg, w, kv, h_last, wl.prefix, wl.n_action, gumbel=g)
+    exact_cfg = oracle_config(wl.shape)
+    _, h_exact, _ = vo.ovla_prefill(exact_cfg, w, patch, ids)
+    assert 1e-4 < np.max(np.abs(h_exact - h_last)) < 0.2          # the mode does change the result
+    for b in range(wl.batch):
+        ref = brute_rollout_ar(cfg, w, patch[b], ids[b], wl.n_action, 1.0, g[b], rnd=bf16_scalar)
+        for j, (rb, rlp, rent, rz) in enumerate(ref):
+            assert bins[b, j] == rb
+            assert abs(logp[b, j] - rlp) < 1e-9 and abs(ent[b, j] - rent) < 1e-9
+            assert np.max(np.abs(logits[b, j] - np.array(rz))) < 1e-9
+    lp2, ent2, _, z2 = vo.ovla_logprob_recompute(cfg, w, patch, ids, bins, wl.n_action)
+    assert np.max(np.abs(z2 - logits)) < 1e-9 and np.max(np.abs(lp2 - logp)) < 1e-9
 
 
 def test_parallel_chunk_matches_scalar_brute_force_with_explicit_mask():

@@ -186,10 +186,21 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
         GemmArgs g{};
         g.A = ws.Nrm; g.W[0] = lw.wq; g.W[1] = lw.wk; g.W[2] = lw.wv; g.n_seg = 3; g.segN = H;
         g.C = ws.QKV; g.M = M; g.K = H; g.epilogue = EPI_STORE;
-        if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
-        if (c.dtype == VLA_DTYPE_BF16 && !(force_generic() & 16)) rc = launch_rope_kv_write_bf16((bf16_t *)ws.Q, ws.QKV, ws.rope, kv, kl, ra, H, st);
-        else rc = launch_rope_kv_write<T>((T *)ws.Q, ws.QKV, ws.rope, kv, kl, ra, H, st);
-        if (rc) return rc;
+        // multi-row bf16 forwards at head_dim 128: rotation and KV write ride the projection's epilogue
+        int fused = 0;
+        if (c.dtype == VLA_DTYPE_BF16 && ra.R > 1 && d == 128 && !(force_generic() & (1 | 16))) {
+            QkvRopeArgs qa{ws.Q, ws.rope, &kv, kl, &ra};
+            GemmArgs gf = g;
+            gf.epilogue = EPI_QKV_ROPE; gf.rope = &qa;
+            fused = try_gemm_bf16_mfma(gf, st);
+            if (fused < 0) return fused;
+        }
+        if (!fused) {
+            if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
+            if (c.dtype == VLA_DTYPE_BF16 && !(force_generic() & 16)) rc = launch_rope_kv_write_bf16((bf16_t *)ws.Q, ws.QKV, ws.rope, kv, kl, ra, H, st);
+            else rc = launch_rope_kv_write<T>((T *)ws.Q, ws.QKV, ws.rope, kv, kl, ra, H, st);
+            if (rc) return rc;
+        }
         int done = 0;
         if (c.dtype == VLA_DTYPE_BF16) {
             if (ra.R == 1)

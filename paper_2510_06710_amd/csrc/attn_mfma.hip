@@ -8,15 +8,17 @@
 //                    exactly the 16-byte (key, 8 dims) unit the row operand wants);
 //   O^T = V^T . P^T (rows = head dims, columns = queries; the accumulator layout of S^T -- a lane
 //                    holds one query column and 16 keys -- is directly the column operand P^T once
-//                    the MFMA's k slots are assigned to those 16 keys; V^T rows come from a
-//                    transposed copy of V [dim][position] written by a small kernel beforehand).
+//                    the MFMA's k slots are assigned to those 16 keys; V^T comes from a transposed,
+//                    blocked copy of V written by a small kernel beforehand).
 // A lane therefore owns a single query for the whole kernel: running max, sum and the rescale of
 // O^T are per-lane scalars, with one lane-xor-32 exchange per key block.
 #include "vla_internal.h"
 
 namespace {
 
-// V [position][d] of the cache -> VT [d][ps_pad] with zeros for positions >= nk.
+// V [position][d] of the cache -> VT [d/32][ps_pad/4][32][4]: for a block of 32 head dims, the four
+// consecutive keys a lane needs are 8 contiguous bytes and the 32 lanes of a half-wave (32 dims) read
+// 256 contiguous bytes.  Positions >= nk are written as zeros.
 template <int D>
 __global__ void __launch_bounds__(256) v_transpose_kernel(bf16_t *vt, const bf16_t *vc, int nk, int pos_stride,
                                                          int ps_pad) {
@@ -35,17 +37,18 @@ __global__ void __launch_bounds__(256) v_transpose_kernel(bf16_t *vt, const bf16
         for (int e = 0; e < 8; e++) tile[r][c * 8 + e] = v[e];
     }
     __syncthreads();
-    for (int q = threadIdx.x; q < D * 4; q += 256) {
-        int dim = q / 4, c = q % 4;
-        bf16x8_t v;
+    const int groups = ps_pad >> 2;
+    for (int q = threadIdx.x; q < D * 8; q += 256) {        // (dim block, key group of this block, dim)
+        int c = q & 31, g = (q >> 5) & 7, b = q >> 8;
+        bf16x4_t v;
 #pragma unroll
-        for (int e = 0; e < 8; e++) v[e] = tile[c * 8 + e][dim];
-        *(bf16x8_t *)(vth + (size_t)dim * ps_pad + kb * 32 + c * 8) = v;
+        for (int e = 0; e < 4; e++) v[e] = tile[g * 4 + e][b * 32 + c];
+        *(bf16x4_t *)(vth + (((size_t)b * groups + kb * 8 + g) * 32 + c) * 4) = v;
     }
 }
 
 template <int D>
-__global__ void __launch_bounds__(256) attn_prefill_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) attn_prefill_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
                                                           const bf16_t *vt, int R, int pos0, int full_from,
                                                           int n_heads, int pos_stride, int ps_pad, int H,
                                                           int q_blocks) {
@@ -129,12 +132,12 @@ __global__ void __launch_bounds__(256) attn_prefill_kernel(bf16_t *out, const bf
         // ---- O^T += V^T . P^T: k slot (hh, e) of product u is key kb*32 + 16u + 8*(e/4) + 4hh + e%4
 #pragma unroll
         for (int u = 0; u < 2; u++) {
-            const int key0 = kb * 32 + 16 * u + 4 * hh;
+            const int g0 = kb * 8 + 4 * u + hh;            // key group (4 keys) of slots e = 0..3
 #pragma unroll
             for (int b = 0; b < DB; b++) {
-                const bf16_t *vrow = vth + (size_t)(b * 32 + col) * ps_pad + key0;
+                const bf16_t *vrow = vth + (((size_t)b * (ps_pad >> 2) + g0) * 32 + col) * 4;
                 bf16x4_t lo = *(const bf16x4_t *)vrow;
-                bf16x4_t hi = *(const bf16x4_t *)(vrow + 8);
+                bf16x4_t hi = *(const bf16x4_t *)(vrow + 2 * 32 * 4);       // two key groups further
                 bf16x8_t vf;
 #pragma unroll
                 for (int e = 0; e < 4; e++) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }

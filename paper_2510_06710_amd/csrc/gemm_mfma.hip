@@ -21,6 +21,12 @@
 
 namespace {
 
+// Timing experiments of the development harness only (wrong results): 2 = no global loads / LDS writes
+// in the K loop, 3 = also no fragment reads, 4 = as 3 without the barrier.  Product builds use 0.
+#ifndef VLA_GEMM_EXPERIMENT
+#define VLA_GEMM_EXPERIMENT 0
+#endif
+
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int TILE_BYTES = BM * BK * 2;     // 32 KB per operand per stage
 
@@ -31,6 +37,11 @@ struct MfmaGemmParams {
     int M, N, K, segN;
     int tiles_m, tiles_n;
     int dbg;
+    int variant;     // 0: register-staged loads, 1: direct-to-LDS four-stage pipeline
+    // EPI_QKV_ROPE
+    bf16_t *q_out, *kc, *vc;
+    const float2 *table;
+    int R, pos0, n_heads, pos_stride, H;
 };
 
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
@@ -51,6 +62,169 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
     int in_panel = lin - panel * GROUP * tiles_n;
     tm = first_m + in_panel % rows;
     tn = in_panel / rows;
+}
+
+// Output of one wave.  A lane holds activation row (lane % 32) of each 32-row block and, per
+// accumulator register r, weight row 8 * (r / 4) + 4 * (lane / 32) + r % 4: written out directly that is
+// 32-byte pieces of 32 different rows per store instruction.  Instead each 32 x 128 block goes through
+// a per-wave LDS panel (row stride 132 floats: the 16 lanes of a quarter-wave hit all 64 banks) and
+// leaves as whole rows: a store (or the load + store of the residual update) covers two 512-byte rows,
+// the bf16 SwiGLU output eight 128-byte rows.
+constexpr int EPI_LD = 132;                               // floats per staged row
+constexpr int EPI_PANEL_BYTES = 32 * EPI_LD * 4;          // 16.5 KB per wave
+
+template <int EPI>
+__device__ __forceinline__ void epilogue(f32x16_t (&acc)[4][4], const MfmaGemmParams &p, int m0, int tn, int wm,
+                                         int wn, int lane, char *lds_all) {
+    float *panel = (float *)(lds_all + (wm * 2 + wn) * EPI_PANEL_BYTES);
+    const int r = lane & 31, hh = lane >> 5;
+    if (EPI == EPI_QKV_ROPE) {
+        // The wave's 128 columns are one head of q, k or v (head_dim 128).  Each 32-row block is staged
+        // in the LDS panel, then q and k are rotated (pairs (i, i + 64), angles from the table) and
+        // written as bf16: q to its [M, H] buffer, k to the [d/8][position][8] layout with the 32 lanes
+        // of a half-wave on 32 consecutive positions of one chunk, v to [position][d].
+        const int n0 = tn * BN + wn * 128;
+        const int seg = n0 / p.H, head = (n0 - seg * p.H) >> 7;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int mblock = m0 + wm * 128 + i * 32;
+#pragma unroll
+            for (int j = 0; j < 4; j++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    f32x4_t v;
+#pragma unroll
+                    for (int e = 0; e < 4; e++) v[e] = acc[j][i][g * 4 + e];
+                    *(f32x4_t *)(panel + r * EPI_LD + j * 32 + g * 8 + 4 * hh) = v;
+                }
+            if (seg == 2) {
+#pragma unroll
+                for (int it = 0; it < 8; it++) {
+                    const int row = it * 4 + (lane >> 4), c = lane & 15, m = mblock + row;
+                    f32x4_t a = *(const f32x4_t *)(panel + row * EPI_LD + c * 8);
+                    f32x4_t b = *(const f32x4_t *)(panel + row * EPI_LD + c * 8 + 4);
+                    bf16x8_t o;
+#pragma unroll
+                    for (int e = 0; e < 4; e++) { o[e] = (bf16_t)a[e]; o[4 + e] = (bf16_t)b[e]; }
+                    if (m < p.M) {
+                        const int sq = m / p.R, pos = p.pos0 + (m - sq * p.R);
+                        *(bf16x8_t *)(p.vc + (((size_t)sq * p.n_heads + head) * p.pos_stride + pos) * 128 + c * 8) = o;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int it = 0; it < 4; it++) {
+                    // q: consecutive lanes take consecutive chunks of a row; k: consecutive positions of a chunk
+                    const int item = it * 64 + lane;
+                    const int row = (seg == 0) ? (item >> 3) : (item & 31);
+                    const int c = (seg == 0) ? (item & 7) : (item >> 5);
+                    const int m = mblock + row;
+                    const float *src = panel + row * EPI_LD + c * 8;
+                    f32x4_t lo0 = *(const f32x4_t *)src, lo1 = *(const f32x4_t *)(src + 4);
+                    f32x4_t hi0 = *(const f32x4_t *)(src + 64), hi1 = *(const f32x4_t *)(src + 68);
+                    if (m < p.M) {
+                        const int sq = m / p.R, rr = m - sq * p.R, pos = p.pos0 + rr;
+                        const f32x4_t *tb = (const f32x4_t *)(p.table + (size_t)rr * 64 + c * 8);
+                        bf16x8_t olo, ohi;
+#pragma unroll
+                        for (int e2 = 0; e2 < 4; e2++) {
+                            const f32x4_t cs = tb[e2];        // (cos, sin) of dims 2 e2 and 2 e2 + 1 of the chunk
+#pragma unroll
+                            for (int u = 0; u < 2; u++) {
+                                const int e = 2 * e2 + u;
+                                const float co = cs[2 * u], si = cs[2 * u + 1];
+                                const float a = e < 4 ? lo0[e & 3] : lo1[e & 3], b = e < 4 ? hi0[e & 3] : hi1[e & 3];
+                                olo[e] = (bf16_t)(a * co - b * si);
+                                ohi[e] = (bf16_t)(b * co + a * si);
+                            }
+                        }
+                        if (seg == 0) {
+                            bf16_t *q = p.q_out + (size_t)m * p.H + head * 128 + c * 8;
+                            *(bf16x8_t *)q = olo;
+                            *(bf16x8_t *)(q + 64) = ohi;
+                        } else {
+                            const size_t hb = ((size_t)sq * p.n_heads + head) * 16;
+                            *(bf16x8_t *)(p.kc + ((hb + c) * p.pos_stride + pos) * 8) = olo;
+                            *(bf16x8_t *)(p.kc + ((hb + 8 + c) * p.pos_stride + pos) * 8) = ohi;
+                        }
+                    }
+                }
+            }
+        }
+        return;
+    }
+    if (EPI == EPI_RESIDUAL) {
+        // read-modify-write of the fp32 residual stream: measured faster straight from the accumulator
+        // layout (64 independent 16-byte load/add/store chains per lane) than through the LDS panel
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int m = m0 + wm * 128 + i * 32 + r;
+            if (m >= p.M) continue;
+            float *out = (float *)p.C + (size_t)m * p.N + tn * BN + wn * 128;
+#pragma unroll
+            for (int j = 0; j < 4; j++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    f32x4_t *dst = (f32x4_t *)(out + j * 32 + g * 8 + 4 * hh);
+                    f32x4_t v = *dst;
+#pragma unroll
+                    for (int e = 0; e < 4; e++) v[e] += acc[j][i][g * 4 + e];
+                    *dst = v;
+                }
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int mblock = m0 + wm * 128 + i * 32;
+        // ---- stage ----------------------------------------------------------------------------------
+        if (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int j = 0; j < 2; j++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    f32x4_t v;
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        float gate = acc[j][i][g * 4 + e], up = acc[j + 2][i][g * 4 + e];
+                        v[e] = gate / (1.0f + __expf(-gate)) * up;
+                    }
+                    *(f32x4_t *)(panel + r * EPI_LD + j * 32 + g * 8 + 4 * hh) = v;
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; j++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    f32x4_t v;
+#pragma unroll
+                    for (int e = 0; e < 4; e++) v[e] = acc[j][i][g * 4 + e];
+                    *(f32x4_t *)(panel + r * EPI_LD + j * 32 + g * 8 + 4 * hh) = v;
+                }
+        }
+        // ---- write out whole rows -------------------------------------------------------------------
+        if (EPI == EPI_SWIGLU) {
+            bf16_t *out = (bf16_t *)p.C + (size_t)tn * 128 + wn * 64 + (lane & 7) * 8;
+#pragma unroll
+            for (int it = 0; it < 4; it++) {
+                const int row = it * 8 + (lane >> 3), m = mblock + row;
+                f32x4_t a = *(const f32x4_t *)(panel + row * EPI_LD + (lane & 7) * 8);
+                f32x4_t b = *(const f32x4_t *)(panel + row * EPI_LD + (lane & 7) * 8 + 4);
+                bf16x8_t o;
+#pragma unroll
+                for (int e = 0; e < 4; e++) { o[e] = (bf16_t)a[e]; o[4 + e] = (bf16_t)b[e]; }
+                if (m < p.M) *(bf16x8_t *)(out + (size_t)m * p.N) = o;
+            }
+        } else {
+            float *out = (float *)p.C + (size_t)tn * BN + wn * 128 + r * 4;
+#pragma unroll
+            for (int it = 0; it < 16; it++) {
+                const int row = it * 2 + hh, m = mblock + row;
+                f32x4_t v = *(const f32x4_t *)(panel + row * EPI_LD + r * 4);
+                if (m < p.M) *(f32x4_t *)(out + (size_t)m * p.N) = v;
+            }
+        }
+    }
 }
 
 template <int EPI>
@@ -157,8 +331,12 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
         // Each region below pairs its memory instructions one by one with MFMAs (sched_group_barrier:
         // 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write), so the matrix pipe keeps issuing
         // while LDS and global traffic trickles in between.
+#if VLA_GEMM_EXPERIMENT < 2
         gload(kn * BK);
+#endif
+#if VLA_GEMM_EXPERIMENT < 3
         frag_load(1, base, 1);
+#endif
         mfma_step(0);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
@@ -172,7 +350,9 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
+#if VLA_GEMM_EXPERIMENT < 3
         frag_load(0, base, 2);
+#endif
         mfma_step(1);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
@@ -181,8 +361,12 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
         __builtin_amdgcn_sched_barrier(0);
+#if VLA_GEMM_EXPERIMENT < 3
         frag_load(1, base, 3);
+#endif
+#if VLA_GEMM_EXPERIMENT < 2
         lstore(s ^ 1);
+#endif
         mfma_step(0);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
@@ -195,8 +379,12 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
             __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
+#if VLA_GEMM_EXPERIMENT != 4
         __syncthreads();
+#endif
+#if VLA_GEMM_EXPERIMENT < 3
         frag_load(0, lds + (s ^ 1) * 2 * TILE_BYTES, 0);
+#endif
         mfma_step(1);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
@@ -207,53 +395,150 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
         __builtin_amdgcn_sched_barrier(0);
     }
 
-    // ---- epilogue: lane holds activation row m = .. + lane % 32 and, per accumulator register r,
-    // weight row 8 * (r / 4) + 4 * (lane / 32) + r % 4 of its block --------------------------------
-    const int mrow_base = m0 + wm * 128 + (lane & 31);
-    const int nquad = 4 * (lane >> 5);
+    __syncthreads();                          // every wave is done reading operand tiles: LDS is reused
+    epilogue<EPI>(acc, p, m0, tn, wm, wn, lane, lds);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Variant with direct-to-LDS loads (global_load_lds_dwordx4) and a four-stage pipeline.
+// K advances by 32 per stage (A 16 KB + W 16 KB = 32 KB, four stages = 128 KB of LDS), so the loads of
+// K tile t+3 are in flight while tile t is multiplied: no staging registers, no ds_write traffic from
+// the waves, and three tiles of latency cover.  A wave instruction fills 1 KB of LDS linearly (lane l ->
+// byte 16 l), i.e. 16 tile rows of 64 bytes; the bank swizzle (chunk c of row r at c ^ ((r >> 2) & 3))
+// is applied by choosing which global chunk each lane fetches.  Fragment reads are issued as inline
+// ds_read_b128 so that the compiler's wait-count insertion -- which would wait for every outstanding
+// LDS-DMA load before any LDS read it can see -- stays out of the loop; the waits are explicit:
+// vmcnt(16) = "my loads of tile t have landed" (tiles t+1, t+2 still in flight, 8 loads each), then one
+// s_barrier per K tile.
+// ------------------------------------------------------------------------------------------------
+constexpr int DBK = 32, DSTAGES = 4;
+constexpr int DREGION = 256 * DBK * 2;          // 16 KB per operand per stage
+constexpr int DSTAGE = 2 * DREGION;
+
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8_t lds_read_b128(int addr) {
+    i32x4_t v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr));
+    return __builtin_bit_cast(bf16x8_t, v);
+}
+
+template <int EPI>
+__global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(MfmaGemmParams p) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    int tm, tn;
+    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * BM;
+    const int K = p.K;
+
+    // ---- per-lane global sources of the 4 + 4 DMA instructions of this wave per K tile --------------
+    const bf16_t *asrc[4], *wsrc[4];
 #pragma unroll
     for (int i = 0; i < 4; i++) {
-        int m = mrow_base + i * 32;
-        if (m >= p.M) continue;
+        const int row = (wave * 4 + i) * 16 + (lane >> 2), pc = lane & 3;
+        const int c = pc ^ ((row >> 2) & 3);
+        asrc[i] = p.A + (size_t)min(m0 + row, p.M - 1) * K + c * 8;
+        const bf16_t *wrow;
         if (EPI == EPI_SWIGLU) {
-            bf16_t *out = (bf16_t *)p.C + (size_t)m * p.N + tn * 128 + wn * 64;
-#pragma unroll
-            for (int j = 0; j < 2; j++)
-#pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    bf16x4_t o;
-#pragma unroll
-                    for (int e = 0; e < 4; e++) {
-                        float gate = acc[j][i][g * 4 + e], up = acc[j + 2][i][g * 4 + e];
-                        o[e] = (bf16_t)(gate / (1.0f + __expf(-gate)) * up);
-                    }
-                    *(bf16x4_t *)(out + j * 32 + g * 8 + nquad) = o;
-                }
-        } else if (EPI == EPI_RESIDUAL) {
-            float *out = (float *)p.C + (size_t)m * p.N + tn * BN + wn * 128;
-#pragma unroll
-            for (int j = 0; j < 4; j++)
-#pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    f32x4_t *dst = (f32x4_t *)(out + j * 32 + g * 8 + nquad);
-                    f32x4_t v = *dst;
-#pragma unroll
-                    for (int e = 0; e < 4; e++) v[e] += acc[j][i][g * 4 + e];
-                    *dst = v;
-                }
+            const int sub = row >> 6;
+            const int f = tn * 128 + (sub >> 1) * 64 + (row & 63);
+            wrow = ((sub & 1) ? p.W1 : p.W0) + (size_t)f * K;
         } else {
-            float *out = (float *)p.C + (size_t)m * p.N + tn * BN + wn * 128;
-#pragma unroll
-            for (int j = 0; j < 4; j++)
-#pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    f32x4_t v;
-#pragma unroll
-                    for (int e = 0; e < 4; e++) v[e] = acc[j][i][g * 4 + e];
-                    *(f32x4_t *)(out + j * 32 + g * 8 + nquad) = v;
-                }
+            const int n = tn * BN + row;
+            const int seg = n / p.segN;
+            const bf16_t *Wp = seg == 0 ? p.W0 : (seg == 1 ? p.W1 : p.W2);
+            wrow = Wp + (size_t)(n - seg * p.segN) * K;
         }
+        wsrc[i] = wrow + c * 8;
     }
+    typedef __attribute__((address_space(3))) void lds_void;
+    typedef const __attribute__((address_space(1))) void glb_void;
+    auto dma = [&](int stage, int kt) {
+        char *base = lds + stage * DSTAGE + wave * 4096;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            __builtin_amdgcn_global_load_lds((glb_void *)(asrc[i] + (size_t)kt * DBK), (lds_void *)(base + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_void *)(wsrc[i] + (size_t)kt * DBK), (lds_void *)(base + DREGION + i * 1024), 16, 0, 0);
+        }
+    };
+
+    // ---- fragment addresses: row * 64 + ((ks * 2 + lane / 32) ^ ((row >> 2) & 3)) * 16 ------------------
+    const int lds0 = (int)(size_t)(lds_void *)lds;       // LDS byte address of the dynamic segment
+    int a_addr[2][4], w_addr[2][4];
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int ra = wm * 128 + i * 32 + (lane & 31), rw = wn * 128 + i * 32 + (lane & 31);
+            const int c = ks * 2 + (lane >> 5);
+            a_addr[ks][i] = lds0 + ra * 64 + ((c ^ ((ra >> 2) & 3)) << 4);
+            w_addr[ks][i] = lds0 + DREGION + rw * 64 + ((c ^ ((rw >> 2) & 3)) << 4);
+        }
+
+    f32x16_t acc[4][4];
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[j][i][r] = 0.f;
+
+    bf16x8_t af[2][4], wf[2][4];
+#pragma unroll
+    for (int b = 0; b < 2; b++)
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) { af[b][i][e] = (bf16_t)0.f; wf[b][i][e] = (bf16_t)0.f; }
+
+    auto frag_load = [&](int buf, int ks, int soff) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            af[buf][i] = lds_read_b128(a_addr[ks][i] + soff);
+            wf[buf][i] = lds_read_b128(w_addr[ks][i] + soff);
+        }
+    };
+    auto mfma_step = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
+    };
+    // waits for this wave's outstanding ds_reads; the fragments pass through so that no MFMA using
+    // them can be scheduled above the wait
+    auto wait_frags = [&](int buf) {
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(af[buf][0]), "+v"(af[buf][1]), "+v"(af[buf][2]), "+v"(af[buf][3]), "+v"(wf[buf][0]),
+                       "+v"(wf[buf][1]), "+v"(wf[buf][2]), "+v"(wf[buf][3]));
+    };
+
+    const int ktiles = K / DBK;
+    dma(0, 0);
+    dma(1, min(1, ktiles - 1));
+    dma(2, min(2, ktiles - 1));
+    for (int kt = 0; kt < ktiles; kt++) {
+        const int stage = kt & 3;
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");      // own loads of tile kt have landed
+        __builtin_amdgcn_s_barrier();                           // everyone's have; tile kt-1 is released
+        frag_load(0, 0, stage * DSTAGE);                        // LDS reads first: their latency is covered below
+        __builtin_amdgcn_sched_barrier(0);
+        dma((kt + 3) & 3, min(kt + 3, ktiles - 1));              // past the end: re-stage the last tile, unused
+        mfma_step(1);                                           // second half of tile kt-1 (zeros at kt = 0)
+        __builtin_amdgcn_sched_barrier(0);
+        wait_frags(0);
+        frag_load(1, 1, stage * DSTAGE);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(0);
+        __builtin_amdgcn_sched_barrier(0);
+        wait_frags(1);
+    }
+    mfma_step(1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // the unused tail loads have landed
+    __syncthreads();                                           // ... for every wave: LDS is reused below
+    epilogue<EPI>(acc, p, m0, tn, wm, wn, lane, lds);
 }
 
 template <int EPI>
@@ -271,8 +556,23 @@ int launch(const MfmaGemmParams &p, hipStream_t st) {
     }
     const double flops = 2.0 * p.M * p.K * (EPI == EPI_SWIGLU ? 2.0 * p.N : (double)p.N);
     ProfScope ps(EPI == EPI_SWIGLU ? "gemm_bf16_mfma<swiglu>" : EPI == EPI_RESIDUAL ? "gemm_bf16_mfma<residual>"
-                                                                                 : "gemm_bf16_mfma<store>", flops, st);
-    gemm_bf16_mfma_kernel<EPI><<<p.tiles_m * p.tiles_n, 256, lds, st>>>(p);
+                 : EPI == EPI_QKV_ROPE ? "gemm_bf16_mfma<qkv_rope>" : "gemm_bf16_mfma<store>", flops, st);
+    if (p.variant == 1) {
+        static bool attr2_set = false;
+        const size_t lds2 = (size_t)DSTAGES * DSTAGE;
+        if (!attr2_set) {
+            hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_dma_kernel<EPI>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+            if (e != hipSuccess) {
+                vla_set_error("hipFuncSetAttribute(gemm_bf16_dma) failed: %s", hipGetErrorString(e));
+                return VLA_EHIP;
+            }
+            attr2_set = true;
+        }
+        gemm_bf16_dma_kernel<EPI><<<p.tiles_m * p.tiles_n, 256, lds2, st>>>(p);
+    } else {
+        gemm_bf16_mfma_kernel<EPI><<<p.tiles_m * p.tiles_n, 256, lds, st>>>(p);
+    }
     int rc = vla_check_launch("gemm_bf16_mfma");
     return rc ? rc : 1;
 }
@@ -290,6 +590,7 @@ int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
     p.C = g.C; p.M = g.M; p.K = g.K; p.segN = g.segN;
     p.tiles_m = (g.M + BM - 1) / BM;
     { const char *e = getenv("VLA_GEMM_DBG"); p.dbg = e ? atoi(e) : 0; }
+    { const char *e = getenv("VLA_GEMM_VARIANT"); p.variant = e ? atoi(e) : 0; }
     if (g.epilogue == EPI_SWIGLU) {
         if (g.segN % 128 != 0) return 0;
         p.N = g.segN;
@@ -297,6 +598,19 @@ int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
         return launch<EPI_SWIGLU>(p, st);
     }
     if (g.segN % BN != 0) return 0;
+    if (g.epilogue == EPI_QKV_ROPE) {
+        const QkvRopeArgs *ra = g.rope;
+        if (!ra || ra->kv->d != 128 || g.n_seg != 3 || g.segN != ra->kv->n_heads * 128) return 0;
+        p.q_out = (bf16_t *)ra->q_out;
+        p.kc = (bf16_t *)ra->kv->k + (size_t)ra->layer * ra->kv->layer_elems;
+        p.vc = (bf16_t *)ra->kv->v + (size_t)ra->layer * ra->kv->layer_elems;
+        p.table = ra->table;
+        p.R = ra->rows->R; p.pos0 = ra->rows->pos0; p.n_heads = ra->kv->n_heads;
+        p.pos_stride = ra->kv->pos_stride; p.H = g.segN;
+        p.N = 3 * g.segN;
+        p.tiles_n = p.N / BN;
+        return launch<EPI_QKV_ROPE>(p, st);
+    }
     p.N = g.n_seg * g.segN;
     p.tiles_n = p.N / BN;
     return g.epilogue == EPI_RESIDUAL ? launch<EPI_RESIDUAL>(p, st) : launch<EPI_STORE>(p, st);

@@ -31,7 +31,17 @@ struct RowsArgs {           // one forward over n_seq sequences x R new rows eac
                             // rows below attend causally (keys 0..position)
 };
 
-enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_QKV_ROPE = 3 };
+
+// Extra arguments of EPI_QKV_ROPE: the QKV projection whose epilogue rotates q and k and writes q to
+// q_out [M, H] and k, v straight into layer `layer` of the KV buffer (head_dim 128 only).
+struct QkvRopeArgs {
+    void *q_out;
+    const float2 *table;    // [R][d/2] (cos, sin)
+    const KvView *kv;
+    int layer;
+    const RowsArgs *rows;
+};
 
 struct GemmArgs {
     const void *A;          // [M, K] row-major (lda = K), storage dtype (or fp32 for fp32 models)
@@ -40,6 +50,7 @@ struct GemmArgs {
     void *C;                // EPI_STORE: fp32 [M, N]; EPI_SWIGLU: storage dtype [M, N]; EPI_RESIDUAL: fp32 [M, N] +=
     int M, K;
     int epilogue;
+    const QkvRopeArgs *rope;   // EPI_QKV_ROPE only
 };
 
 // ---- generic (any shape, fp32 or bf16 storage) kernels: kernels_generic.hip -----------------

@@ -154,7 +154,14 @@ static int force_generic() {
 template <typename T>
 static int run_gemm(const vla_config &c, GemmArgs g, void *skinny_scratch, hipStream_t st) {
     if (c.dtype == VLA_DTYPE_BF16) {
-        int r = (skinny_scratch && !(force_generic() & 2)) ? try_gemm_bf16_skinny(g, skinny_scratch, st) : 0;
+        int r = 0;
+        if (skinny_scratch && !(force_generic() & 2)) {
+            // single-row forwards: up to 128 rows stream the weights through the skinny kernel; above
+            // that the work is MFMA bound and the large tile with split K does better
+            if (g.M > 128 && !(force_generic() & 1))
+                r = try_gemm_bf16_mfma_splitk(g, skinny_scratch, gemm_skinny_scratch_bytes(g.M, 2 * c.ffn > 3 * c.hidden ? 2 * c.ffn : 3 * c.hidden), st);
+            if (r == 0) r = try_gemm_bf16_skinny(g, skinny_scratch, st);
+        }
         if (r != 0) return r < 0 ? r : 0;
         r = (force_generic() & 1) ? 0 : try_gemm_bf16_mfma(g, st);
         if (r != 0) return r < 0 ? r : 0;

@@ -38,6 +38,8 @@ struct MfmaGemmParams {
     int tiles_m, tiles_n;
     int dbg;
     int variant;     // 0: register-staged loads, 1: direct-to-LDS four-stage pipeline
+    int splits;      // K split across workgroups (decode at M > 128); partial sums go to P
+    float *P;        // [splits][M][N] fp32 (SwiGLU: [splits][M][2N], gate columns then up columns)
     // EPI_QKV_ROPE
     bf16_t *q_out, *kc, *vc;
     const float2 *table;
@@ -227,6 +229,40 @@ __device__ __forceinline__ void epilogue(f32x16_t (&acc)[4][4], const MfmaGemmPa
     }
 }
 
+// Split-K: the wave's 32 x 128 blocks leave as fp32 partial sums, whole rows at a time, for the ordered
+// reduction kernel.  SwiGLU tiles carry 64 gate and 64 up columns per wave: gate goes to column f, up to
+// column N + f of a [M][2N] panel.
+template <int EPI>
+__device__ __forceinline__ void epilogue_partial(f32x16_t (&acc)[4][4], const MfmaGemmParams &p, int split, int m0,
+                                                 int tn, int wm, int wn, int lane, char *lds_all) {
+    float *panel = (float *)(lds_all + (wm * 2 + wn) * EPI_PANEL_BYTES);
+    const int r = lane & 31, hh = lane >> 5;
+    const int NP = (EPI == EPI_SWIGLU) ? 2 * p.N : p.N;
+    int col;
+    if (EPI == EPI_SWIGLU) col = (r < 16 ? 0 : p.N - 64) + tn * 128 + wn * 64 + r * 4;   // r >= 16: up half
+    else col = tn * BN + wn * 128 + r * 4;
+    float *out = p.P + (size_t)split * p.M * NP + col;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int mblock = m0 + wm * 128 + i * 32;
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                f32x4_t v;
+#pragma unroll
+                for (int e = 0; e < 4; e++) v[e] = acc[j][i][g * 4 + e];
+                *(f32x4_t *)(panel + r * EPI_LD + j * 32 + g * 8 + 4 * hh) = v;
+            }
+#pragma unroll
+        for (int it = 0; it < 16; it++) {
+            const int row = it * 2 + hh, m = mblock + row;
+            f32x4_t v = *(const f32x4_t *)(panel + row * EPI_LD + r * 4);
+            if (m < p.M) *(f32x4_t *)(out + (size_t)m * NP) = v;
+        }
+    }
+}
+
 template <int EPI>
 __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -234,7 +270,9 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     int tm, tn;
-    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    const int n_tiles = p.tiles_m * p.tiles_n;
+    const int split = blockIdx.x / n_tiles;
+    tile_of_block(blockIdx.x - split * n_tiles, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM;
     const int K = p.K;
 
@@ -318,15 +356,16 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
                 acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
     };
 
-    const int ktiles = K / BK;
-    gload(0);
+    const int ktiles_all = K / BK;
+    const int kt0 = (int)((long)split * ktiles_all / p.splits), ktiles = (int)((long)(split + 1) * ktiles_all / p.splits);
+    gload(kt0 * BK);
     lstore(0);
     __syncthreads();
     frag_load(0, lds, 0);
-    for (int kt = 0; kt < ktiles; kt++) {
-        const int s = kt & 1;
+    for (int kt = kt0; kt < ktiles; kt++) {
+        const int s = (kt - kt0) & 1;
         // the last tile re-stages itself into the idle buffer: a branch-free body schedules better
-        const int kn = p.dbg ? 0 : min(kt + 1, ktiles - 1);
+        const int kn = p.dbg ? kt0 : min(kt + 1, ktiles - 1);
         const char *base = lds + s * 2 * TILE_BYTES;
         // Each region below pairs its memory instructions one by one with MFMAs (sched_group_barrier:
         // 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write), so the matrix pipe keeps issuing
@@ -396,7 +435,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     }
 
     __syncthreads();                          // every wave is done reading operand tiles: LDS is reused
-    epilogue<EPI>(acc, p, m0, tn, wm, wn, lane, lds);
+    if (p.splits > 1) epilogue_partial<EPI>(acc, p, split, m0, tn, wm, wn, lane, lds);
+    else epilogue<EPI>(acc, p, m0, tn, wm, wn, lane, lds);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -571,7 +611,7 @@ int launch(const MfmaGemmParams &p, hipStream_t st) {
         }
         gemm_bf16_dma_kernel<EPI><<<p.tiles_m * p.tiles_n, 256, lds2, st>>>(p);
     } else {
-        gemm_bf16_mfma_kernel<EPI><<<p.tiles_m * p.tiles_n, 256, lds, st>>>(p);
+        gemm_bf16_mfma_kernel<EPI><<<p.tiles_m * p.tiles_n * p.splits, 256, lds, st>>>(p);
     }
     int rc = vla_check_launch("gemm_bf16_mfma");
     return rc ? rc : 1;
@@ -591,6 +631,7 @@ int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
     p.tiles_m = (g.M + BM - 1) / BM;
     { const char *e = getenv("VLA_GEMM_DBG"); p.dbg = e ? atoi(e) : 0; }
     { const char *e = getenv("VLA_GEMM_VARIANT"); p.variant = e ? atoi(e) : 0; }
+    p.splits = 1;
     if (g.epilogue == EPI_SWIGLU) {
         if (g.segN % 128 != 0) return 0;
         p.N = g.segN;
@@ -614,4 +655,40 @@ int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
     p.N = g.n_seg * g.segN;
     p.tiles_n = p.N / BN;
     return g.epilogue == EPI_RESIDUAL ? launch<EPI_RESIDUAL>(p, st) : launch<EPI_STORE>(p, st);
+}
+
+// Decode forwards with more than 128 rows: the large tile with K split over workgroups so that the
+// single row of tiles still covers the chip; partial sums are reduced in split order by the decode
+// GEMM's reduction kernel (no atomics).  `scratch` holds the partials.
+int try_gemm_bf16_mfma_splitk(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st) {
+    if (g.M < 1 || g.M > BM || g.K % BK != 0 || !scratch || g.epilogue == EPI_QKV_ROPE) return 0;
+    MfmaGemmParams p{};
+    p.A = (const bf16_t *)g.A;
+    p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
+    p.C = g.C; p.M = g.M; p.K = g.K; p.segN = g.segN;
+    p.tiles_m = 1;
+    p.dbg = 0; p.variant = 0;
+    int np;
+    if (g.epilogue == EPI_SWIGLU) {
+        if (g.segN % 128 != 0) return 0;
+        p.N = g.segN; p.tiles_n = g.segN / 128; np = 2 * p.N;
+    } else {
+        if (g.segN % BN != 0) return 0;
+        p.N = g.n_seg * g.segN; p.tiles_n = p.N / BN; np = p.N;
+    }
+    const int ktiles = g.K / BK;
+    int splits = (256 + p.tiles_n / 2) / p.tiles_n;          // about one workgroup per CU
+    if (splits > ktiles / 4) splits = ktiles / 4;              // at least four K tiles per split
+    if (splits > 16) splits = 16;
+    while (splits > 1 && (size_t)splits * g.M * np * sizeof(float) > scratch_bytes) splits--;
+    if (splits < 1) splits = 1;
+    p.splits = splits;
+    p.P = (float *)scratch;
+    int rc;
+    if (g.epilogue == EPI_SWIGLU) rc = launch<EPI_SWIGLU>(p, st);
+    else if (g.epilogue == EPI_RESIDUAL) rc = launch<EPI_RESIDUAL>(p, st);
+    else rc = launch<EPI_STORE>(p, st);
+    if (rc < 0) return rc;
+    if (splits > 1 && (rc = launch_splitk_reduce(g.epilogue, g.C, p.P, splits, g.M, p.N, st))) return rc;
+    return 1;
 }

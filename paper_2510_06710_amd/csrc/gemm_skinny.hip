@@ -256,6 +256,19 @@ int launch_epi(const SkinnyParams &p, int n_tiles, hipStream_t st) {
 
 }  // namespace
 
+// Adds the split-K partial sums P[splits][M][NP] (NP = N, or 2N for SwiGLU) in split order and applies
+// the epilogue.
+int launch_splitk_reduce(int epilogue, void *C, const float *P, int splits, int M, int N, hipStream_t st) {
+    const int np = (epilogue == EPI_SWIGLU) ? 2 * N : N;
+    ProfScope ps("splitk_reduce", (double)(splits + 1) * M * np * 4.0, st);
+    size_t MN = (size_t)M * N;
+    unsigned blocks = (unsigned)((MN / 4 + 255) / 256);
+    if (epilogue == EPI_RESIDUAL) skinny_reduce_kernel<EPI_RESIDUAL><<<blocks, 256, 0, st>>>(C, P, splits, M, N);
+    else if (epilogue == EPI_SWIGLU) skinny_reduce_kernel<EPI_SWIGLU><<<blocks, 256, 0, st>>>(C, P, splits, M, N);
+    else skinny_reduce_kernel<EPI_STORE><<<blocks, 256, 0, st>>>(C, P, splits, M, N);
+    return vla_check_launch("splitk_reduce");
+}
+
 static int skinny_target_wgs() {
     static int v = -1;
     if (v < 0) {
@@ -296,15 +309,6 @@ int try_gemm_bf16_skinny(const GemmArgs &g, void *scratch, hipStream_t st) {
         else rc = launch_epi<EPI_STORE>(p, n_tiles, st);
         if (rc) return rc;
     }
-    if (splits > 1) {
-        const int np = (g.epilogue == EPI_SWIGLU) ? 2 * p.N : p.N;
-        ProfScope ps("skinny_reduce", (double)(splits + 1) * g.M * np * 4.0, st);
-        size_t MN = (size_t)g.M * p.N;
-        unsigned blocks = (unsigned)((MN / 4 + 255) / 256);
-        if (g.epilogue == EPI_RESIDUAL) skinny_reduce_kernel<EPI_RESIDUAL><<<blocks, 256, 0, st>>>(g.C, p.P, splits, g.M, p.N);
-        else if (g.epilogue == EPI_SWIGLU) skinny_reduce_kernel<EPI_SWIGLU><<<blocks, 256, 0, st>>>(g.C, p.P, splits, g.M, p.N);
-        else skinny_reduce_kernel<EPI_STORE><<<blocks, 256, 0, st>>>(g.C, p.P, splits, g.M, p.N);
-        if ((rc = vla_check_launch("skinny_reduce"))) return rc;
-    }
+    if (splits > 1 && (rc = launch_splitk_reduce(g.epilogue, g.C, p.P, splits, g.M, p.N, st))) return rc;
     return 1;
 }

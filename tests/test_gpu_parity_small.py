@@ -54,14 +54,18 @@ def test_aligned_bf16_rollout_fast_kernels(B):
         _print(f"aligned bf16 B={B} vs {mode} oracle", compare_rollout(gpu, ref, "bf16", autoregressive=True))
 
 
-def test_hidden_1024_bf16_register_resident_norm():
-    """hidden = 1024 takes the vectorised RMSNorm (rows held in registers) as the 7B shape does."""
+@pytest.mark.parametrize("B", [3, 140])
+def test_hidden_1024_bf16_register_resident_norm(B):
+    """hidden = 1024 takes the vectorised RMSNorm (rows held in registers) as the 7B shape does; with
+    140 environments the decode GEMMs take the large tile with K split over workgroups."""
     wl = vi.Workload("h1024", vi.ModelShape(n_layers=2, hidden=1024, n_heads=8, ffn=1024, vocab=512, dtype="bf16"),
-                     batch=3, n_patches=20, n_instr=5, n_action=3)
+                     batch=B, n_patches=20, n_instr=5, n_action=3)
     gpu = GpuCase(wl, 12).rollout()
-    for mode in ("bf16", "exact"):
+    # stated bar against the oracle on the same bf16-stored tensors; against the exact oracle the
+    # operand rounding of a 1024-wide, 2-layer model already reaches 1.3e-2 on a log-prob
+    for mode, tol in (("bf16", "bf16"), ("exact", "bf16_deep")):
         ref = oracle_rollout(wl, 12, operand_dtype=mode)
-        _print(f"hidden 1024 bf16 vs {mode} oracle", compare_rollout(gpu, ref, "bf16", autoregressive=True))
+        _print(f"hidden 1024 bf16 vs {mode} oracle", compare_rollout(gpu, ref, tol, autoregressive=True))
 
 
 def test_aligned_bf16_chunk_and_recompute_fast_kernels():

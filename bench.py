@@ -80,6 +80,58 @@ def cpu_baseline(wl, vi, sample_layers=8):
                       f"{wl.n_action} action tokens), fp64 numpy, {dt:.1f} s measured, scaled by layers"}
 
 
+def bench_recompute(args, wl, torch, vi, vb, Rollout):
+    """The log-prob recompute workload (cfg5): a step is one vla_logprob_recompute call over all stored
+    rollouts (internally micro-batched by max_batch = 128)."""
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    N, S, A, shape = wl.batch, wl.prefix, wl.n_action, wl.shape
+    synth = vi.SynthModel(shape, 0, device=dev)
+    run = Rollout(synth, min(N, 128), S + A, device=dev, value_b=vi.VALUE_BIAS)
+    patch, ids = vi.observation(wl, 0, device=dev)
+    bins = vi.stored_bins(wl, 0, device=dev)
+    slot = synth.slot_embed(A) if wl.mode == 1 else None
+    stream = torch.cuda.current_stream()
+
+    def step():
+        return run.recompute(patch, ids, bins, A, wl.mode, slot, wl.temperature, want_value=True,
+                             want_logits=False, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    vb.lib().vla_profile_enable(1)
+    step()
+    torch.cuda.synchronize()
+    prof = profile_report(vb)
+    vb.lib().vla_profile_enable(0)
+    rows = S + A - 1 if wl.mode == 0 else S + A
+    flops = N * rows * 2.0 * shape.layer_params * shape.n_layers
+    dom = prof.get("gemm_bf16_mfma<swiglu>")
+    roofline = None
+    if dom:
+        ach = dom["work"] / (dom["ms"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16_mfma_kernel<EPI_SWIGLU> (gate/up projection)",
+                    "achieved": ach, "peak": MI355X_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / MI355X_BF16_TFLOPS,
+                    "launches": dom["count"], "avg_launch_ms": dom["ms"] / dom["count"], "traffic": None}
+    out = {"metric": "stored rollouts/sec, log-prob recompute (7B shape), % MFMA roofline", "value": N / (ms * 1e-3),
+           "unit": "rollouts/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+           "config": {"workload": wl.name, "rollouts": N, "prefix": S, "action_tokens": A, "rows_per_rollout": rows,
+                      "micro_batch": min(N, 128), "layers": shape.n_layers, "hidden": shape.hidden},
+           "roofline": roofline,
+           "phases": {"recompute_tokens_per_s": N * rows / (ms * 1e-3), "mfma_TFLOPs": flops / (ms * 1e-3) / 1e12,
+                      "mfma_frac": flops / (ms * 1e-3) / 1e12 / MI355X_BF16_TFLOPS},
+           "kernels": {k: {"n": v["count"], "ms": round(v["ms"], 3)} for k, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"])}}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,10 +153,10 @@ def main():
     from paper_2510_06710_amd.harness import Rollout
 
     wl = vi.WORKLOADS[args.workload]
-    if wl.kind != "rollout":
-        print("bench.py times rollout workloads (prefill + decode)", file=sys.stderr)
-        sys.exit(2)
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if wl.kind == "recompute":
+        bench_recompute(args, wl, torch, vi, vb, Rollout)
+        return
     dev = "cuda:0"
     torch.cuda.set_device(0)
     B, S, A = wl.batch, wl.prefix, wl.n_action

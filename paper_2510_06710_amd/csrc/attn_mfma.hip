@@ -48,7 +48,7 @@ __global__ void __launch_bounds__(256) v_transpose_kernel(bf16_t *vt, const bf16
 }
 
 template <int D>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) attn_prefill_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4))) attn_prefill_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
                                                           const bf16_t *vt, int R, int pos0, int full_from,
                                                           int n_heads, int pos_stride, int ps_pad, int H,
                                                           int q_blocks) {
@@ -86,17 +86,35 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))
         for (int i = 0; i < 16; i++) o_acc[b][i] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
+    // K fragments of key block kb (clamped key index: positions >= nk are masked below)
+    auto load_k = [&](bf16x8_t (&kf)[KS], int kb) {
+        const int key_ld = min(kb * 32 + col, nk - 1);
+#pragma unroll
+        for (int kk = 0; kk < KS; kk++)
+            kf[kk] = *(const bf16x8_t *)(kh + ((size_t)(kk * 2 + hh) * pos_stride + key_ld) * 8);
+    };
+    bf16x8_t kf[KS], kf_next[KS];
+    load_k(kf, 0);
     for (int kb = 0; kb < n_kb; kb++) {
+        // ---- issue this block's V^T loads and the next block's K loads before any arithmetic ------------
+        bf16x4_t vlo[2][DB], vhi[2][DB];
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            const int g0 = kb * 8 + 4 * u + hh;            // key group (4 keys) of slots e = 0..3
+#pragma unroll
+            for (int b = 0; b < DB; b++) {
+                const bf16_t *vrow = vth + (((size_t)b * (ps_pad >> 2) + g0) * 32 + col) * 4;
+                vlo[u][b] = *(const bf16x4_t *)vrow;
+                vhi[u][b] = *(const bf16x4_t *)(vrow + 2 * 32 * 4);       // two key groups further
+            }
+        }
+        load_k(kf_next, min(kb + 1, n_kb - 1));
         // ---- S^T block: rows = keys kb*32 .. +31, columns = the wave's 32 queries ---------------
-        const int key_ld = min(kb * 32 + col, nk - 1);          // clamped load, masked below
         f32x16_t st;
 #pragma unroll
         for (int i = 0; i < 16; i++) st[i] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < KS; kk++) {
-            bf16x8_t kf = *(const bf16x8_t *)(kh + ((size_t)(kk * 2 + hh) * pos_stride + key_ld) * 8);
-            st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st, 0, 0, 0);
-        }
+        for (int kk = 0; kk < KS; kk++) st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], st, 0, 0, 0);
         // register i of this lane is key kb*32 + 8*(i/4) + 4*hh + i%4 for query `col`
         float bmax = -INFINITY;
 #pragma unroll
@@ -125,26 +143,26 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))
         psum += __shfl_xor(psum, 32, 64);
         l_run = l_run * corr + psum;
         m_run = m_new;
+        if (!__all(corr == 1.0f)) {                        // the running max moved for some query of the wave
 #pragma unroll
-        for (int b = 0; b < DB; b++)
+            for (int b = 0; b < DB; b++)
 #pragma unroll
-            for (int i = 0; i < 16; i++) o_acc[b][i] *= corr;
+                for (int i = 0; i < 16; i++) o_acc[b][i] *= corr;
+        }
         // ---- O^T += V^T . P^T: k slot (hh, e) of product u is key kb*32 + 16u + 8*(e/4) + 4hh + e%4
 #pragma unroll
         for (int u = 0; u < 2; u++) {
-            const int g0 = kb * 8 + 4 * u + hh;            // key group (4 keys) of slots e = 0..3
 #pragma unroll
             for (int b = 0; b < DB; b++) {
-                const bf16_t *vrow = vth + (((size_t)b * (ps_pad >> 2) + g0) * 32 + col) * 4;
-                bf16x4_t lo = *(const bf16x4_t *)vrow;
-                bf16x4_t hi = *(const bf16x4_t *)(vrow + 2 * 32 * 4);       // two key groups further
                 bf16x8_t vf;
 #pragma unroll
-                for (int e = 0; e < 4; e++) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
+                for (int e = 0; e < 4; e++) { vf[e] = vlo[u][b][e]; vf[4 + e] = vhi[u][b][e]; }
                 o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], o_acc[b], 0, 0, 0);
                 o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pl[u], o_acc[b], 0, 0, 0);
             }
         }
+#pragma unroll
+        for (int kk = 0; kk < KS; kk++) kf[kk] = kf_next[kk];
     }
     // ---- store: lane holds query `col`, dims b*32 + 8*(i/4) + 4*hh + i%4 -------------------------
     if (qb * 32 + col < R) {

@@ -15,17 +15,9 @@
 //
 // Epilogues: store fp32 (QKV, rounded only after the rotation); add into the fp32 residual stream; SwiGLU (tile rows interleave 64 gate and
 // 64 up rows per wave so that silu(gate) * up pairs two accumulators of the same lane).
-#include <stdlib.h>
-
 #include "vla_internal.h"
 
 namespace {
-
-// Timing experiments of the development harness only (wrong results): 2 = no global loads / LDS writes
-// in the K loop, 3 = also no fragment reads, 4 = as 3 without the barrier.  Product builds use 0.
-#ifndef VLA_GEMM_EXPERIMENT
-#define VLA_GEMM_EXPERIMENT 0
-#endif
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int TILE_BYTES = BM * BK * 2;     // 32 KB per operand per stage
@@ -36,8 +28,6 @@ struct MfmaGemmParams {
     void *C;
     int M, N, K, segN;
     int tiles_m, tiles_n;
-    int dbg;
-    int variant;     // 0: register-staged loads, 1: direct-to-LDS four-stage pipeline
     int splits;      // K split across workgroups (decode at M > 128); partial sums go to P
     float *P;        // [splits][M][N] fp32 (SwiGLU: [splits][M][2N], gate columns then up columns)
     // EPI_QKV_ROPE
@@ -365,17 +355,13 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     for (int kt = kt0; kt < ktiles; kt++) {
         const int s = (kt - kt0) & 1;
         // the last tile re-stages itself into the idle buffer: a branch-free body schedules better
-        const int kn = p.dbg ? kt0 : min(kt + 1, ktiles - 1);
+        const int kn = min(kt + 1, ktiles - 1);
         const char *base = lds + s * 2 * TILE_BYTES;
         // Each region below pairs its memory instructions one by one with MFMAs (sched_group_barrier:
         // 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write), so the matrix pipe keeps issuing
         // while LDS and global traffic trickles in between.
-#if VLA_GEMM_EXPERIMENT < 2
         gload(kn * BK);
-#endif
-#if VLA_GEMM_EXPERIMENT < 3
         frag_load(1, base, 1);
-#endif
         mfma_step(0);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
@@ -389,9 +375,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
-#if VLA_GEMM_EXPERIMENT < 3
         frag_load(0, base, 2);
-#endif
         mfma_step(1);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
@@ -400,12 +384,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
         __builtin_amdgcn_sched_barrier(0);
-#if VLA_GEMM_EXPERIMENT < 3
         frag_load(1, base, 3);
-#endif
-#if VLA_GEMM_EXPERIMENT < 2
         lstore(s ^ 1);
-#endif
         mfma_step(0);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
@@ -418,12 +398,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
             __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
-#if VLA_GEMM_EXPERIMENT != 4
         __syncthreads();
-#endif
-#if VLA_GEMM_EXPERIMENT < 3
         frag_load(0, lds + (s ^ 1) * 2 * TILE_BYTES, 0);
-#endif
         mfma_step(1);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
@@ -437,148 +413,6 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     __syncthreads();                          // every wave is done reading operand tiles: LDS is reused
     if (p.splits > 1) epilogue_partial<EPI>(acc, p, split, m0, tn, wm, wn, lane, lds);
     else epilogue<EPI>(acc, p, m0, tn, wm, wn, lane, lds);
-}
-
-// ------------------------------------------------------------------------------------------------
-// Variant with direct-to-LDS loads (global_load_lds_dwordx4) and a four-stage pipeline.
-// K advances by 32 per stage (A 16 KB + W 16 KB = 32 KB, four stages = 128 KB of LDS), so the loads of
-// K tile t+3 are in flight while tile t is multiplied: no staging registers, no ds_write traffic from
-// the waves, and three tiles of latency cover.  A wave instruction fills 1 KB of LDS linearly (lane l ->
-// byte 16 l), i.e. 16 tile rows of 64 bytes; the bank swizzle (chunk c of row r at c ^ ((r >> 2) & 3))
-// is applied by choosing which global chunk each lane fetches.  Fragment reads are issued as inline
-// ds_read_b128 so that the compiler's wait-count insertion -- which would wait for every outstanding
-// LDS-DMA load before any LDS read it can see -- stays out of the loop; the waits are explicit:
-// vmcnt(16) = "my loads of tile t have landed" (tiles t+1, t+2 still in flight, 8 loads each), then one
-// s_barrier per K tile.
-// ------------------------------------------------------------------------------------------------
-constexpr int DBK = 32, DSTAGES = 4;
-constexpr int DREGION = 256 * DBK * 2;          // 16 KB per operand per stage
-constexpr int DSTAGE = 2 * DREGION;
-
-typedef int i32x4_t __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ bf16x8_t lds_read_b128(int addr) {
-    i32x4_t v;
-    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr));
-    return __builtin_bit_cast(bf16x8_t, v);
-}
-
-template <int EPI>
-__global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(MfmaGemmParams p) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    int tm, tn;
-    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
-    const int m0 = tm * BM;
-    const int K = p.K;
-
-    // ---- per-lane global sources of the 4 + 4 DMA instructions of this wave per K tile --------------
-    const bf16_t *asrc[4], *wsrc[4];
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int row = (wave * 4 + i) * 16 + (lane >> 2), pc = lane & 3;
-        const int c = pc ^ ((row >> 2) & 3);
-        asrc[i] = p.A + (size_t)min(m0 + row, p.M - 1) * K + c * 8;
-        const bf16_t *wrow;
-        if (EPI == EPI_SWIGLU) {
-            const int sub = row >> 6;
-            const int f = tn * 128 + (sub >> 1) * 64 + (row & 63);
-            wrow = ((sub & 1) ? p.W1 : p.W0) + (size_t)f * K;
-        } else {
-            const int n = tn * BN + row;
-            const int seg = n / p.segN;
-            const bf16_t *Wp = seg == 0 ? p.W0 : (seg == 1 ? p.W1 : p.W2);
-            wrow = Wp + (size_t)(n - seg * p.segN) * K;
-        }
-        wsrc[i] = wrow + c * 8;
-    }
-    typedef __attribute__((address_space(3))) void lds_void;
-    typedef const __attribute__((address_space(1))) void glb_void;
-    auto dma = [&](int stage, int kt) {
-        char *base = lds + stage * DSTAGE + wave * 4096;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            __builtin_amdgcn_global_load_lds((glb_void *)(asrc[i] + (size_t)kt * DBK), (lds_void *)(base + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((glb_void *)(wsrc[i] + (size_t)kt * DBK), (lds_void *)(base + DREGION + i * 1024), 16, 0, 0);
-        }
-    };
-
-    // ---- fragment addresses: row * 64 + ((ks * 2 + lane / 32) ^ ((row >> 2) & 3)) * 16 ------------------
-    const int lds0 = (int)(size_t)(lds_void *)lds;       // LDS byte address of the dynamic segment
-    int a_addr[2][4], w_addr[2][4];
-#pragma unroll
-    for (int ks = 0; ks < 2; ks++)
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const int ra = wm * 128 + i * 32 + (lane & 31), rw = wn * 128 + i * 32 + (lane & 31);
-            const int c = ks * 2 + (lane >> 5);
-            a_addr[ks][i] = lds0 + ra * 64 + ((c ^ ((ra >> 2) & 3)) << 4);
-            w_addr[ks][i] = lds0 + DREGION + rw * 64 + ((c ^ ((rw >> 2) & 3)) << 4);
-        }
-
-    f32x16_t acc[4][4];
-#pragma unroll
-    for (int j = 0; j < 4; j++)
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[j][i][r] = 0.f;
-
-    bf16x8_t af[2][4], wf[2][4];
-#pragma unroll
-    for (int b = 0; b < 2; b++)
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-#pragma unroll
-            for (int e = 0; e < 8; e++) { af[b][i][e] = (bf16_t)0.f; wf[b][i][e] = (bf16_t)0.f; }
-
-    auto frag_load = [&](int buf, int ks, int soff) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            af[buf][i] = lds_read_b128(a_addr[ks][i] + soff);
-            wf[buf][i] = lds_read_b128(w_addr[ks][i] + soff);
-        }
-    };
-    auto mfma_step = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < 4; j++)
-#pragma unroll
-            for (int i = 0; i < 4; i++)
-                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
-    };
-    // waits for this wave's outstanding ds_reads; the fragments pass through so that no MFMA using
-    // them can be scheduled above the wait
-    auto wait_frags = [&](int buf) {
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(af[buf][0]), "+v"(af[buf][1]), "+v"(af[buf][2]), "+v"(af[buf][3]), "+v"(wf[buf][0]),
-                       "+v"(wf[buf][1]), "+v"(wf[buf][2]), "+v"(wf[buf][3]));
-    };
-
-    const int ktiles = K / DBK;
-    dma(0, 0);
-    dma(1, min(1, ktiles - 1));
-    dma(2, min(2, ktiles - 1));
-    for (int kt = 0; kt < ktiles; kt++) {
-        const int stage = kt & 3;
-        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");      // own loads of tile kt have landed
-        __builtin_amdgcn_s_barrier();                           // everyone's have; tile kt-1 is released
-        frag_load(0, 0, stage * DSTAGE);                        // LDS reads first: their latency is covered below
-        __builtin_amdgcn_sched_barrier(0);
-        dma((kt + 3) & 3, min(kt + 3, ktiles - 1));              // past the end: re-stage the last tile, unused
-        mfma_step(1);                                           // second half of tile kt-1 (zeros at kt = 0)
-        __builtin_amdgcn_sched_barrier(0);
-        wait_frags(0);
-        frag_load(1, 1, stage * DSTAGE);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step(0);
-        __builtin_amdgcn_sched_barrier(0);
-        wait_frags(1);
-    }
-    mfma_step(1);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // the unused tail loads have landed
-    __syncthreads();                                           // ... for every wave: LDS is reused below
-    epilogue<EPI>(acc, p, m0, tn, wm, wn, lane, lds);
 }
 
 template <int EPI>
@@ -597,22 +431,7 @@ int launch(const MfmaGemmParams &p, hipStream_t st) {
     const double flops = 2.0 * p.M * p.K * (EPI == EPI_SWIGLU ? 2.0 * p.N : (double)p.N);
     ProfScope ps(EPI == EPI_SWIGLU ? "gemm_bf16_mfma<swiglu>" : EPI == EPI_RESIDUAL ? "gemm_bf16_mfma<residual>"
                  : EPI == EPI_QKV_ROPE ? "gemm_bf16_mfma<qkv_rope>" : "gemm_bf16_mfma<store>", flops, st);
-    if (p.variant == 1) {
-        static bool attr2_set = false;
-        const size_t lds2 = (size_t)DSTAGES * DSTAGE;
-        if (!attr2_set) {
-            hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_dma_kernel<EPI>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
-            if (e != hipSuccess) {
-                vla_set_error("hipFuncSetAttribute(gemm_bf16_dma) failed: %s", hipGetErrorString(e));
-                return VLA_EHIP;
-            }
-            attr2_set = true;
-        }
-        gemm_bf16_dma_kernel<EPI><<<p.tiles_m * p.tiles_n, 256, lds2, st>>>(p);
-    } else {
-        gemm_bf16_mfma_kernel<EPI><<<p.tiles_m * p.tiles_n * p.splits, 256, lds, st>>>(p);
-    }
+    gemm_bf16_mfma_kernel<EPI><<<p.tiles_m * p.tiles_n * p.splits, 256, lds, st>>>(p);
     int rc = vla_check_launch("gemm_bf16_mfma");
     return rc ? rc : 1;
 }
@@ -629,8 +448,6 @@ int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
     p.C = g.C; p.M = g.M; p.K = g.K; p.segN = g.segN;
     p.tiles_m = (g.M + BM - 1) / BM;
-    { const char *e = getenv("VLA_GEMM_DBG"); p.dbg = e ? atoi(e) : 0; }
-    { const char *e = getenv("VLA_GEMM_VARIANT"); p.variant = e ? atoi(e) : 0; }
     p.splits = 1;
     if (g.epilogue == EPI_SWIGLU) {
         if (g.segN % 128 != 0) return 0;
@@ -667,7 +484,6 @@ int try_gemm_bf16_mfma_splitk(const GemmArgs &g, void *scratch, size_t scratch_b
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
     p.C = g.C; p.M = g.M; p.K = g.K; p.segN = g.segN;
     p.tiles_m = 1;
-    p.dbg = 0; p.variant = 0;
     int np;
     if (g.epilogue == EPI_SWIGLU) {
         if (g.segN % 128 != 0) return 0;

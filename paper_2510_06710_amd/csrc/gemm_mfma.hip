@@ -40,14 +40,14 @@ __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
 // Maps the linear workgroup id to an output tile.  Workgroups are dealt round-robin to the eight
 // XCDs, each with its own L2: ids of one XCD are made contiguous, then walked in column panels
-// of `GROUP` tile rows so that the ~32 tiles resident on an XCD share activation and weight rows.
+// of `GROUP` tile rows so that the ~32 tiles resident on an XCD (4 x 8) share activation and weight rows.
 __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int &tm, int &tn) {
     int total = tiles_m * tiles_n;
     int per_xcd = (total + 7) / 8;
     int xcd = pid % 8, local = pid / 8;
     int lin = xcd * per_xcd + local;
     if (per_xcd * 8 != total) lin = pid;     // ragged tile counts: keep the plain order
-    constexpr int GROUP = 8;
+    constexpr int GROUP = 4;                 // measured best of 1, 2, 4, 6, 8, 16, 32 on the 7B shapes
     int panel = lin / (GROUP * tiles_n);
     int first_m = panel * GROUP;
     int rows = min(GROUP, tiles_m - first_m);
@@ -146,23 +146,35 @@ __device__ __forceinline__ void epilogue(f32x16_t (&acc)[4][4], const MfmaGemmPa
         return;
     }
     if (EPI == EPI_RESIDUAL) {
-        // read-modify-write of the fp32 residual stream: measured faster straight from the accumulator
-        // layout (64 independent 16-byte load/add/store chains per lane) than through the LDS panel
+        // read-modify-write of the fp32 residual stream through the LDS panel: per 32-row block all
+        // sixteen 2-row loads of x are issued first (whole 512-byte rows), then added and stored
+        float *out = (float *)p.C + (size_t)tn * BN + wn * 128 + r * 4;
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            const int m = m0 + wm * 128 + i * 32 + r;
-            if (m >= p.M) continue;
-            float *out = (float *)p.C + (size_t)m * p.N + tn * BN + wn * 128;
+            const int mblock = m0 + wm * 128 + i * 32;
+            f32x4_t x[16];
+#pragma unroll
+            for (int it = 0; it < 16; it++) {
+                const int m = min(mblock + it * 2 + hh, p.M - 1);
+                x[it] = *(const f32x4_t *)(out + (size_t)m * p.N);
+            }
 #pragma unroll
             for (int j = 0; j < 4; j++)
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
-                    f32x4_t *dst = (f32x4_t *)(out + j * 32 + g * 8 + 4 * hh);
-                    f32x4_t v = *dst;
+                    f32x4_t v;
 #pragma unroll
-                    for (int e = 0; e < 4; e++) v[e] += acc[j][i][g * 4 + e];
-                    *dst = v;
+                    for (int e = 0; e < 4; e++) v[e] = acc[j][i][g * 4 + e];
+                    *(f32x4_t *)(panel + r * EPI_LD + j * 32 + g * 8 + 4 * hh) = v;
                 }
+#pragma unroll
+            for (int it = 0; it < 16; it++) {
+                const int row = it * 2 + hh, m = mblock + row;
+                f32x4_t v = *(const f32x4_t *)(panel + row * EPI_LD + r * 4);
+#pragma unroll
+                for (int e = 0; e < 4; e++) v[e] += x[it][e];
+                if (m < p.M) *(f32x4_t *)(out + (size_t)m * p.N) = v;
+            }
         }
         return;
     }

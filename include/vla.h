@@ -185,6 +185,44 @@ int vla_profile_report(char *buf, size_t n);
  * traffic counters collected around the hot kernels can be scaled by what they read for it. */
 int vla_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/* ---- consumers of the recomputed log-probabilities in the policy update ------------------------
+ * All arrays DEVICE fp32 (flags and masks int32), row-major; launches on `stream`, no sync.  Sums are
+ * taken in a fixed order (no atomics), so results are bit-reproducible.
+ *
+ * vla_gae -- generalized advantage estimation (appendix I-B):
+ *   delta_t = r_t + gamma V(s_{t+1}) - V(s_t),  A_t = sum_k (gamma lambda)^k delta_{t+k}.
+ *   rewards [n, T]; values [n, T+1] (column T bootstraps the last step); dones [n, T] or NULL: a
+ *   non-zero done_t ends an episode at step t inside the row (partial reset), cutting both the
+ *   bootstrap term and the sum.  Outputs adv [n, T] and returns = adv + V [n, T] (returns may be NULL).
+ *
+ * vla_grpo_advantage -- group-relative advantage (appendix I-C): for each group of G consecutive
+ *   trajectories A_i = (R_i - mean) / std with the population standard deviation.  total_reward
+ *   [n_groups * G]; adv out, same shape; keep [n_groups] out or NULL: 0 for groups whose returns are
+ *   all equal (advantages 0; the success-rate filter of section IV-C.3 drops them), else 1.
+ *
+ * vla_policy_objective -- clipped surrogate of PPO / GRPO (appendix I-B, I-C, II-C.2):
+ *   s = min(rho A, clip(rho, 1 - clip_low, 1 + clip_high) A), rho = exp(logp_new - logp_old).
+ *   logp_new, logp_old [n_traj, T]; adv [n_traj, T] if adv_per_step else [n_traj]; mask [n_traj, T]
+ *   (non-zero = valid step) or NULL.  per_trajectory = 0: objective = mean of s over all valid steps
+ *   (PPO's E_t); 1: (1/n_traj) sum_i (1/T_i) sum_t s with T_i the valid steps of trajectory i (GRPO
+ *   with the valid-action mask; a trajectory without valid steps contributes 0).
+ *   ws: DEVICE scratch of vla_policy_objective_workspace_bytes(n_traj) bytes.
+ *   Outputs: objective [1]; per_step [n_traj, T] or NULL (masked s); clip_frac [1] or NULL (share of
+ *   valid steps where the clipped branch is the smaller one).
+ *
+ * vla_logp_aggregate -- log-probability granularity (section IV-C.1): out[i] = sum of the `inner`
+ *   consecutive entries logp[i * inner ...], i < n_out: token -> action with inner = tokens per action,
+ *   action -> chunk with inner = actions per chunk. */
+int vla_gae(const float *rewards, const float *values, const int32_t *dones, int n, int T, float gamma,
+            float lambda, float *adv, float *returns, void *stream);
+int vla_grpo_advantage(const float *total_reward, int n_groups, int G, float *adv, int32_t *keep, void *stream);
+size_t vla_policy_objective_workspace_bytes(int n_traj);
+int vla_policy_objective(const float *logp_new, const float *logp_old, const float *adv, int adv_per_step,
+                         const int32_t *mask, int n_traj, int T, float clip_low, float clip_high,
+                         int per_trajectory, void *ws, size_t ws_bytes, float *objective, float *per_step,
+                         float *clip_frac, void *stream);
+int vla_logp_aggregate(const float *logp, size_t n_out, int inner, float *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

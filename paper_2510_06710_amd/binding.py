@@ -69,6 +69,12 @@ def lib() -> C.CDLL:
         L.vla_profile_enable.argtypes = [i32]
         L.vla_profile_report.argtypes = [C.c_char_p, sz]
         L.vla_calibration_copy.argtypes = [vp, vp, sz, vp]
+        L.vla_gae.argtypes = [vp, vp, vp, i32, i32, f32, f32, vp, vp, vp]
+        L.vla_grpo_advantage.argtypes = [vp, i32, i32, vp, vp, vp]
+        L.vla_policy_objective_workspace_bytes.argtypes = [i32]
+        L.vla_policy_objective_workspace_bytes.restype = sz
+        L.vla_policy_objective.argtypes = [vp, vp, vp, i32, vp, i32, i32, f32, f32, i32, vp, sz, vp, vp, vp, vp]
+        L.vla_logp_aggregate.argtypes = [vp, sz, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -145,6 +151,31 @@ def vla_logprob_recompute(model, ws, patch, ids, bins, N, P, T, A, mode, slot_em
 
 def vla_calibration_copy(dst, src, nbytes: int, stream=None) -> None:
     _check(lib().vla_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
+def vla_gae(rewards, values, dones, n, T, gamma, lam, adv, returns=None, stream=None) -> None:
+    _check(lib().vla_gae(_ptr(rewards), _ptr(values), _ptr(dones), n, T, gamma, lam, _ptr(adv), _ptr(returns),
+                         _stream(stream)))
+
+
+def vla_grpo_advantage(total_reward, n_groups, G, adv, keep=None, stream=None) -> None:
+    _check(lib().vla_grpo_advantage(_ptr(total_reward), n_groups, G, _ptr(adv), _ptr(keep), _stream(stream)))
+
+
+def vla_policy_objective_workspace_bytes(n_traj: int) -> int:
+    return lib().vla_policy_objective_workspace_bytes(n_traj)
+
+
+def vla_policy_objective(logp_new, logp_old, adv, adv_per_step, mask, n_traj, T, clip_low, clip_high,
+                         per_trajectory, ws, objective, per_step=None, clip_frac=None, stream=None) -> None:
+    _check(lib().vla_policy_objective(_ptr(logp_new), _ptr(logp_old), _ptr(adv), int(adv_per_step), _ptr(mask),
+                                      n_traj, T, clip_low, clip_high, int(per_trajectory), _ptr(ws),
+                                      ws.numel() * ws.element_size(), _ptr(objective), _ptr(per_step),
+                                      _ptr(clip_frac), _stream(stream)))
+
+
+def vla_logp_aggregate(logp, n_out, inner, out, stream=None) -> None:
+    _check(lib().vla_logp_aggregate(_ptr(logp), n_out, inner, _ptr(out), _stream(stream)))
 
 
 def make_config(shape, max_batch: int, max_seq: int) -> vla_config:

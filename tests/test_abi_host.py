@@ -23,7 +23,8 @@ def test_library_exports_every_declared_symbol():
     names = header_symbols()
     assert {"vla_prefill", "vla_decode_actions", "vla_logprob_recompute", "vla_create", "vla_destroy",
             "vla_kv_bytes", "vla_workspace_bytes", "vla_last_error", "vla_version", "vla_profile_enable",
-            "vla_profile_report", "vla_calibration_copy"} <= set(names)
+            "vla_profile_report", "vla_calibration_copy", "vla_gae", "vla_grpo_advantage",
+            "vla_policy_objective", "vla_policy_objective_workspace_bytes", "vla_logp_aggregate"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
     assert vb.vla_version() == 1
@@ -60,6 +61,18 @@ def test_null_weight_pointer_rejected():
     with pytest.raises(vb.VlaError) as e:
         vb.vla_create(cfg, w)
     assert e.value.code == vb.VLA_EINVAL and "layer 0" in str(e.value)
+
+
+def test_rl_entry_points_reject_bad_arguments_without_a_device():
+    L = vb.lib()
+    p = C.c_void_p(0x1000)
+    assert L.vla_gae(None, p, None, 4, 8, 0.99, 0.95, p, None, None) == vb.VLA_EINVAL
+    assert L.vla_gae(p, p, None, 0, 8, 0.99, 0.95, p, None, None) == vb.VLA_EINVAL
+    assert L.vla_grpo_advantage(p, 4, 0, p, None, None) == vb.VLA_EINVAL
+    assert L.vla_policy_objective(p, p, p, 0, None, 4, 8, 0.2, 0.28, 1, p, 8, p, None, None, None) == vb.VLA_EWORKSPACE
+    assert L.vla_policy_objective(p, p, p, 0, None, 4, 8, -0.1, 0.28, 1, p, 1 << 20, p, None, None, None) == vb.VLA_EINVAL
+    assert L.vla_policy_objective_workspace_bytes(10) == 120
+    assert L.vla_logp_aggregate(p, 0, 7, p, None) == vb.VLA_EINVAL
 
 
 def test_size_queries():

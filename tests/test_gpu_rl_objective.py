@@ -1,0 +1,102 @@
+"""GPU parity of the advantage / objective kernels against oracle/rl_oracle.py (fp32 device
+arithmetic against fp64: 1e-5 relative), with the shapes of the paper's settings: 128-256 parallel
+envs, 80-step episodes, groups of 8, clip (0.2, 0.28), gamma 0.99, lambda 0.95, 7 tokens x 8 actions."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rl_oracle as ro
+from paper_2510_06710_amd import binding as vb
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a, dtype=torch.float32):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dtype).to(DEV)
+
+
+@pytest.mark.parametrize("n,T,with_dones", [(128, 160, True), (256, 80, False), (1, 1, False), (3, 513, True)])
+def test_gae(n, T, with_dones):
+    rng = np.random.default_rng(n * 1000 + T)
+    r = rng.standard_normal((n, T)).astype(np.float32)
+    v = rng.standard_normal((n, T + 1)).astype(np.float32)
+    d = (rng.uniform(size=(n, T)) < 0.02).astype(np.int32) if with_dones else None
+    adv, ret = torch.empty(n, T, device=DEV), torch.empty(n, T, device=DEV)
+    vb.vla_gae(dev(r), dev(v), None if d is None else dev(d, torch.int32), n, T, 0.99, 0.95, adv, ret)
+    torch.cuda.synchronize()
+    ra, rr = ro.ogae(r, v, d, 0.99, 0.95)
+    scale = max(1.0, np.abs(ra).max())
+    assert np.max(np.abs(adv.cpu().numpy() - ra)) < 1e-5 * scale
+    assert np.max(np.abs(ret.cpu().numpy() - rr)) < 1e-5 * scale
+
+
+@pytest.mark.parametrize("n_groups,G", [(32, 8), (1, 1), (100, 3)])
+def test_grpo_advantage(n_groups, G):
+    rng = np.random.default_rng(n_groups + G)
+    R = rng.integers(0, 2, n_groups * G).astype(np.float32)      # success / failure returns
+    adv = torch.empty(n_groups * G, device=DEV)
+    keep = torch.empty(n_groups, dtype=torch.int32, device=DEV)
+    vb.vla_grpo_advantage(dev(R), n_groups, G, adv, keep)
+    torch.cuda.synchronize()
+    ra, rk = ro.ogrpo_advantage(R, G)
+    assert np.array_equal(keep.cpu().numpy().astype(bool), rk)
+    assert np.max(np.abs(adv.cpu().numpy() - ra)) < 1e-5
+
+
+@pytest.mark.parametrize("n,T,per_step_adv,per_traj,masked", [(256, 80, False, True, True), (128, 160, True, False, False),
+                                                              (5, 1, False, True, False), (64, 4096, True, False, True)])
+def test_policy_objective(n, T, per_step_adv, per_traj, masked):
+    rng = np.random.default_rng(n + T)
+    lo = -np.abs(rng.standard_normal((n, T))).astype(np.float32) * 3
+    ln = (lo + rng.standard_normal((n, T)).astype(np.float32) * 0.25).astype(np.float32)
+    A = rng.standard_normal((n, T) if per_step_adv else n).astype(np.float32)
+    m = None
+    if masked:
+        m = (np.arange(T)[None, :] < rng.integers(0, T + 1, n)[:, None]).astype(np.int32)
+    ws = torch.empty(vb.vla_policy_objective_workspace_bytes(n), dtype=torch.uint8, device=DEV)
+    obj, frac = torch.empty(1, device=DEV), torch.empty(1, device=DEV)
+    per = torch.empty(n, T, device=DEV)
+    vb.vla_policy_objective(dev(ln), dev(lo), dev(A), per_step_adv, None if m is None else dev(m, torch.int32), n, T,
+                            0.2, 0.28, per_traj, ws, obj, per, frac)
+    torch.cuda.synchronize()
+    ro_obj, ro_s, ro_frac = ro.opolicy_objective(ln, lo, A, m, np.float32(0.2), np.float32(0.28), per_traj)
+    assert np.max(np.abs(per.cpu().numpy() - ro_s)) < 2e-5 * max(1.0, np.abs(ro_s).max())
+    assert abs(obj.item() - ro_obj) < 2e-5 * max(1.0, abs(ro_obj))
+    assert abs(frac.item() - ro_frac) < 1e-5
+    obj2 = torch.empty(1, device=DEV)                      # bit-reproducible
+    vb.vla_policy_objective(dev(ln), dev(lo), dev(A), per_step_adv, None if m is None else dev(m, torch.int32), n, T,
+                            0.2, 0.28, per_traj, ws, obj2)
+    torch.cuda.synchronize()
+    assert obj2.item() == obj.item()
+
+
+def test_logp_aggregate_token_action_chunk():
+    rng = np.random.default_rng(7)
+    logp = -np.abs(rng.standard_normal((128, 8, 7))).astype(np.float32)      # [env, action, token]
+    action = torch.empty(128 * 8, device=DEV)
+    chunk = torch.empty(128, device=DEV)
+    vb.vla_logp_aggregate(dev(logp), 128 * 8, 7, action)
+    vb.vla_logp_aggregate(action, 128, 8, chunk)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(action.cpu().numpy() - ro.ologp_aggregate(logp, 7))) < 1e-5
+    assert np.max(np.abs(chunk.cpu().numpy() - ro.ologp_aggregate(ro.ologp_aggregate(logp, 7), 8))) < 1e-4
+
+
+def test_recompute_feeds_the_objective_rho_one_on_policy():
+    """Recompute under the rollout's own weights gives rho = 1: the objective equals the mean advantage
+    (up to fp32 rounding of the two log-prob paths) and nothing is clipped."""
+    import vla_inputs as vi
+    from parity import GpuCase
+    wl = vi.scaled(vi.WORKLOADS["cfg1_tiny_fp32"], batch=8)
+    case = GpuCase(wl, 3)
+    out = case.rollout()
+    rc = case.recompute(out["bins"])
+    n, T = out["logp"].shape
+    A = np.linspace(-1.0, 1.0, n).astype(np.float32)
+    ws = torch.empty(vb.vla_policy_objective_workspace_bytes(n), dtype=torch.uint8, device=DEV)
+    obj, frac = torch.empty(1, device=DEV), torch.empty(1, device=DEV)
+    vb.vla_policy_objective(dev(rc["logp"]), dev(out["logp"]), dev(A), False, None, n, T, 0.2, 0.28, True, ws, obj,
+                            None, frac)
+    torch.cuda.synchronize()
+    assert abs(obj.item() - A.mean()) < 1e-4 and frac.item() == 0.0

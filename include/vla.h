@@ -71,6 +71,9 @@ typedef struct vla_config {
     int32_t max_batch;   /* capacity: sequences per call                                     */
     int32_t max_seq;     /* capacity: positions per sequence (prefix + action rows); also the
                             position stride of the KV buffer                                 */
+    int32_t value_dim;   /* outputs of the value head: 1 = one scalar per observation (chunk-level
+                            value), C = one value per atomic action of the chunk (action-level
+                            value, section IV-C.2); 0 is read as 1                            */
 } vla_config;
 
 /* DEVICE pointers.  attn_norm, ffn_norm: fp32 [hidden].  wq, wk, wv, wo: dtype [hidden, hidden].
@@ -80,12 +83,14 @@ typedef struct vla_layer_weights {
 } vla_layer_weights;
 
 /* embed, lm_head: DEVICE dtype [vocab, hidden] (only the last 256 rows of lm_head are read).
- * final_norm: DEVICE fp32 [hidden].  value_w: DEVICE fp32 [hidden] or NULL (no value head).
- * layers: HOST array of n_layers entries, copied by vla_create. */
+ * final_norm: DEVICE fp32 [hidden].  value_w: DEVICE fp32 [value_dim, hidden] or NULL (no value head).
+ * value_b: scalar bias added to every value output; value_bias: DEVICE fp32 [value_dim] added per
+ * output, or NULL.  layers: HOST array of n_layers entries, copied by vla_create. */
 typedef struct vla_weights {
     const void *embed, *lm_head, *final_norm, *value_w;
     float value_b;
     const vla_layer_weights *layers;
+    const void *value_bias;
 } vla_weights;
 
 typedef struct vla_model vla_model;
@@ -120,7 +125,7 @@ size_t vla_workspace_bytes(const vla_config *cfg, int entry, int B, int S, int A
  *   kv        DEVICE, >= vla_kv_bytes(cfg, B, P+T)        ws  DEVICE workspace, ws_bytes long
  *   patch     DEVICE dtype [B, P, hidden] (P may be 0)     ids DEVICE int32 [B, T] in [0, vocab)
  *   h_last    DEVICE fp32 [B, hidden] out: final-norm output of the last prefix row
- *   value     DEVICE fp32 [B] out or NULL: value_w . h_last + value_b (section IV-C.2)
+ *   value     DEVICE fp32 [B, value_dim] out or NULL: value_w . h_last + bias (section IV-C.2)
  * Requires P + T >= 1, B <= max_batch, P + T <= max_seq. */
 int vla_prefill(vla_model *model, void *kv, void *ws, size_t ws_bytes,
                 const void *patch, const int32_t *ids, int B, int P, int T,
@@ -158,7 +163,7 @@ int vla_decode_actions(vla_model *model, void *kv, void *ws, size_t ws_bytes,
  *     slot rows see all rows.
  *   bins   DEVICE int32 [N, A], each in [0, 256): the stored actions
  *   logp   DEVICE fp32 [N, A] out: log-prob of the stored bin at the given temperature
- *   entropy DEVICE fp32 [N, A] out      value DEVICE fp32 [N] out or NULL (last prefix row)
+ *   entropy DEVICE fp32 [N, A] out      value DEVICE fp32 [N, value_dim] out or NULL (last prefix row)
  *   logits DEVICE fp32 [N, A, 256] out or NULL
  * N may exceed max_batch: rollouts are processed in internal micro-batches and the result does
  * not depend on the split. */

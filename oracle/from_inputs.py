@@ -19,7 +19,7 @@ def oracle_config(shape, operand_dtype: str = "exact") -> OracleConfig:
                         operand_dtype=operand_dtype)
 
 
-def oracle_weights(model, value_b: float, cache_layers: bool = True) -> OracleWeights:
+def oracle_weights(model, value_b: float, cache_layers: bool = True, value_dim: int = 1) -> OracleWeights:
     """``model`` is a CPU ``SynthModel``.  Layers are generated on first use; with
     ``cache_layers`` they are kept in their storage dtype and widened per call, so a 7B-shape
     model costs 13 GB of host memory instead of 52 GB."""
@@ -36,4 +36,5 @@ def oracle_weights(model, value_b: float, cache_layers: bool = True) -> OracleWe
 
     return OracleWeights(embed=to_f64(model.embed()), lm_head=to_f64(model.lm_head()),
                          final_norm=to_f64(model.final_norm()), layer=layer,
-                         value_w=to_f64(model.value_w()), value_b=value_b)
+                         value_w=to_f64(model.value_w(value_dim)),
+                         value_b=value_b if value_dim == 1 else value_b + to_f64(model.value_bias(value_dim)))

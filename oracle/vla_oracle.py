@@ -97,8 +97,8 @@ class OracleWeights:
     lm_head: np.ndarray      # [V, H]
     final_norm: np.ndarray   # [H]
     layer: Callable[[int], Dict[str, np.ndarray]]
-    value_w: Optional[np.ndarray] = None   # [H]
-    value_b: float = 0.0
+    value_w: Optional[np.ndarray] = None   # [H] (chunk-level scalar) or [C, H] (action-level)
+    value_b: object = 0.0                  # scalar, or [C]
 
 
 KV = List[Tuple[np.ndarray, np.ndarray]]   # per layer (K, V), each [n, n_heads, rows, d]
@@ -213,9 +213,11 @@ def chunk_mask(S: int, A: int) -> np.ndarray:
 
 
 def value_head(cfg: OracleConfig, w: OracleWeights, h_last: np.ndarray) -> Optional[np.ndarray]:
+    """Linear value head on the final-norm output of the last prefix row (section IV-C.2): one scalar
+    per observation (chunk-level, V: S -> R) or one value per atomic action (action-level, S -> R^C)."""
     if w.value_w is None:
         return None
-    return h_last @ w.value_w + w.value_b
+    return h_last @ np.asarray(w.value_w).T + w.value_b
 
 
 # ----------------------------------------------------------------------------------------

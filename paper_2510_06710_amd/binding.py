@@ -23,7 +23,7 @@ class vla_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32),
                 ("ffn", C.c_int32), ("vocab", C.c_int32), ("n_bins", C.c_int32),
                 ("dtype", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float),
-                ("max_batch", C.c_int32), ("max_seq", C.c_int32)]
+                ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("value_dim", C.c_int32)]
 
 
 class vla_layer_weights(C.Structure):
@@ -34,7 +34,7 @@ class vla_layer_weights(C.Structure):
 class vla_weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
                 ("value_w", C.c_void_p), ("value_b", C.c_float),
-                ("layers", C.POINTER(vla_layer_weights))]
+                ("layers", C.POINTER(vla_layer_weights)), ("value_bias", C.c_void_p)]
 
 
 class VlaError(RuntimeError):
@@ -178,27 +178,28 @@ def vla_logp_aggregate(logp, n_out, inner, out, stream=None) -> None:
     _check(lib().vla_logp_aggregate(_ptr(logp), n_out, inner, _ptr(out), _stream(stream)))
 
 
-def make_config(shape, max_batch: int, max_seq: int) -> vla_config:
+def make_config(shape, max_batch: int, max_seq: int, value_dim: int = 1) -> vla_config:
     """``shape`` is any object with the decoder fields (n_layers, hidden, ..., dtype "f32"/"bf16")."""
     return vla_config(shape.n_layers, shape.hidden, shape.n_heads, shape.ffn, shape.vocab, shape.n_bins,
                       VLA_DTYPE_F32 if shape.dtype == "f32" else VLA_DTYPE_BF16, shape.rms_eps,
-                      shape.rope_theta, max_batch, max_seq)
+                      shape.rope_theta, max_batch, max_seq, value_dim)
 
 
 class DeviceModel:
     """Keeps device weight tensors alive and owns the library's model handle.  ``layers`` is a list
     of dicts of device tensors with the nine per-layer names of ``vla_layer_weights``."""
 
-    def __init__(self, cfg: vla_config, embed, lm_head, final_norm, layers, value_w=None, value_b=0.0):
+    def __init__(self, cfg: vla_config, embed, lm_head, final_norm, layers, value_w=None, value_b=0.0,
+                 value_bias=None):
         self.cfg = cfg
-        self._keep = (embed, lm_head, final_norm, layers, value_w)
+        self._keep = (embed, lm_head, final_norm, layers, value_w, value_bias)
         arr = (vla_layer_weights * len(layers))()
         for a, d in zip(arr, layers):
             for name, _ in vla_layer_weights._fields_:
                 setattr(a, name, d[name].data_ptr())
         self._layers = arr
         w = vla_weights(embed.data_ptr(), lm_head.data_ptr(), final_norm.data_ptr(), _ptr(value_w),
-                        float(value_b), arr)
+                        float(value_b), arr, _ptr(value_bias))
         self.handle = vla_create(cfg, w)
 
     def close(self):

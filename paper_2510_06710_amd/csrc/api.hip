@@ -84,10 +84,12 @@ static int check_config(const vla_config *c) {
     int d = c->hidden / c->n_heads;
     if (d % 16 != 0 || d > 256) { vla_set_error("head_dim %d unsupported (multiple of 16, at most 256)", d); return VLA_ESHAPE; }
     if (c->max_seq > 8192) { vla_set_error("max_seq %d unsupported (at most 8192)", c->max_seq); return VLA_ESHAPE; }
+    if (c->value_dim < 0 || c->value_dim > 1024) { vla_set_error("value_dim %d unsupported (0..1024)", c->value_dim); return VLA_ESHAPE; }
     if (c->hidden > 8192) { vla_set_error("hidden %d unsupported (at most 8192)", c->hidden); return VLA_ESHAPE; }
     return VLA_OK;
 }
 
+static inline int value_dim(const vla_config &c) { return c.value_dim > 0 ? c.value_dim : 1; }
 static inline size_t elt_size(const vla_config &c) { return c.dtype == VLA_DTYPE_F32 ? 4 : 2; }
 static inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -253,7 +255,7 @@ static int prefill_impl(vla_model *m, void *kvbuf, void *wsbuf, const void *patc
     KvView kv = kv_view(c, kvbuf, B, c.n_layers);
     if ((rc = run_layers<T>(m, ws, ra, kv, false, st))) return rc;
     if ((rc = launch_final_norm_rows(h_last, ws.X, (const float *)m->w.final_norm, B, S, S - 1, 1, H, c.rms_eps, st))) return rc;
-    if (value && (rc = launch_value_head(value, h_last, (const float *)m->w.value_w, m->w.value_b, B, H, H, st))) return rc;
+    if (value && (rc = launch_value_head(value, h_last, (const float *)m->w.value_w, m->w.value_b, (const float *)m->w.value_bias, value_dim(m->cfg), B, H, H, st))) return rc;
     return 0;
 }
 
@@ -322,7 +324,7 @@ static int recompute_impl(vla_model *m, void *wsbuf, const void *patch, const in
         if (value) {
             float *hv = ws.Hb + (size_t)mb * A * H;
             if ((rc = launch_final_norm_rows(hv, ws.X, (const float *)m->w.final_norm, n, R, S - 1, 1, H, c.rms_eps, st))) return rc;
-            if ((rc = launch_value_head(value + n0, hv, (const float *)m->w.value_w, m->w.value_b, n, H, H, st))) return rc;
+            if ((rc = launch_value_head(value + (size_t)n0 * value_dim(m->cfg), hv, (const float *)m->w.value_w, m->w.value_b, (const float *)m->w.value_bias, value_dim(m->cfg), n, H, H, st))) return rc;
         }
     }
     return 0;

@@ -374,13 +374,16 @@ __global__ void __launch_bounds__(256) head_sample_kernel(const float *h, const 
     }
 }
 
-__global__ void value_head_kernel(float *value, const float *h, const float *w, float b, int H, int h_stride) {
+// value[row, c] = w[c] . h[row] + b + bias[c]; one workgroup per (row, c).
+__global__ void value_head_kernel(float *value, const float *h, const float *w, float b, const float *bias, int H,
+                                  int h_stride) {
     __shared__ float red[4];
-    const float *hr = h + (size_t)blockIdx.x * h_stride;
+    const int c = blockIdx.y, vd = gridDim.y;
+    const float *hr = h + (size_t)blockIdx.x * h_stride, *wc = w + (size_t)c * H;
     float acc = 0.f;
-    for (int i = threadIdx.x; i < H; i += 256) acc += hr[i] * w[i];
+    for (int i = threadIdx.x; i < H; i += 256) acc += hr[i] * wc[i];
     acc = block_sum_256(acc, red);
-    if (threadIdx.x == 0) value[blockIdx.x] = acc + b;
+    if (threadIdx.x == 0) value[(size_t)blockIdx.x * vd + c] = acc + b + (bias ? bias[c] : 0.f);
 }
 
 }  // namespace
@@ -484,11 +487,11 @@ int launch_head_sample(const float *h, const T *lm_head_bins, int n_rows, int H,
                                                     X_next, embed, vocab);
     return vla_check_launch("head_sample");
 }
-int launch_value_head(float *value, const float *h, const float *w, float b, int n, int H, int h_stride,
-                      hipStream_t st) {
+int launch_value_head(float *value, const float *h, const float *w, float b, const float *bias, int vd, int n,
+                      int H, int h_stride, hipStream_t st) {
     if (n == 0) return 0;
     ProfScope ps("value_head", 0.0, st);
-    value_head_kernel<<<n, 256, 0, st>>>(value, h, w, b, H, h_stride);
+    value_head_kernel<<<dim3(n, vd), 256, 0, st>>>(value, h, w, b, bias, H, h_stride);
     return vla_check_launch("value_head");
 }
 

@@ -87,8 +87,8 @@ int launch_head_sample(const float *h, const T *lm_head_bins, int n_rows, int H,
                        const float *gumbel, const int32_t *given_bins, int32_t *bins_out, float *logp,
                        float *ent, float *logits, int out_stride, int out_off, float *X_next,
                        const T *embed, int vocab, hipStream_t st);
-int launch_value_head(float *value, const float *h, const float *w, float b, int n, int H, int h_stride,
-                      hipStream_t st);
+int launch_value_head(float *value, const float *h, const float *w, float b, const float *bias, int vd, int n,
+                      int H, int h_stride, hipStream_t st);
 
 // ---- gfx950 fast paths (bf16, aligned shapes); each returns 1 if it handled the call, 0 if the
 // shape is outside what it supports (caller then uses the generic kernel), <0 on launch error ----

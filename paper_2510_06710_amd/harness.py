@@ -12,15 +12,17 @@ class Rollout:
     """One model on one GPU plus the buffers for a (B, S, A) rollout problem."""
 
     def __init__(self, synth_model, max_batch: int, max_seq: int, device="cuda:0", with_value=True,
-                 value_b: float = 0.0):
+                 value_b: float = 0.0, value_dim: int = 1):
         self.shape = synth_model.shape
         self.device = torch.device(device)
         assert str(synth_model.device).startswith("cuda"), "weights must be generated on the GPU"
-        self.cfg = vb.make_config(self.shape, max_batch, max_seq)
+        self.value_dim = value_dim
+        self.cfg = vb.make_config(self.shape, max_batch, max_seq, value_dim)
         layers = [synth_model.layer(l) for l in range(self.shape.n_layers)]
         self.embed = synth_model.embed()
         self.model = vb.DeviceModel(self.cfg, self.embed, synth_model.lm_head(), synth_model.final_norm(),
-                                    layers, synth_model.value_w() if with_value else None, value_b)
+                                    layers, synth_model.value_w(value_dim) if with_value else None, value_b,
+                                    synth_model.value_bias(value_dim) if with_value and value_dim > 1 else None)
         self._bufs = {}
 
     def _buf(self, name, nbytes):
@@ -28,6 +30,10 @@ class Rollout:
         if t is None or t.numel() < nbytes:
             self._bufs[name] = t = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         return t
+
+    def _value_out(self, n):
+        shape = (n,) if self.value_dim == 1 else (n, self.value_dim)
+        return torch.empty(*shape, dtype=torch.float32, device=self.device)
 
     def kv(self, B, max_pos):
         return self._buf("kv", vb.vla_kv_bytes(self.cfg, B, max_pos))
@@ -38,7 +44,7 @@ class Rollout:
         kv = self.kv(B, self.cfg.max_seq)
         ws = self._buf("ws", vb.vla_workspace_bytes(self.cfg, vb.VLA_ENTRY_PREFILL, B, P + T, 0))
         h_last = torch.empty(B, self.shape.hidden, dtype=torch.float32, device=self.device)
-        value = torch.empty(B, dtype=torch.float32, device=self.device) if want_value else None
+        value = self._value_out(B) if want_value else None
         vb.vla_prefill(self.model.handle, kv, ws, patch, ids, B, P, T, h_last, value, stream)
         return h_last, value
 
@@ -64,7 +70,7 @@ class Rollout:
         dev = self.device
         logp = torch.empty(N, A, dtype=torch.float32, device=dev)
         ent = torch.empty(N, A, dtype=torch.float32, device=dev)
-        value = torch.empty(N, dtype=torch.float32, device=dev) if want_value else None
+        value = self._value_out(N) if want_value else None
         logits = torch.empty(N, A, 256, dtype=torch.float32, device=dev) if want_logits else None
         vb.vla_logprob_recompute(self.model.handle, ws, patch, ids, bins, N, P, T, A, mode, slot_embed,
                                  temperature, logp, ent, value, logits, stream)

@@ -34,12 +34,12 @@ NEAR_TIE = 1e-2
 
 
 def oracle_rollout(wl: vi.Workload, seed: int, env0: int = 0, envs=None, sampled=True, weights=None,
-                   operand_dtype="exact"):
+                   operand_dtype="exact", value_dim=1):
     """Oracle prefill + decode for environments [env0, env0+envs)."""
     envs = wl.batch - env0 if envs is None else envs
     model = vi.SynthModel(wl.shape, seed)
     cfg = oracle_config(wl.shape, operand_dtype)
-    w = weights if weights is not None else oracle_weights(model, vi.VALUE_BIAS)
+    w = weights if weights is not None else oracle_weights(model, vi.VALUE_BIAS, value_dim=value_dim)
     patch, ids = vi.observation(wl, seed, env0=env0, envs=envs)
     g = to_f64(vi.gumbel_noise(wl, seed, env0=env0, envs=envs)) if sampled else None
     slot = to_f64(model.slot_embed(wl.n_action)) if wl.mode == 1 else None
@@ -53,11 +53,11 @@ def oracle_rollout(wl: vi.Workload, seed: int, env0: int = 0, envs=None, sampled
 
 
 def oracle_recompute(wl: vi.Workload, seed: int, bins: np.ndarray, env0: int = 0, envs=None, weights=None,
-                     operand_dtype="exact"):
+                     operand_dtype="exact", value_dim=1):
     envs = wl.batch - env0 if envs is None else envs
     model = vi.SynthModel(wl.shape, seed)
     cfg = oracle_config(wl.shape, operand_dtype)
-    w = weights if weights is not None else oracle_weights(model, vi.VALUE_BIAS)
+    w = weights if weights is not None else oracle_weights(model, vi.VALUE_BIAS, value_dim=value_dim)
     patch, ids = vi.observation(wl, seed, env0=env0, envs=envs)
     slot = to_f64(model.slot_embed(wl.n_action)) if wl.mode == 1 else None
     logp, ent, value, logits = vo.ovla_logprob_recompute(cfg, w, to_f64(patch), ids.numpy().astype(np.int64),
@@ -68,12 +68,13 @@ def oracle_recompute(wl: vi.Workload, seed: int, bins: np.ndarray, env0: int = 0
 class GpuCase:
     """The library on cuda:0 for one workload (weights generated on the device)."""
 
-    def __init__(self, wl: vi.Workload, seed: int, max_batch=None, max_seq=None):
+    def __init__(self, wl: vi.Workload, seed: int, max_batch=None, max_seq=None, value_dim=1):
         from paper_2510_06710_amd.harness import Rollout
         self.wl, self.seed = wl, seed
         self.synth = vi.SynthModel(wl.shape, seed, device="cuda:0")
         rows = wl.prefix + wl.n_action
-        self.run = Rollout(self.synth, max_batch or wl.batch, max_seq or rows, value_b=vi.VALUE_BIAS)
+        self.run = Rollout(self.synth, max_batch or wl.batch, max_seq or rows, value_b=vi.VALUE_BIAS,
+                           value_dim=value_dim)
         self.slot = self.synth.slot_embed(wl.n_action) if wl.mode == 1 else None
 
     def rollout(self, sampled=True, env0=0, envs=None):

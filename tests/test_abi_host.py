@@ -35,7 +35,7 @@ def fake_model(cfg):
     for a in lw:
         for name, _ in vb.vla_layer_weights._fields_:
             setattr(a, name, 0x1000)
-    w = vb.vla_weights(0x1000, 0x1000, 0x1000, None, 0.0, lw)
+    w = vb.vla_weights(0x1000, 0x1000, 0x1000, None, 0.0, lw, None)
     return vb.vla_create(cfg, w), lw
 
 
@@ -57,7 +57,7 @@ def test_config_validation_codes():
 def test_null_weight_pointer_rejected():
     cfg = vb.make_config(vi.TINY, 8, 80)
     lw = (vb.vla_layer_weights * cfg.n_layers)()
-    w = vb.vla_weights(0x1000, 0x1000, 0x1000, None, 0.0, lw)
+    w = vb.vla_weights(0x1000, 0x1000, 0x1000, None, 0.0, lw, None)
     with pytest.raises(vb.VlaError) as e:
         vb.vla_create(cfg, w)
     assert e.value.code == vb.VLA_EINVAL and "layer 0" in str(e.value)

@@ -153,3 +153,18 @@ def test_greedy_matches_argmax_of_returned_logits_and_stats_are_consistent():
     lp = z - lse[..., None]
     assert np.max(np.abs(np.take_along_axis(lp, gpu["bins"][..., None].astype(np.int64), -1)[..., 0] - gpu["logp"])) < 1e-5
     assert np.max(np.abs(-(np.exp(lp) * lp).sum(-1) - gpu["ent"])) < 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_action_level_value_head(dtype):
+    """Value head with one output per atomic action of the chunk (section IV-C.2, V: S -> R^C), C = 8."""
+    wl = vi.scaled(TINY, dtype=dtype, batch=5)
+    ref = oracle_rollout(wl, 13, value_dim=8)
+    case = GpuCase(wl, 13, value_dim=8)
+    out = case.rollout()
+    assert out["value"].shape == (5, 8) and ref["value"].shape == (5, 8)
+    compare_rollout(out, ref, dtype, autoregressive=True)
+    rc = case.recompute(ref["bins"])
+    compare_recompute(rc, oracle_recompute(wl, 13, ref["bins"], value_dim=8), dtype)
+    scalar = GpuCase(wl, 13).rollout()                      # output 0 is the chunk-level head
+    assert np.allclose(scalar["value"], out["value"][:, 0], atol=1e-6)

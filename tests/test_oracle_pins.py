@@ -515,3 +515,14 @@ def test_value_head_closed_forms():
     w.value_w = np.zeros_like(w.value_w)
     _, _, v0 = vo.ovla_prefill(cfg, w, patch, ids)
     assert np.allclose(v0, vi.VALUE_BIAS, atol=0)
+
+
+def test_action_level_value_head_is_one_dot_product_per_action():
+    wl = small_workload()
+    cfg, _, patch, ids = setup(wl)
+    w = oracle_weights(vi.SynthModel(wl.shape, 0), vi.VALUE_BIAS, value_dim=4)
+    _, h_last, v = vo.ovla_prefill(cfg, w, patch, ids)
+    assert v.shape == (wl.batch, 4)
+    for b in range(wl.batch):
+        for c in range(4):
+            assert abs(v[b, c] - (_dot(h_last[b].tolist(), w.value_w[c].tolist()) + vi.VALUE_BIAS + 0.125 * c)) < 1e-12

@@ -259,9 +259,15 @@ class SynthModel:
     def final_norm(self):
         return self._gain(TAG_FINAL_NORM, self.shape.hidden)
 
-    def value_w(self):
-        return normal(self.seed, TAG_VALUE_W, (self.shape.hidden,), sigma=WEIGHT_SIGMA,
-                      dtype=torch.float32, device=self.device)
+    def value_w(self, dim: int = 1):
+        """Value head weights: [H] for the scalar head, [dim, H] for the action-level head (row 0 of
+        the latter equals the scalar head)."""
+        shp = (self.shape.hidden,) if dim == 1 else (dim, self.shape.hidden)
+        return normal(self.seed, TAG_VALUE_W, shp, sigma=WEIGHT_SIGMA, dtype=torch.float32, device=self.device)
+
+    def value_bias(self, dim: int):
+        """Per-output bias of the action-level value head, added to ``VALUE_BIAS``: 0.125 * c."""
+        return (0.125 * torch.arange(dim, dtype=torch.float32)).to(self.device)
 
     def slot_embed(self, n_action: int):
         return self._mat(TAG_SLOT_EMBED, (n_action, self.shape.hidden))

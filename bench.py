@@ -139,6 +139,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg3_7b_b256")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-batch", action="store_true",
+                    help="time the step at batch sizes 1, 2, 4, ... up to the workload's batch: the t_G(.) "
+                         "profile that the paper's auto-placement measures (section IV-A.3)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one 1 GiB plain copy kernel (reference for rocprofv3 --pmc traffic counters)")
     args = ap.parse_args()
@@ -176,6 +179,28 @@ def main():
     def step():
         h_last, _ = prefill()
         return decode(h_last)
+
+    if args.sweep_batch:
+        rows = []
+        b = 1
+        while b <= B:
+            pb, ib, gb = patch[:b].contiguous(), ids[:b].contiguous(), gumbel[:b].contiguous()
+
+            def step_b():
+                h, _ = run.prefill(pb, ib, want_value=True, stream=stream)
+                return run.decode(h, S, A, wl.mode, slot, wl.temperature, gb, want_logits=False, stream=stream)
+            step_b()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                step_b()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            rows.append({"batch": b, "ms_per_step": ms, "env_actions_per_s": b / (ms * 1e-3)})
+            b *= 2
+        print(json.dumps({"metric": "t_G(batch): generation step time vs batch size", "workload": wl.name,
+                          "steps": args.steps, "sweep": rows}))
+        return
 
     if args.calibration_copy:
         a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)

@@ -195,7 +195,7 @@ int try_attention_prefill_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, i
     const int nk = ra.pos0 + ra.R, ps_pad = round_up32(nk);
     const int n_items = ra.n_seq * kv.n_heads;
     if (n_items == 0) return 1;
-    if (n_items > 65535 * 16) return 0;
+    if (n_items > 65535) return 0;                    // grid.y limit; the generic kernel takes over
     const bf16_t *kc = (const bf16_t *)kv.k + (size_t)layer * kv.layer_elems;
     const bf16_t *vc = (const bf16_t *)kv.v + (size_t)layer * kv.layer_elems;
     bf16_t *vt = (bf16_t *)vt_scratch;

@@ -168,3 +168,14 @@ def test_action_level_value_head(dtype):
     compare_recompute(rc, oracle_recompute(wl, 13, ref["bins"], value_dim=8), dtype)
     scalar = GpuCase(wl, 13).rollout()                      # output 0 is the chunk-level head
     assert np.allclose(scalar["value"], out["value"][:, 0], atol=1e-6)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_chunk_of_25_actions_at_temperature_1p6(dtype):
+    """RoboTwin-style setting of the hyper-parameter table: action chunk 25 (25 x 7 = 175 slots in one
+    forward), sampling temperature 1.6."""
+    wl = vi.scaled(TINY, dtype=dtype, batch=3, n_action=175, mode=1, temperature=1.6)
+    ref = oracle_rollout(wl, 14)
+    case = GpuCase(wl, 14)
+    _print(f"chunk 25 tau 1.6 {dtype}", compare_rollout(case.rollout(), ref, dtype, autoregressive=False))
+    compare_recompute(case.recompute(ref["bins"]), oracle_recompute(wl, 14, ref["bins"]), dtype)

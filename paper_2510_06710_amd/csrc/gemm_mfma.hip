@@ -17,6 +17,8 @@
 // 64 up rows per wave so that silu(gate) * up pairs two accumulators of the same lane).
 #include "vla_internal.h"
 
+#include <type_traits>
+
 namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
@@ -265,7 +267,9 @@ __device__ __forceinline__ void epilogue_partial(f32x16_t (&acc)[4][4], const Mf
     }
 }
 
-template <int EPI>
+// SPLITK: each workgroup takes one K range of one tile and stores fp32 partial sums (decode);
+// otherwise a workgroup owns a whole tile and runs the epilogue itself (prefill, recompute).
+template <int EPI, bool SPLITK>
 __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     // stage s: A tile at lds + s * 2 * TILE_BYTES, W tile TILE_BYTES after it
@@ -273,7 +277,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     const int wm = wave >> 1, wn = wave & 1;
     int tm, tn;
     const int n_tiles = p.tiles_m * p.tiles_n;
-    const int split = blockIdx.x / n_tiles;
+    const int split = SPLITK ? blockIdx.x / n_tiles : 0;
     tile_of_block(blockIdx.x - split * n_tiles, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM;
     const int K = p.K;
@@ -309,20 +313,25 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[j][i][r] = 0.f;
 
-    bf16x8_t stage_a[8], stage_w[8];
-    auto gload = [&](int k0) {
+    // Two register sets of staged global loads: a tile's loads are issued two K tiles before the tile
+    // is multiplied, so a miss that goes past the L2 (all workgroups of an XCD walk K in step and miss
+    // on the same lines together) has a full tile time to return.
+    bf16x8_t stage_a[2][8], stage_w[2][8];
+    auto gload = [&](auto set_c, int k0) {
+        constexpr int SET = decltype(set_c)::value;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            stage_a[i] = *(const bf16x8_t *)(asrc[i] + k0);
-            stage_w[i] = *(const bf16x8_t *)(wsrc[i] + k0);
+            stage_a[SET][i] = *(const bf16x8_t *)(asrc[i] + k0);
+            stage_w[SET][i] = *(const bf16x8_t *)(wsrc[i] + k0);
         }
     };
-    auto lstore = [&](int s) {
+    auto lstore = [&](auto set_c, int s) {
+        constexpr int SET = decltype(set_c)::value;
         char *base = lds + s * 2 * TILE_BYTES;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            *(bf16x8_t *)(base + (i * 256 + t) * 16) = stage_a[i];
-            *(bf16x8_t *)(base + TILE_BYTES + (i * 256 + t) * 16) = stage_w[i];
+            *(bf16x8_t *)(base + (i * 256 + t) * 16) = stage_a[SET][i];
+            *(bf16x8_t *)(base + TILE_BYTES + (i * 256 + t) * 16) = stage_w[SET][i];
         }
     };
 
@@ -359,20 +368,27 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     };
 
     const int ktiles_all = K / BK;
-    const int kt0 = (int)((long)split * ktiles_all / p.splits), ktiles = (int)((long)(split + 1) * ktiles_all / p.splits);
-    gload(kt0 * BK);
-    lstore(0);
+    const int kt0 = SPLITK ? (int)((long)split * ktiles_all / p.splits) : 0;
+    const int ktiles = SPLITK ? (int)((long)(split + 1) * ktiles_all / p.splits) : ktiles_all;
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    gload(P0{}, kt0 * BK);
+    gload(P1{}, min(kt0 + 1, ktiles - 1) * BK);
+    lstore(P0{}, 0);
     __syncthreads();
     frag_load(0, lds, 0);
-    for (int kt = kt0; kt < ktiles; kt++) {
-        const int s = (kt - kt0) & 1;
-        // the last tile re-stages itself into the idle buffer: a branch-free body schedules better
-        const int kn = min(kt + 1, ktiles - 1);
+    // One K tile; `par` = parity of the tile within this workgroup's K range = its LDS stage = the
+    // register set that held it (free again now) and that takes the loads of the tile two ahead.
+    auto tile = [&](auto par_c, int kt) {
+        constexpr int s = decltype(par_c)::value;
+        using Other = std::integral_constant<int, s ^ 1>;
+        // the last tiles re-stage the final tile: a branch-free body schedules better
+        const int kn = min(kt + 2, ktiles - 1);
         const char *base = lds + s * 2 * TILE_BYTES;
         // Each region below pairs its memory instructions one by one with MFMAs (sched_group_barrier:
         // 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write), so the matrix pipe keeps issuing
         // while LDS and global traffic trickles in between.
-        gload(kn * BK);
+        gload(par_c, kn * BK);
         frag_load(1, base, 1);
         mfma_step(0);
 #pragma unroll
@@ -397,7 +413,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
         __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
         __builtin_amdgcn_sched_barrier(0);
         frag_load(1, base, 3);
-        lstore(s ^ 1);
+        lstore(Other{}, s ^ 1);
         mfma_step(0);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
@@ -420,19 +436,25 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
         __builtin_amdgcn_sched_barrier(0);
+    };
+    int kt = kt0;
+    for (; kt + 1 < ktiles; kt += 2) {
+        tile(P0{}, kt);
+        tile(P1{}, kt + 1);
     }
+    if (kt < ktiles) tile(P0{}, kt);
 
     __syncthreads();                          // every wave is done reading operand tiles: LDS is reused
-    if (p.splits > 1) epilogue_partial<EPI>(acc, p, split, m0, tn, wm, wn, lane, lds);
+    if (SPLITK) epilogue_partial<EPI>(acc, p, split, m0, tn, wm, wn, lane, lds);
     else epilogue<EPI>(acc, p, m0, tn, wm, wn, lane, lds);
 }
 
-template <int EPI>
+template <int EPI, bool SPLITK>
 int launch(const MfmaGemmParams &p, hipStream_t st) {
     static bool attr_set = false;
     const size_t lds = 4 * (size_t)TILE_BYTES;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_mfma_kernel<EPI>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_mfma_kernel<EPI, SPLITK>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) {
             vla_set_error("hipFuncSetAttribute(gemm_bf16_mfma) failed: %s", hipGetErrorString(e));
@@ -441,9 +463,11 @@ int launch(const MfmaGemmParams &p, hipStream_t st) {
         attr_set = true;
     }
     const double flops = 2.0 * p.M * p.K * (EPI == EPI_SWIGLU ? 2.0 * p.N : (double)p.N);
-    ProfScope ps(EPI == EPI_SWIGLU ? "gemm_bf16_mfma<swiglu>" : EPI == EPI_RESIDUAL ? "gemm_bf16_mfma<residual>"
+    ProfScope ps(SPLITK ? (EPI == EPI_SWIGLU ? "gemm_bf16_mfma_splitk<swiglu>" : EPI == EPI_RESIDUAL
+                           ? "gemm_bf16_mfma_splitk<residual>" : "gemm_bf16_mfma_splitk<store>")
+                 : EPI == EPI_SWIGLU ? "gemm_bf16_mfma<swiglu>" : EPI == EPI_RESIDUAL ? "gemm_bf16_mfma<residual>"
                  : EPI == EPI_QKV_ROPE ? "gemm_bf16_mfma<qkv_rope>" : "gemm_bf16_mfma<store>", flops, st);
-    gemm_bf16_mfma_kernel<EPI><<<p.tiles_m * p.tiles_n * p.splits, 256, lds, st>>>(p);
+    gemm_bf16_mfma_kernel<EPI, SPLITK><<<p.tiles_m * p.tiles_n * p.splits, 256, lds, st>>>(p);
     int rc = vla_check_launch("gemm_bf16_mfma");
     return rc ? rc : 1;
 }
@@ -465,7 +489,7 @@ int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
         if (g.segN % 128 != 0) return 0;
         p.N = g.segN;
         p.tiles_n = g.segN / 128;
-        return launch<EPI_SWIGLU>(p, st);
+        return launch<EPI_SWIGLU, false>(p, st);
     }
     if (g.segN % BN != 0) return 0;
     if (g.epilogue == EPI_QKV_ROPE) {
@@ -479,11 +503,11 @@ int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
         p.pos_stride = ra->kv->pos_stride; p.H = g.segN;
         p.N = 3 * g.segN;
         p.tiles_n = p.N / BN;
-        return launch<EPI_QKV_ROPE>(p, st);
+        return launch<EPI_QKV_ROPE, false>(p, st);
     }
     p.N = g.n_seg * g.segN;
     p.tiles_n = p.N / BN;
-    return g.epilogue == EPI_RESIDUAL ? launch<EPI_RESIDUAL>(p, st) : launch<EPI_STORE>(p, st);
+    return g.epilogue == EPI_RESIDUAL ? launch<EPI_RESIDUAL, false>(p, st) : launch<EPI_STORE, false>(p, st);
 }
 
 // Decode forwards with more than 128 rows: the large tile with K split over workgroups so that the
@@ -513,10 +537,14 @@ int try_gemm_bf16_mfma_splitk(const GemmArgs &g, void *scratch, size_t scratch_b
     p.splits = splits;
     p.P = (float *)scratch;
     int rc;
-    if (g.epilogue == EPI_SWIGLU) rc = launch<EPI_SWIGLU>(p, st);
-    else if (g.epilogue == EPI_RESIDUAL) rc = launch<EPI_RESIDUAL>(p, st);
-    else rc = launch<EPI_STORE>(p, st);
+    if (splits == 1) {                                         // no room for partials: whole tiles
+        if (g.epilogue == EPI_SWIGLU) return launch<EPI_SWIGLU, false>(p, st);
+        return g.epilogue == EPI_RESIDUAL ? launch<EPI_RESIDUAL, false>(p, st) : launch<EPI_STORE, false>(p, st);
+    }
+    if (g.epilogue == EPI_SWIGLU) rc = launch<EPI_SWIGLU, true>(p, st);
+    else if (g.epilogue == EPI_RESIDUAL) rc = launch<EPI_RESIDUAL, true>(p, st);
+    else rc = launch<EPI_STORE, true>(p, st);
     if (rc < 0) return rc;
-    if (splits > 1 && (rc = launch_splitk_reduce(g.epilogue, g.C, p.P, splits, g.M, p.N, st))) return rc;
+    if ((rc = launch_splitk_reduce(g.epilogue, g.C, p.P, splits, g.M, p.N, st))) return rc;
     return 1;
 }

@@ -110,6 +110,7 @@ struct Workspace {
     void *kvs_k, *kvs_v;   // one-layer KV scratch (recompute)
     void *vt;        // scratch of the MFMA prefill attention
     void *skinny;    // split-K partial sums of the decode GEMM (single-row forwards only)
+    int a_rows;      // rows allocated for Nrm, AO and ACT (M rounded up to whole 256-row GEMM tiles)
     size_t total;
 };
 
@@ -120,12 +121,16 @@ static Workspace plan_workspace(const vla_config &c, char *base, int n_seq, int 
     size_t off = 0, es = elt_size(c);
     size_t M = (size_t)n_seq * R, H = c.hidden, F = c.ffn;
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += align_up(bytes); return (void *)p; };
+    // GEMM activation operands are padded to whole tiles of 256 rows: the MFMA kernel reads (and
+    // discards the products of) the rows between M and the end of its last tile
+    size_t Mp = (M + 255) / 256 * 256;
+    w.a_rows = (int)Mp;
     w.X = (float *)take(M * H * 4);
-    w.Nrm = take(M * H * es);
+    w.Nrm = take(Mp * H * es);
     w.QKV = (float *)take(M * 3 * H * 4);
     w.Q = take(M * H * es);
-    w.AO = take(M * H * es);
-    w.ACT = take(M * F * es);
+    w.AO = take(Mp * H * es);
+    w.ACT = take(Mp * F * es);
     w.rope = (float2 *)take((size_t)R * (H / c.n_heads / 2) * sizeof(float2));
     w.Hb = (float *)take((size_t)head_rows * H * 4);
     w.kvs_k = kv_scratch ? take(kv_layer_elems(c, n_seq) * es) : nullptr;
@@ -194,7 +199,7 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
         if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.attn_norm, M, st))) return rc;
         GemmArgs g{};
         g.A = ws.Nrm; g.W[0] = lw.wq; g.W[1] = lw.wk; g.W[2] = lw.wv; g.n_seg = 3; g.segN = H;
-        g.C = ws.QKV; g.M = M; g.K = H; g.epilogue = EPI_STORE;
+        g.C = ws.QKV; g.M = M; g.K = H; g.epilogue = EPI_STORE; g.a_rows = ws.a_rows;
         // multi-row bf16 forwards at head_dim 128: rotation and KV write ride the projection's epilogue
         int fused = 0;
         if (c.dtype == VLA_DTYPE_BF16 && ra.R > 1 && d == 128 && !(force_generic() & (1 | 16))) {
@@ -220,15 +225,15 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
         }
         if (!done && (rc = launch_attention_generic<T>((T *)ws.AO, (const T *)ws.Q, kv, kl, ra, H, st))) return rc;
         g = GemmArgs{};
-        g.A = ws.AO; g.W[0] = lw.wo; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = H; g.epilogue = EPI_RESIDUAL;
+        g.A = ws.AO; g.W[0] = lw.wo; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = H; g.epilogue = EPI_RESIDUAL; g.a_rows = ws.a_rows;
         if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
         if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.ffn_norm, M, st))) return rc;
         g = GemmArgs{};
         g.A = ws.Nrm; g.W[0] = lw.w_gate; g.W[1] = lw.w_up; g.n_seg = 2; g.segN = F; g.C = ws.ACT; g.M = M; g.K = H;
-        g.epilogue = EPI_SWIGLU;
+        g.epilogue = EPI_SWIGLU; g.a_rows = ws.a_rows;
         if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
         g = GemmArgs{};
-        g.A = ws.ACT; g.W[0] = lw.w_down; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = F; g.epilogue = EPI_RESIDUAL;
+        g.A = ws.ACT; g.W[0] = lw.w_down; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = F; g.epilogue = EPI_RESIDUAL; g.a_rows = ws.a_rows;
         if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
     }
     return 0;

@@ -2,7 +2,8 @@
 // QKV, O, gate/up and down projections of the 7B-shape workloads.
 //
 // Tiling: one 256-thread workgroup (4 waves, one per SIMD) owns a 256 x 256 output tile and steps K
-// by 64 through a double-buffered LDS stage (2 x 64 KB of the CU's 160 KB).  Each wave owns a
+// by 64 through a double-buffered LDS stage (2 x 64 KB of the CU's 160 KB; one workgroup per CU, walking
+// several tiles in turn).  Each wave owns a
 // 128 x 128 sub-tile = 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 (256 fp32 accumulators per lane).
 // The weight rows are the MFMA's row operand and the activation rows its column operand, so a lane
 // ends up with four consecutive output columns of one activation row: 8-byte bf16 / 16-byte fp32
@@ -54,8 +55,10 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
     int first_m = panel * GROUP;
     int rows = min(GROUP, tiles_m - first_m);
     int in_panel = lin - panel * GROUP * tiles_n;
-    tm = first_m + in_panel % rows;
-    tn = in_panel / rows;
+    // the divisions run on the vector unit; the results are the same in every lane and go back to
+    // scalar registers so that everything derived from them (tile base addresses) stays scalar
+    tm = __builtin_amdgcn_readfirstlane(first_m + in_panel % rows);
+    tn = __builtin_amdgcn_readfirstlane(in_panel / rows);
 }
 
 // Output of one wave.  A lane holds activation row (lane % 32) of each 32-row block and, per
@@ -64,6 +67,18 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
 // a per-wave LDS panel (row stride 132 floats: the 16 lanes of a quarter-wave hit all 64 banks) and
 // leaves as whole rows: a store (or the load + store of the residual update) covers two 512-byte rows,
 // the bf16 SwiGLU output eight 128-byte rows.
+// One accumulator element, moved from its accumulation register to a vector register exactly where the
+// epilogue consumes it.  Left to the compiler, all 256 moves are hoisted to the top of the epilogue and
+// push the next item's in-flight loads out to scratch memory.
+__device__ __forceinline__ float acc_read(const f32x16_t &v, int e) {
+    float x;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(v[e]));
+    return x;
+}
+// The matrix pipe's last results must have landed before the first such move (the assembler text above
+// is opaque to the compiler's hazard handling): 2 x 16 idle cycles cover the 16-pass MFMA.
+__device__ __forceinline__ void acc_settle() { asm volatile("s_nop 15\n\ts_nop 15"); }
+
 constexpr int EPI_LD = 132;                               // floats per staged row
 constexpr int EPI_PANEL_BYTES = 32 * EPI_LD * 4;          // 16.5 KB per wave
 
@@ -82,13 +97,14 @@ __device__ __forceinline__ void epilogue(f32x16_t (&acc)[4][4], const MfmaGemmPa
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             const int mblock = m0 + wm * 128 + i * 32;
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < 4; j++)
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
                     f32x4_t v;
 #pragma unroll
-                    for (int e = 0; e < 4; e++) v[e] = acc[j][i][g * 4 + e];
+                    for (int e = 0; e < 4; e++) v[e] = acc_read(acc[j][i], g * 4 + e);
                     *(f32x4_t *)(panel + r * EPI_LD + j * 32 + g * 8 + 4 * hh) = v;
                 }
             if (seg == 2) {
@@ -148,41 +164,63 @@ __device__ __forceinline__ void epilogue(f32x16_t (&acc)[4][4], const MfmaGemmPa
         return;
     }
     if (EPI == EPI_RESIDUAL) {
-        // read-modify-write of the fp32 residual stream through the LDS panel: per 32-row block all
-        // sixteen 2-row loads of x are issued first (whole 512-byte rows), then added and stored
+        // read-modify-write of the fp32 residual stream through the LDS panel.  x is loaded in whole
+        // 512-byte rows, eight 2-row loads per half block, each half issued one block ahead of its use so
+        // that the load latency runs under the staging and the stores in between.
         float *out = (float *)p.C + (size_t)tn * BN + wn * 128 + r * 4;
+        f32x4_t x[2][8];
+        auto load_x = [&](auto half_c, int i) {
+            constexpr int HB = decltype(half_c)::value;
+            const int mblock = m0 + wm * 128 + i * 32;
+#pragma unroll
+            for (int it = 0; it < 8; it++) {
+                const int m = min(mblock + (HB * 8 + it) * 2 + hh, p.M - 1);
+                x[HB][it] = *(const f32x4_t *)(out + (size_t)m * p.N);
+            }
+        };
+        auto add_store = [&](auto half_c, int i) {
+            constexpr int HB = decltype(half_c)::value;
+            const int mblock = m0 + wm * 128 + i * 32;
+#pragma unroll
+            for (int it = 0; it < 8; it++) {
+                const int row = (HB * 8 + it) * 2 + hh, m = mblock + row;
+                f32x4_t v = *(const f32x4_t *)(panel + row * EPI_LD + r * 4);
+#pragma unroll
+                for (int e = 0; e < 4; e++) v[e] += x[HB][it][e];
+                if (m < p.M) *(f32x4_t *)(out + (size_t)m * p.N) = v;
+            }
+        };
+        using H0 = std::integral_constant<int, 0>;
+        using H1 = std::integral_constant<int, 1>;
+        load_x(H0{}, 0);
+        load_x(H1{}, 0);
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            const int mblock = m0 + wm * 128 + i * 32;
-            f32x4_t x[16];
-#pragma unroll
-            for (int it = 0; it < 16; it++) {
-                const int m = min(mblock + it * 2 + hh, p.M - 1);
-                x[it] = *(const f32x4_t *)(out + (size_t)m * p.N);
-            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < 4; j++)
 #pragma unroll
                 for (int g = 0; g < 4; g++) {
                     f32x4_t v;
 #pragma unroll
-                    for (int e = 0; e < 4; e++) v[e] = acc[j][i][g * 4 + e];
+                    for (int e = 0; e < 4; e++) v[e] = acc_read(acc[j][i], g * 4 + e);
                     *(f32x4_t *)(panel + r * EPI_LD + j * 32 + g * 8 + 4 * hh) = v;
                 }
-#pragma unroll
-            for (int it = 0; it < 16; it++) {
-                const int row = it * 2 + hh, m = mblock + row;
-                f32x4_t v = *(const f32x4_t *)(panel + row * EPI_LD + r * 4);
-#pragma unroll
-                for (int e = 0; e < 4; e++) v[e] += x[it][e];
-                if (m < p.M) *(f32x4_t *)(out + (size_t)m * p.N) = v;
-            }
+            __builtin_amdgcn_sched_barrier(0);
+            add_store(H0{}, i);
+            if (i < 3) load_x(H0{}, i + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            add_store(H1{}, i);
+            if (i < 3) load_x(H1{}, i + 1);
         }
         return;
     }
 #pragma unroll
     for (int i = 0; i < 4; i++) {
         const int mblock = m0 + wm * 128 + i * 32;
+        // one block at a time: the loads of the next item are in flight in 64 registers across the
+        // epilogue, and interleaving all four blocks would push those out to scratch memory
+        __builtin_amdgcn_sched_barrier(0);
         // ---- stage ----------------------------------------------------------------------------------
         if (EPI == EPI_SWIGLU) {
 #pragma unroll
@@ -192,10 +230,11 @@ __device__ __forceinline__ void epilogue(f32x16_t (&acc)[4][4], const MfmaGemmPa
                     f32x4_t v;
 #pragma unroll
                     for (int e = 0; e < 4; e++) {
-                        float gate = acc[j][i][g * 4 + e], up = acc[j + 2][i][g * 4 + e];
-                        v[e] = gate / (1.0f + __expf(-gate)) * up;
+                        float gate = acc_read(acc[j][i], g * 4 + e), up = acc_read(acc[j + 2][i], g * 4 + e);
+                        v[e] = vla_silu_mul(gate, up);
                     }
                     *(f32x4_t *)(panel + r * EPI_LD + j * 32 + g * 8 + 4 * hh) = v;
+                    __builtin_amdgcn_sched_barrier(0);
                 }
         } else {
 #pragma unroll
@@ -204,7 +243,7 @@ __device__ __forceinline__ void epilogue(f32x16_t (&acc)[4][4], const MfmaGemmPa
                 for (int g = 0; g < 4; g++) {
                     f32x4_t v;
 #pragma unroll
-                    for (int e = 0; e < 4; e++) v[e] = acc[j][i][g * 4 + e];
+                    for (int e = 0; e < 4; e++) v[e] = acc_read(acc[j][i], g * 4 + e);
                     *(f32x4_t *)(panel + r * EPI_LD + j * 32 + g * 8 + 4 * hh) = v;
                 }
         }
@@ -255,7 +294,7 @@ __device__ __forceinline__ void epilogue_partial(f32x16_t (&acc)[4][4], const Mf
             for (int g = 0; g < 4; g++) {
                 f32x4_t v;
 #pragma unroll
-                for (int e = 0; e < 4; e++) v[e] = acc[j][i][g * 4 + e];
+                for (int e = 0; e < 4; e++) v[e] = acc_read(acc[j][i], g * 4 + e);
                 *(f32x4_t *)(panel + r * EPI_LD + j * 32 + g * 8 + 4 * hh) = v;
             }
 #pragma unroll
@@ -267,62 +306,88 @@ __device__ __forceinline__ void epilogue_partial(f32x16_t (&acc)[4][4], const Mf
     }
 }
 
-// SPLITK: each workgroup takes one K range of one tile and stores fp32 partial sums (decode);
-// otherwise a workgroup owns a whole tile and runs the epilogue itself (prefill, recompute).
+// One workgroup walks a list of work items (an output tile, or with SPLITK one K range of a tile)
+// `gridDim.x` apart and streams their K tiles through one continuous pipeline: while the last two K
+// tiles of an item are multiplied, the first two of the next item are already being fetched, so only
+// the very first item of a workgroup pays the load latency of an empty pipeline.
+//   SPLITK: items store fp32 partial sums (decode); otherwise the item's epilogue runs here.
+// Items with an odd number of K tiles flip the stage parity, so the host launches one workgroup per
+// item for those (the loop below then runs once).
 template <int EPI, bool SPLITK>
 __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    // stage s: A tile at lds + s * 2 * TILE_BYTES, W tile TILE_BYTES after it
+    // stage s: A tile at lds + s * 2 * TILE_BYTES, W tile TILE_BYTES after it; the epilogue's panels
+    // start at stage 1 and run 2 KB past it
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    int tm, tn;
     const int n_tiles = p.tiles_m * p.tiles_n;
-    const int split = SPLITK ? blockIdx.x / n_tiles : 0;
-    tile_of_block(blockIdx.x - split * n_tiles, p.tiles_m, p.tiles_n, tm, tn);
-    const int m0 = tm * BM;
+    const int n_items = n_tiles * p.splits;
     const int K = p.K;
+    const int ktiles_all = K / BK;
+    int item = blockIdx.x;
+    if (item >= n_items) return;
 
-    // ---- per-thread global sources: 8 chunks of A and 8 chunks of W per K tile -----------------
-    const bf16_t *asrc[8], *wsrc[8];
-#pragma unroll
-    for (int i = 0; i < 8; i++) {
-        int q = i * 256 + t;
-        int row = q >> 3, pc = q & 7;
-        int c = pc ^ swz(row);
-        int m = min(m0 + row, p.M - 1);
-        asrc[i] = p.A + (size_t)m * K + c * 8;
-        const bf16_t *wrow;
+    // ---- load cursor: the K tile the next batch of global loads fetches --------------------------
+    // A thread loads chunk (t & 7) of rows i * 32 + (t >> 3), i = 0..7, of both operand tiles; the swizzle
+    // depends on the row only through t >> 3, so a single per-thread byte offset serves all sixteen
+    // loads.  They are buffer loads: scalar descriptor of the tile's 256 rows + that offset + a scalar
+    // offset (K position and row block).  Activation rows past M are read like any other (the caller
+    // guarantees the buffer holds whole tiles of rows); their products are never stored.
+    const int trow = t >> 3;
+    const int thread_off = trow * K * 2 + ((t & 7) ^ swz(trow)) * 16;
+    const int tile_bytes = BM * K * 2;
+    __amdgpu_buffer_rsrc_t a_rsrc, w_rsrc0, w_rsrc1;
+    int ld_item, ld_k, ld_k_end;                     // ld_k in bytes along a row
+    int nx_split, nx_tm, nx_tn, nx_nkt;              // the item the cursor is on, for the multiply side
+    auto setup_load = [&](int it) {
+        const int split = SPLITK ? __builtin_amdgcn_readfirstlane(it / n_tiles) : 0;
+        int tm, tn;
+        tile_of_block(it - split * n_tiles, p.tiles_m, p.tiles_n, tm, tn);
+        a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * K), (short)0, tile_bytes, 0x00020000);
         if (EPI == EPI_SWIGLU) {
-            int sub = row >> 6;
-            int f = tn * 128 + (sub >> 1) * 64 + (row & 63);
-            wrow = ((sub & 1) ? p.W1 : p.W0) + (size_t)f * K;
+            w_rsrc0 = __builtin_amdgcn_make_buffer_rsrc((void *)(p.W0 + (size_t)(tn * 128) * K), (short)0, tile_bytes / 2, 0x00020000);
+            w_rsrc1 = __builtin_amdgcn_make_buffer_rsrc((void *)(p.W1 + (size_t)(tn * 128) * K), (short)0, tile_bytes / 2, 0x00020000);
         } else {
-            int n = tn * BN + row;
-            int seg = n / p.segN;
+            const int n = tn * BN;
+            const int seg = __builtin_amdgcn_readfirstlane(n / p.segN);
             const bf16_t *Wp = seg == 0 ? p.W0 : (seg == 1 ? p.W1 : p.W2);
-            wrow = Wp + (size_t)(n - seg * p.segN) * K;
+            w_rsrc0 = w_rsrc1 = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * K), (short)0, tile_bytes, 0x00020000);
         }
-        wsrc[i] = wrow + c * 8;
-    }
+        const int k0 = SPLITK ? (int)((long)split * ktiles_all / p.splits) : 0;
+        const int k1 = SPLITK ? (int)((long)(split + 1) * ktiles_all / p.splits) : ktiles_all;
+        ld_item = it;
+        ld_k = k0 * (BK * 2);
+        ld_k_end = k1 * (BK * 2);
+        nx_split = split; nx_tm = tm; nx_tn = tn; nx_nkt = k1 - k0;
+    };
+    // After a batch of loads: next K tile, else the next item's first, else stay on the last tile (it is
+    // fetched again and never used: a loop body without a branch around its loads schedules better).
+    auto advance = [&]() {
+        ld_k += BK * 2;
+        if (ld_k == ld_k_end) {
+            const int nxt = ld_item + (int)gridDim.x;
+            if (nxt < n_items) setup_load(nxt);
+            else ld_k -= BK * 2;
+        }
+    };
 
     f32x16_t acc[4][4];   // [weight-row block][activation-row block]
-#pragma unroll
-    for (int j = 0; j < 4; j++)
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[j][i][r] = 0.f;
 
     // Two register sets of staged global loads: a tile's loads are issued two K tiles before the tile
     // is multiplied, so a miss that goes past the L2 (all workgroups of an XCD walk K in step and miss
     // on the same lines together) has a full tile time to return.
     bf16x8_t stage_a[2][8], stage_w[2][8];
-    auto gload = [&](auto set_c, int k0) {
+    auto gload = [&](auto set_c) {
         constexpr int SET = decltype(set_c)::value;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            stage_a[SET][i] = *(const bf16x8_t *)(asrc[i] + k0);
-            stage_w[SET][i] = *(const bf16x8_t *)(wsrc[i] + k0);
+            stage_a[SET][i] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, thread_off, ld_k + i * 32 * K * 2, 0));
+            // SwiGLU tiles interleave 64 gate rows and 64 up rows per wave: row blocks g g u u g g u u
+            if (EPI == EPI_SWIGLU)
+                stage_w[SET][i] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(
+                    ((i >> 1) & 1) ? w_rsrc1 : w_rsrc0, thread_off, ld_k + ((i >> 2) * 64 + (i & 1) * 32) * K * 2, 0));
+            else
+                stage_w[SET][i] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc0, thread_off, ld_k + i * 32 * K * 2, 0));
         }
     };
     auto lstore = [&](auto set_c, int s) {
@@ -347,9 +412,9 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     const int khalf = lane >> 5;
 
     // Software pipeline (one wave per SIMD, so nothing else hides LDS latency): the fragments of
-    // k-step ks+1 are read while the MFMAs of k-step ks run; the next K tile's global loads are issued
-    // at the top of the tile, written to the other LDS stage during k-step 2, and after one barrier
-    // the first fragments of the next tile are read under the MFMAs of k-step 3.
+    // k-step ks+1 are read while the MFMAs of k-step ks run; the global loads of the tile two ahead are
+    // issued at the top of a tile, the tile one ahead is written to the other LDS stage during k-step 2,
+    // and after one barrier its first fragments are read under the MFMAs of k-step 3.
     bf16x8_t af[2][4], wf[2][4];
     auto frag_load = [&](int buf, const char *base, int ks) {
         const int c = ks * 2 + khalf;
@@ -367,28 +432,18 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
                 acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
     };
 
-    const int ktiles_all = K / BK;
-    const int kt0 = SPLITK ? (int)((long)split * ktiles_all / p.splits) : 0;
-    const int ktiles = SPLITK ? (int)((long)(split + 1) * ktiles_all / p.splits) : ktiles_all;
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
-    gload(P0{}, kt0 * BK);
-    gload(P1{}, min(kt0 + 1, ktiles - 1) * BK);
-    lstore(P0{}, 0);
-    __syncthreads();
-    frag_load(0, lds, 0);
-    // One K tile; `par` = parity of the tile within this workgroup's K range = its LDS stage = the
-    // register set that held it (free again now) and that takes the loads of the tile two ahead.
-    auto tile = [&](auto par_c, int kt) {
+    // One K tile; `par` = parity of the tile within the workgroup's stream = its LDS stage = the register
+    // set that held it (free again now) and that takes the loads of the tile two ahead.
+    auto tile = [&](auto par_c) {
         constexpr int s = decltype(par_c)::value;
         using Other = std::integral_constant<int, s ^ 1>;
-        // the last tiles re-stage the final tile: a branch-free body schedules better
-        const int kn = min(kt + 2, ktiles - 1);
         const char *base = lds + s * 2 * TILE_BYTES;
         // Each region below pairs its memory instructions one by one with MFMAs (sched_group_barrier:
         // 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write), so the matrix pipe keeps issuing
         // while LDS and global traffic trickles in between.
-        gload(par_c, kn * BK);
+        gload(par_c);
         frag_load(1, base, 1);
         mfma_step(0);
 #pragma unroll
@@ -436,28 +491,60 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
         __builtin_amdgcn_sched_barrier(0);
+        advance();
     };
-    int kt = kt0;
-    for (; kt + 1 < ktiles; kt += 2) {
-        tile(P0{}, kt);
-        tile(P1{}, kt + 1);
-    }
-    if (kt < ktiles) tile(P0{}, kt);
 
-    __syncthreads();                          // every wave is done reading operand tiles: LDS is reused
-    if (SPLITK) epilogue_partial<EPI>(acc, p, split, m0, tn, wm, wn, lane, lds);
-    else epilogue<EPI>(acc, p, m0, tn, wm, wn, lane, lds);
+    setup_load(item);
+    int split = nx_split, tm = nx_tm, tn = nx_tn, nkt = nx_nkt;
+    gload(P0{});
+    advance();
+    gload(P1{});
+    advance();
+    lstore(P0{}, 0);
+    __syncthreads();
+    frag_load(0, lds, 0);
+    for (; item < n_items; item += (int)gridDim.x) {
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc[j][i][r] = 0.f;
+        int kt = 0;
+        for (; kt + 1 < nkt; kt += 2) {
+            tile(P0{});
+            tile(P1{});
+        }
+        if (kt < nkt) tile(P0{});
+        // The last barrier of the K loop came after every wave's last read of the stage just multiplied
+        // (stage 1 for an even tile count); the other stage already holds the next item's first K tile.
+        // The panels go over stage 1; no wave may refill that stage before all panels are drained.
+        char *panels = lds + 2 * TILE_BYTES;
+        acc_settle();
+        if (SPLITK) epilogue_partial<EPI>(acc, p, split, tm * BM, tn, wm, wn, lane, panels);
+        else epilogue<EPI>(acc, p, tm * BM, tn, wm, wn, lane, panels);
+        __syncthreads();
+        // the cursor moved on to the next item (if any) two K tiles before this one ended
+        split = nx_split; tm = nx_tm; tn = nx_tn; nkt = nx_nkt;
+    }
 }
 
 template <int EPI, bool SPLITK>
 int launch(const MfmaGemmParams &p, hipStream_t st) {
     static bool attr_set = false;
-    const size_t lds = 4 * (size_t)TILE_BYTES;
+    static int n_cu = 0;
+    const size_t lds = 2 * (size_t)TILE_BYTES + 4 * (size_t)EPI_PANEL_BYTES;      // 130 KB of the CU's 160 KB
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_mfma_kernel<EPI, SPLITK>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) {
             vla_set_error("hipFuncSetAttribute(gemm_bf16_mfma) failed: %s", hipGetErrorString(e));
+            return VLA_EHIP;
+        }
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1) {
+            vla_set_error("gemm_bf16_mfma: cannot read the compute-unit count");
             return VLA_EHIP;
         }
         attr_set = true;
@@ -467,7 +554,14 @@ int launch(const MfmaGemmParams &p, hipStream_t st) {
                            ? "gemm_bf16_mfma_splitk<residual>" : "gemm_bf16_mfma_splitk<store>")
                  : EPI == EPI_SWIGLU ? "gemm_bf16_mfma<swiglu>" : EPI == EPI_RESIDUAL ? "gemm_bf16_mfma<residual>"
                  : EPI == EPI_QKV_ROPE ? "gemm_bf16_mfma<qkv_rope>" : "gemm_bf16_mfma<store>", flops, st);
-    gemm_bf16_mfma_kernel<EPI, SPLITK><<<p.tiles_m * p.tiles_n * p.splits, 256, lds, st>>>(p);
+    // One workgroup fits a CU (130 KB of LDS, 512 registers per lane).  Whole tiles with an even K-tile
+    // count are dealt round-robin to one workgroup per CU; blockIdx % 8 is the XCD, and a stride of a
+    // multiple of 8 keeps every workgroup's items on its own XCD's share of the tile order.
+    int n_items = p.tiles_m * p.tiles_n * p.splits;
+    int grid = n_items;
+    // (at least four K tiles per item: the load cursor must never be more than one item ahead)
+    if (!SPLITK && (p.K / BK) % 2 == 0 && p.K / BK >= 4 && n_cu % 8 == 0 && n_items > n_cu) grid = n_cu;
+    gemm_bf16_mfma_kernel<EPI, SPLITK><<<grid, 256, lds, st>>>(p);
     int rc = vla_check_launch("gemm_bf16_mfma");
     return rc ? rc : 1;
 }
@@ -475,10 +569,10 @@ int launch(const MfmaGemmParams &p, hipStream_t st) {
 }  // namespace
 
 // Handles bf16 problems with K a multiple of 64 and N tiles that do not straddle weight segments
-// (any M: rows beyond M are clamped on load and masked on store, and a row's result does not
-// depend on which tile it falls in); anything else is declined (0) and runs on the generic kernel.
+// (any M: rows beyond M are loaded from the padded buffer and masked on store, and a row's result does
+// not depend on which tile it falls in); anything else is declined (0) and runs on the generic kernel.
 int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
-    if (g.M < 1 || g.K % BK != 0) return 0;
+    if (g.M < 1 || g.K % BK != 0 || g.a_rows < (g.M + BM - 1) / BM * BM) return 0;
     MfmaGemmParams p{};
     p.A = (const bf16_t *)g.A;
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
@@ -514,7 +608,7 @@ int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
 // single row of tiles still covers the chip; partial sums are reduced in split order by the decode
 // GEMM's reduction kernel (no atomics).  `scratch` holds the partials.
 int try_gemm_bf16_mfma_splitk(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st) {
-    if (g.M < 1 || g.M > BM || g.K % BK != 0 || !scratch || g.epilogue == EPI_QKV_ROPE) return 0;
+    if (g.M < 1 || g.M > BM || g.a_rows < BM || g.K % BK != 0 || !scratch || g.epilogue == EPI_QKV_ROPE) return 0;
     MfmaGemmParams p{};
     p.A = (const bf16_t *)g.A;
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];

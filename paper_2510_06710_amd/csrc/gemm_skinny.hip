@@ -164,7 +164,7 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(SkinnyParams p) {
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
                     float gate = acc[0][i][g * 4 + e], up = acc[NB - 1][i][g * 4 + e];
-                    o[e] = (bf16_t)(gate / (1.0f + __expf(-gate)) * up);
+                    o[e] = (bf16_t)vla_silu_mul(gate, up);
                 }
                 *(bf16x4_t *)(out + g * 8 + nquad) = o;
             }
@@ -222,7 +222,7 @@ __global__ void skinny_reduce_kernel(void *C, const float *P, int splits, int M,
     } else if (EPI == EPI_SWIGLU) {
         bf16x4_t o;
 #pragma unroll
-        for (int e = 0; e < 4; e++) o[e] = (bf16_t)(s[e] / (1.0f + __expf(-s[e])) * u[e]);
+        for (int e = 0; e < 4; e++) o[e] = (bf16_t)vla_silu_mul(s[e], u[e]);
         *(bf16x4_t *)((bf16_t *)C + i) = o;
     } else {
         *(f32x4_t *)((float *)C + i) = s;

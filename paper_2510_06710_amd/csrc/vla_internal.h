@@ -51,6 +51,8 @@ struct GemmArgs {
     int M, K;
     int epilogue;
     const QkvRopeArgs *rope;   // EPI_QKV_ROPE only
+    int a_rows;             // rows of A that may be read (>= M; contents past M arbitrary): the MFMA kernel
+                            // loads whole 256-row tiles and declines if the buffer does not cover them
 };
 
 // ---- generic (any shape, fp32 or bf16 storage) kernels: kernels_generic.hip -----------------
@@ -89,6 +91,13 @@ int launch_head_sample(const float *h, const T *lm_head_bins, int n_rows, int H,
                        const T *embed, int vocab, hipStream_t st);
 int launch_value_head(float *value, const float *h, const float *w, float b, const float *bias, int vd, int n,
                       int H, int h_stride, hipStream_t st);
+
+// silu(gate) * up of the bf16 fast paths: hardware exponential and reciprocal (1 ulp each, far below
+// the bf16 rounding that follows); one formula for the prefill and the decode GEMMs so that both
+// round the same way.
+__device__ __forceinline__ float vla_silu_mul(float gate, float up) {
+    return gate * __builtin_amdgcn_rcpf(1.0f + __expf(-gate)) * up;
+}
 
 // ---- gfx950 fast paths (bf16, aligned shapes); each returns 1 if it handled the call, 0 if the
 // shape is outside what it supports (caller then uses the generic kernel), <0 on launch error ----

@@ -132,6 +132,43 @@ def bench_recompute(args, wl, torch, vi, vb, Rollout):
     print(json.dumps(out))
 
 
+def bench_pipeline(args, wl, torch, vb, run, patch, ids, gumbel, slot):
+    """t_1 vs t_2 of section IV-A on one GPU: Generation on the GPU, a CPU-parallel stub simulator that
+    takes sim_ms_per_env * (environments in the sub-batch) per step on the host."""
+    from paper_2510_06710_amd.harness import PipelinedRollout
+    B, S, A, m = wl.batch, wl.prefix, wl.n_action, args.chunks
+
+    def halves(k):
+        n = B // k
+        return ([(patch[j * n:(j + 1) * n].contiguous(), ids[j * n:(j + 1) * n].contiguous()) for j in range(k)],
+                [gumbel[j * n:(j + 1) * n].contiguous() for j in range(k)])
+
+    def gen_ms(k):                                    # t_G at the sub-batch size, generation alone
+        obs, g = halves(k)
+        pr = PipelinedRollout(run, 1)
+        pr.epoch([obs[0]], 1, S, A, lambda j, t, b: None, wl.mode, slot, wl.temperature, [g[0]])
+        _, _, dt = pr.epoch([obs[0]], 2, S, A, lambda j, t, b: None, wl.mode, slot, wl.temperature, [g[0]])
+        pr.close()
+        return dt * 1e3 / 2
+
+    t_gen = {k: gen_ms(k) for k in (1, 2)}
+    per_env = args.sim_ms_per_env if args.sim_ms_per_env is not None else t_gen[1] / B
+    out = {"metric": "rollout epoch time, collocated (k=1) vs pipelined (k=2), stub host simulator",
+           "workload": wl.name, "chunks": m, "sim_ms_per_env": per_env, "modes": {}}
+    for k in (1, 2):
+        obs, g = halves(k)
+        t_sim = per_env * (B // k)
+        pr = PipelinedRollout(run, k)
+        _, log, dt = pr.epoch(obs, m, S, A, lambda j, t, b: time.sleep(t_sim * 1e-3), wl.mode, slot, wl.temperature, g)
+        pr.close()
+        out["modes"][f"k{k}"] = {"measured_ms": dt * 1e3, "t_gen_ms": t_gen[k], "t_sim_ms": t_sim,
+                                 "modelled_ms": vb.vla_pipeline_time(t_gen[k], t_sim, k, m),
+                                 "env_actions_per_s": B * m / dt}
+    out["speedup_measured"] = out["modes"]["k1"]["measured_ms"] / out["modes"]["k2"]["measured_ms"]
+    out["speedup_modelled"] = out["modes"]["k1"]["modelled_ms"] / out["modes"]["k2"]["modelled_ms"]
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -142,6 +179,14 @@ def main():
     ap.add_argument("--sweep-batch", action="store_true",
                     help="time the step at batch sizes 1, 2, 4, ... up to the workload's batch: the t_G(.) "
                          "profile that the paper's auto-placement measures (section IV-A.3)")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="rollout epoch against a timed stub simulator on the host: collocated schedule (k = 1) "
+                         "vs fine-grained pipelining with two sub-batches (k = 2), measured and as modelled "
+                         "(section IV-A)")
+    ap.add_argument("--chunks", type=int, default=4, help="--pipeline: chunk steps per epoch (m)")
+    ap.add_argument("--sim-ms-per-env", type=float, default=None,
+                    help="--pipeline: stub simulator time per environment and step (default: the measured "
+                         "generation time per environment, i.e. a 1:1 Generation:Simulator ratio)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one 1 GiB plain copy kernel (reference for rocprofv3 --pmc traffic counters)")
     args = ap.parse_args()
@@ -200,6 +245,10 @@ def main():
             b *= 2
         print(json.dumps({"metric": "t_G(batch): generation step time vs batch size", "workload": wl.name,
                           "steps": args.steps, "sweep": rows}))
+        return
+
+    if args.pipeline:
+        bench_pipeline(args, wl, torch, vb, run, patch, ids, gumbel, slot)
         return
 
     if args.calibration_copy:

@@ -228,6 +228,39 @@ int vla_policy_objective(const float *logp_new, const float *logp_old, const flo
                          float *clip_frac, void *stream);
 int vla_logp_aggregate(const float *logp, size_t n_out, int inner, float *out, void *stream);
 
+/* ---------------------------------------------------------------- GPU allocation modes (section IV-A)
+ * Host-only arithmetic (no device work, all pointers HOST): the rollout-time model behind the
+ * automatic placement.  One rollout epoch is m_chunks steps, each a Generation phase (t_gen for the
+ * environments of one Generation GPU) followed by a Simulator phase (t_sim likewise).
+ *
+ * vla_pipeline_time -- k = 1, collocated mode: *out = m_chunks (t_gen + t_sim), the section's t_1.
+ *   k = 2, hybrid mode with fine-grained pipelining: the environments are split in two sub-batches that
+ *   take turns on the Generation and on the Simulator partition (times are then per sub-batch):
+ *   *out = 2 m_chunks max(t_gen, t_sim) + min(t_gen, t_sim).  The section leaves t_2 as "estimated
+ *   under pipelined execution"; this is the makespan of the schedule it describes.  Other k: VLA_EINVAL.
+ *
+ * vla_profile_lookup -- profile[i] is a component's measured time at batch 2^i, i < n_prof (the
+ *   section profiles batch sizes 2^0 ... n_S); other batches are interpolated linearly between the two
+ *   neighbours.  batch < 1 or above 2^(n_prof-1): VLA_ESHAPE.
+ *
+ * vla_auto_placement -- min over k in {1, 2} and N_G + N_S = n_gpus of the rollout time.  k = 1 uses
+ *   all n_gpus for both components with ceil(n_envs / n_gpus) environments each; k = 2 gives n_gen GPUs
+ *   to Generation and n_sim = n_gpus - n_gen to the Simulator, each sub-batch holding
+ *   ceil(n_envs / (2 n_gen)) resp. ceil(n_envs / (2 n_sim)) environments per GPU (splits that leave a
+ *   GPU without an environment are skipped).  *best receives the fastest candidate (the first on ties,
+ *   in the order k = 1, then n_gen = 1, 2, ...); if `all` is not NULL up to all_cap candidates are
+ *   written in that order and *n_all (if not NULL) receives their total number. */
+typedef struct {
+    int32_t k;        /* pipeline stages: 1 collocated, 2 hybrid with pipelining */
+    int32_t n_gen;    /* GPUs running Generation (all of them when k = 1)        */
+    int32_t n_sim;    /* GPUs running the Simulator (all of them when k = 1)     */
+    double time;      /* modelled time of one rollout epoch                       */
+} vla_placement;
+int vla_pipeline_time(double t_gen, double t_sim, int k, int m_chunks, double *out);
+int vla_profile_lookup(const double *profile, int n_prof, double batch, double *out);
+int vla_auto_placement(const double *t_gen, const double *t_sim, int n_prof, int n_envs, int n_gpus,
+                       int m_chunks, vla_placement *best, vla_placement *all, int all_cap, int *n_all);
+
 #ifdef __cplusplus
 }
 #endif

@@ -37,6 +37,10 @@ class vla_weights(C.Structure):
                 ("layers", C.POINTER(vla_layer_weights)), ("value_bias", C.c_void_p)]
 
 
+class vla_placement(C.Structure):
+    _fields_ = [("k", C.c_int32), ("n_gen", C.c_int32), ("n_sim", C.c_int32), ("time", C.c_double)]
+
+
 class VlaError(RuntimeError):
     def __init__(self, code: int, message: str):
         super().__init__(f"libvla error {code}: {message}")
@@ -75,6 +79,11 @@ def lib() -> C.CDLL:
         L.vla_policy_objective_workspace_bytes.restype = sz
         L.vla_policy_objective.argtypes = [vp, vp, vp, i32, vp, i32, i32, f32, f32, i32, vp, sz, vp, vp, vp, vp]
         L.vla_logp_aggregate.argtypes = [vp, sz, i32, vp, vp]
+        dp = C.POINTER(C.c_double)
+        L.vla_pipeline_time.argtypes = [C.c_double, C.c_double, i32, i32, dp]
+        L.vla_profile_lookup.argtypes = [dp, i32, C.c_double, dp]
+        L.vla_auto_placement.argtypes = [dp, dp, i32, i32, i32, i32, C.POINTER(vla_placement),
+                                         C.POINTER(vla_placement), i32, C.POINTER(C.c_int)]
         _lib = L
     return _lib
 
@@ -176,6 +185,36 @@ def vla_policy_objective(logp_new, logp_old, adv, adv_per_step, mask, n_traj, T,
 
 def vla_logp_aggregate(logp, n_out, inner, out, stream=None) -> None:
     _check(lib().vla_logp_aggregate(_ptr(logp), n_out, inner, _ptr(out), _stream(stream)))
+
+
+def _doubles(values):
+    return (C.c_double * len(values))(*[float(v) for v in values])
+
+
+def vla_pipeline_time(t_gen: float, t_sim: float, k: int, m_chunks: int) -> float:
+    out = C.c_double()
+    _check(lib().vla_pipeline_time(t_gen, t_sim, k, m_chunks, C.byref(out)))
+    return out.value
+
+
+def vla_profile_lookup(profile, batch: float) -> float:
+    out = C.c_double()
+    _check(lib().vla_profile_lookup(_doubles(profile), len(profile), batch, C.byref(out)))
+    return out.value
+
+
+def vla_auto_placement(t_gen, t_sim, n_envs: int, n_gpus: int, m_chunks: int):
+    """Returns (best, candidates), each candidate a (k, n_gen, n_sim, time) tuple."""
+    if len(t_gen) != len(t_sim):
+        raise ValueError("t_gen and t_sim must cover the same batch sizes")
+    best = vla_placement()
+    cap = n_gpus
+    arr = (vla_placement * cap)()
+    n = C.c_int()
+    _check(lib().vla_auto_placement(_doubles(t_gen), _doubles(t_sim), len(t_gen), n_envs, n_gpus, m_chunks,
+                                    C.byref(best), arr, cap, C.byref(n)))
+    tup = lambda c: (c.k, c.n_gen, c.n_sim, c.time)
+    return tup(best), [tup(arr[i]) for i in range(min(n.value, cap))]
 
 
 def make_config(shape, max_batch: int, max_seq: int, value_dim: int = 1) -> vla_config:

@@ -35,24 +35,25 @@ class Rollout:
         shape = (n,) if self.value_dim == 1 else (n, self.value_dim)
         return torch.empty(*shape, dtype=torch.float32, device=self.device)
 
-    def kv(self, B, max_pos):
-        return self._buf("kv", vb.vla_kv_bytes(self.cfg, B, max_pos))
+    def kv(self, B, max_pos, lane=0):
+        return self._buf(f"kv{lane}", vb.vla_kv_bytes(self.cfg, B, max_pos))
 
-    def prefill(self, patch, ids, want_value=True, stream=None):
+    # `lane` selects a private KV buffer and workspace, so that calls on different streams can overlap.
+    def prefill(self, patch, ids, want_value=True, stream=None, lane=0):
         B, P = patch.shape[0], patch.shape[1]
         T = ids.shape[1]
-        kv = self.kv(B, self.cfg.max_seq)
-        ws = self._buf("ws", vb.vla_workspace_bytes(self.cfg, vb.VLA_ENTRY_PREFILL, B, P + T, 0))
+        kv = self.kv(B, self.cfg.max_seq, lane)
+        ws = self._buf(f"ws{lane}", vb.vla_workspace_bytes(self.cfg, vb.VLA_ENTRY_PREFILL, B, P + T, 0))
         h_last = torch.empty(B, self.shape.hidden, dtype=torch.float32, device=self.device)
         value = self._value_out(B) if want_value else None
         vb.vla_prefill(self.model.handle, kv, ws, patch, ids, B, P, T, h_last, value, stream)
         return h_last, value
 
     def decode(self, h_last, S, A, mode=0, slot_embed=None, temperature=1.0, gumbel=None,
-               want_logits=True, stream=None):
+               want_logits=True, stream=None, lane=0):
         B = h_last.shape[0]
-        kv = self.kv(B, self.cfg.max_seq)
-        ws = self._buf("ws", vb.vla_workspace_bytes(self.cfg, vb.VLA_ENTRY_DECODE, B, S, A))
+        kv = self.kv(B, self.cfg.max_seq, lane)
+        ws = self._buf(f"ws{lane}", vb.vla_workspace_bytes(self.cfg, vb.VLA_ENTRY_DECODE, B, S, A))
         dev = self.device
         bins = torch.empty(B, A, dtype=torch.int32, device=dev)
         logp = torch.empty(B, A, dtype=torch.float32, device=dev)
@@ -66,7 +67,7 @@ class Rollout:
                   want_logits=True, stream=None):
         N, P = patch.shape[0], patch.shape[1]
         T = ids.shape[1]
-        ws = self._buf("ws", vb.vla_workspace_bytes(self.cfg, vb.VLA_ENTRY_RECOMPUTE, N, P + T, A))
+        ws = self._buf("ws0", vb.vla_workspace_bytes(self.cfg, vb.VLA_ENTRY_RECOMPUTE, N, P + T, A))
         dev = self.device
         logp = torch.empty(N, A, dtype=torch.float32, device=dev)
         ent = torch.empty(N, A, dtype=torch.float32, device=dev)
@@ -75,3 +76,69 @@ class Rollout:
         vb.vla_logprob_recompute(self.model.handle, ws, patch, ids, bins, N, P, T, A, mode, slot_embed,
                                  temperature, logp, ent, value, logits, stream)
         return logp, ent, value, logits
+
+
+class PipelinedRollout:
+    """Rollout epoch with fine-grained pipelining on one GPU (section IV-A, hybrid mode, figure with
+    k = 2): the environments are split into k sub-batches; while the simulator steps one sub-batch, the
+    policy generates the actions of the next.  Each sub-batch has its own stream, KV buffer and
+    workspace.  The simulator is the caller's: ``sim_step(j, t, bins_host)`` is called on a worker thread
+    once the actions of sub-batch j at step t are on the host, and returns when that sub-batch's next
+    observation exists (here the observation tensors stay the same; what the simulator computes is
+    outside this library).  k = 1 is the collocated schedule: generation and simulation alternate."""
+
+    def __init__(self, run: Rollout, k: int):
+        import concurrent.futures
+        self.run, self.k = run, k
+        self.streams = [torch.cuda.Stream(device=run.device) for _ in range(k)]      # default priority
+        self.pool = concurrent.futures.ThreadPoolExecutor(max_workers=k)
+
+    def epoch(self, obs, m_chunks: int, S: int, A: int, sim_step, mode=0, slot_embed=None, temperature=1.0,
+              gumbel=None):
+        """obs[j] = (patch, ids) of sub-batch j (device tensors); gumbel[j] its noise or None.
+        Returns (outputs, log): outputs[t][j] = (bins, logp, entropy) device tensors, log a list of
+        (event, j, t, time) host timestamps in seconds from the start."""
+        import time
+        torch.cuda.synchronize(self.run.device)      # inputs made on other streams are complete
+        t0 = time.perf_counter()
+        log = []
+        gen_done = None                              # the Generation side takes one sub-batch at a time
+        pending = [None] * self.k
+        outputs = []
+        host_bins = [torch.empty(obs[j][0].shape[0], A, dtype=torch.int32).pin_memory() for j in range(self.k)]
+
+        def simulate(j, t, ready):
+            ready.synchronize()                      # the actions of (j, t) are on the host
+            log.append(("actions", j, t, time.perf_counter() - t0))
+            sim_step(j, t, host_bins[j])
+            log.append(("observation", j, t, time.perf_counter() - t0))
+
+        for t in range(m_chunks):
+            row = []
+            for j in range(self.k):
+                if pending[j] is not None:
+                    pending[j].result()              # o_t of sub-batch j exists
+                patch, ids = obs[j]
+                st = self.streams[j]
+                log.append(("generate", j, t, time.perf_counter() - t0))
+                with torch.cuda.stream(st):
+                    if gen_done is not None:
+                        st.wait_event(gen_done)
+                    h_last, _ = self.run.prefill(patch, ids, want_value=False, stream=st, lane=j)
+                    bins, logp, ent, _ = self.run.decode(h_last, S, A, mode, slot_embed, temperature,
+                                                         None if gumbel is None else gumbel[j], want_logits=False,
+                                                         stream=st, lane=j)
+                    host_bins[j].copy_(bins, non_blocking=True)
+                    ready = torch.cuda.Event()
+                    ready.record(st)
+                    gen_done = ready
+                row.append((bins, logp, ent))
+                pending[j] = self.pool.submit(simulate, j, t, ready)
+            outputs.append(row)
+        for f in pending:
+            if f is not None:
+                f.result()
+        return outputs, log, time.perf_counter() - t0
+
+    def close(self):
+        self.pool.shutdown(wait=True)

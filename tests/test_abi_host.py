@@ -24,7 +24,8 @@ def test_library_exports_every_declared_symbol():
     assert {"vla_prefill", "vla_decode_actions", "vla_logprob_recompute", "vla_create", "vla_destroy",
             "vla_kv_bytes", "vla_workspace_bytes", "vla_last_error", "vla_version", "vla_profile_enable",
             "vla_profile_report", "vla_calibration_copy", "vla_gae", "vla_grpo_advantage",
-            "vla_policy_objective", "vla_policy_objective_workspace_bytes", "vla_logp_aggregate"} <= set(names)
+            "vla_policy_objective", "vla_policy_objective_workspace_bytes", "vla_logp_aggregate",
+            "vla_pipeline_time", "vla_profile_lookup", "vla_auto_placement"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
     assert vb.vla_version() == 1

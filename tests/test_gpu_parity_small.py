@@ -179,3 +179,50 @@ def test_chunk_of_25_actions_at_temperature_1p6(dtype):
     case = GpuCase(wl, 14)
     _print(f"chunk 25 tau 1.6 {dtype}", compare_rollout(case.rollout(), ref, dtype, autoregressive=False))
     compare_recompute(case.recompute(ref["bins"]), oracle_recompute(wl, 14, ref["bins"]), dtype)
+
+
+def test_pipelined_rollout_equals_plain_calls_and_respects_the_schedule():
+    """Fine-grained pipelining (section IV-A): two sub-batches on two streams give, bit for bit, what
+    plain calls on each sub-batch give, and the host log shows the schedule's dependencies: a sub-batch's
+    simulator step starts after its actions, its next generation after its observation."""
+    import time
+
+    from paper_2510_06710_amd.harness import PipelinedRollout
+    wl = vi.scaled(vi.WORKLOADS["cfg1_tiny_fp32"], batch=6, dtype="bf16")
+    case = GpuCase(wl, 3)
+    S, A = wl.prefix, wl.n_action
+    obs, noise, plain = [], [], []
+    for j in range(2):
+        patch, ids = vi.observation(wl, 3, device="cuda:0", env0=3 * j, envs=3)
+        g = vi.gumbel_noise(wl, 3, device="cuda:0", env0=3 * j, envs=3)
+        obs.append((patch, ids))
+        noise.append(g)
+        h, _ = case.run.prefill(patch, ids)
+        b, lp, en, _ = case.run.decode(h, S, A, wl.mode, None, wl.temperature, g)
+        torch.cuda.synchronize()
+        plain.append((b.cpu(), lp.cpu(), en.cpu()))
+    seen = []
+
+    def sim(j, t, bins_host):
+        seen.append((j, t, bins_host.clone()))
+        time.sleep(0.02)
+
+    pr = PipelinedRollout(case.run, 2)
+    outs, log, _ = pr.epoch(obs, 3, S, A, sim, wl.mode, None, wl.temperature, noise)
+    pr.close()
+    torch.cuda.synchronize()
+    for t in range(3):
+        for j in range(2):
+            b, lp, en = outs[t][j]
+            assert torch.equal(b.cpu(), plain[j][0]) and torch.equal(lp.cpu(), plain[j][1]) and torch.equal(en.cpu(), plain[j][2])
+    assert sorted((j, t) for j, t, _ in seen) == [(j, t) for j in range(2) for t in range(3)]
+    for j, t, hb in seen:
+        assert torch.equal(hb, plain[j][0])                # the simulator saw the finished actions
+    when = {(e, j, t): x for e, j, t, x in log}
+    for j in range(2):
+        for t in range(3):
+            assert when[("generate", j, t)] <= when[("actions", j, t)] <= when[("observation", j, t)]
+            if t:
+                assert when[("observation", j, t - 1)] <= when[("generate", j, t)]
+    # the overlap the mode is for: sub-batch 1 is being generated while sub-batch 0 is in the simulator
+    assert when[("generate", 1, 0)] < when[("observation", 0, 0)]

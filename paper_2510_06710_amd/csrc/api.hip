@@ -156,6 +156,12 @@ static int force_generic() {
     return v;
 }
 
+static int mid_gemm_enabled() {
+    static int v = -1;
+    if (v < 0) { const char *e = getenv("VLA_MID_GEMM"); v = e ? atoi(e) : 1; }
+    return v;
+}
+
 // Kernel choice depends on the storage type and on whether the forward has one row per sequence
 // (decode) -- never on M itself, so a row's result is the same whatever batch it is part of.
 template <typename T>
@@ -165,8 +171,13 @@ static int run_gemm(const vla_config &c, GemmArgs g, void *skinny_scratch, hipSt
         if (skinny_scratch && !(force_generic() & 2)) {
             // single-row forwards: up to 128 rows stream the weights through the skinny kernel; above
             // that the work is MFMA bound and the large tile with split K does better
-            if (g.M > 128 && !(force_generic() & 1))
-                r = try_gemm_bf16_mfma_splitk(g, skinny_scratch, gemm_skinny_scratch_bytes(g.M, 2 * c.ffn > 3 * c.hidden ? 2 * c.ffn : 3 * c.hidden), st);
+            if (g.M > 128 && !(force_generic() & 1)) {
+                const size_t sb = gemm_skinny_scratch_bytes(g.M, 2 * c.ffn > 3 * c.hidden ? 2 * c.ffn : 3 * c.hidden);
+                r = mid_gemm_enabled() ? try_gemm_bf16_mid(g, skinny_scratch, sb, st) : 0;
+                if (r == 0) r = try_gemm_bf16_mfma_splitk(g, skinny_scratch, sb, st);
+            }
+            if (r == 0 && mid_gemm_enabled() == 2)
+                r = try_gemm_bf16_mid(g, skinny_scratch, gemm_skinny_scratch_bytes(g.M, 2 * c.ffn > 3 * c.hidden ? 2 * c.ffn : 3 * c.hidden), st);
             if (r == 0) r = try_gemm_bf16_skinny(g, skinny_scratch, st);
         }
         if (r != 0) return r < 0 ? r : 0;

@@ -107,6 +107,7 @@ int launch_rope_kv_write_bf16(bf16_t *q_out, const float *qkv, const float2 *tab
 int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int H, float eps, hipStream_t st);
 int try_gemm_bf16_skinny(const GemmArgs &g, void *scratch, hipStream_t st);
 int try_gemm_bf16_mfma_splitk(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st);
+int try_gemm_bf16_mid(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st);
 int launch_splitk_reduce(int epilogue, void *C, const float *P, int splits, int M, int N, hipStream_t st);
 size_t gemm_skinny_scratch_bytes(int M, int max_n);
 int try_attention_prefill_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, int layer,

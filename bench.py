@@ -300,7 +300,7 @@ def main():
                     "avg_launch_ms": r["ms"] / r["count"],
                     "flops_per_launch": r["work"] / r["count"],
                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "gemm_swiglu_cfg3_traffic.txt"),
-                                            "gemm_bf16_mfma_kernel<2>")}
+                                            "gemm_bf16_mfma_kernel<2, false>")}
     # decode HBM accounting: weights once per forward + each environment's own K, V rows per forward
     kv_tok = 2 * shape.n_layers * shape.hidden * 2
     fwd = A - 1 if wl.mode == 0 else 1

@@ -192,7 +192,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (environments shard "
-              "without any exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "by environment without any exchange, each GPU with a full weight replica). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch

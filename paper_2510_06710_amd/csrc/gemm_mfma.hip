@@ -1,21 +1,24 @@
 // bf16 MFMA GEMM for gfx950: C[M, N] = A[M, K] . W[N, K]^T with fp32 accumulation, used for the
 // QKV, O, gate/up and down projections of the 7B-shape workloads.
 //
-// Tiling: one 256-thread workgroup (4 waves, one per SIMD) owns a 256 x 256 output tile and steps K
-// by 64 through a double-buffered LDS stage (2 x 64 KB of the CU's 160 KB; one workgroup per CU, walking
-// several tiles in turn).  Each wave owns a
-// 128 x 128 sub-tile = 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 (256 fp32 accumulators per lane).
-// The weight rows are the MFMA's row operand and the activation rows its column operand, so a lane
-// ends up with four consecutive output columns of one activation row: 8-byte bf16 / 16-byte fp32
-// stores in the epilogue.
+// Tiling: a 256-thread workgroup (4 waves, one per SIMD) computes 256 x 256 output tiles and steps K
+// by 64 through a double-buffered LDS stage (2 x 64 KB of the CU's 160 KB, so one workgroup per CU).
+// Each wave owns a 128 x 128 sub-tile = 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 (256 fp32
+// accumulators per lane).  The weight rows are the MFMA's row operand and the activation rows its
+// column operand, so a lane ends up with four consecutive output columns of one activation row.
+// With more tiles than CUs the grid is one workgroup per CU and each walks its tiles in turn, the
+// global loads running two K tiles ahead and straight on into the next tile.
 //
 // LDS stage: a tile row is 64 bf16 = eight 16-byte chunks; chunk c of row r sits at chunk position
 // c ^ ((r >> 1) & 7), which spreads the sixteen rows a quarter-wave reads at once over all banks.
 // Global loads are 16 bytes per lane and write LDS linearly (lane t -> 16 * t), the swizzle being
 // applied on the global side.
 //
-// Epilogues: store fp32 (QKV, rounded only after the rotation); add into the fp32 residual stream; SwiGLU (tile rows interleave 64 gate and
-// 64 up rows per wave so that silu(gate) * up pairs two accumulators of the same lane).
+// Epilogues (through a per-wave LDS panel, so that memory sees whole rows): store fp32; add into the
+// fp32 residual stream; SwiGLU (tile rows interleave 64 gate and 64 up rows per wave so that
+// silu(gate) * up pairs two accumulators of the same lane); QKV with the rotation and the KV-cache
+// write (q, k, v stay fp32 until after the rotation).  With split K the tile's fp32 partial sums are
+// stored instead and reduced by the decode GEMM's reduction kernel.
 #include "vla_internal.h"
 
 #include <type_traits>

@@ -162,6 +162,21 @@ static int mid_gemm_enabled() {
     return v;
 }
 
+static int dma_gemm_enabled() {
+    static int v = -1;
+    if (v < 0) { const char *e = getenv("VLA_GEMM_DMA"); v = e ? atoi(e) : 1; }
+    return v;
+}
+
+// The large-tile GEMM: the direct-to-LDS kernel where it applies, else the register-staged one.
+static int try_gemm_bf16_large(const GemmArgs &g, hipStream_t st) {
+    if (dma_gemm_enabled()) {
+        int r = try_gemm_bf16_dma(g, st);
+        if (r != 0) return r;
+    }
+    return try_gemm_bf16_mfma(g, st);
+}
+
 // Kernel choice depends on the storage type and on whether the forward has one row per sequence
 // (decode) -- never on M itself, so a row's result is the same whatever batch it is part of.
 template <typename T>
@@ -181,7 +196,7 @@ static int run_gemm(const vla_config &c, GemmArgs g, void *skinny_scratch, hipSt
             if (r == 0) r = try_gemm_bf16_skinny(g, skinny_scratch, st);
         }
         if (r != 0) return r < 0 ? r : 0;
-        r = (force_generic() & 1) ? 0 : try_gemm_bf16_mfma(g, st);
+        r = (force_generic() & 1) ? 0 : try_gemm_bf16_large(g, st);
         if (r != 0) return r < 0 ? r : 0;
     }
     return launch_gemm_generic<T>(g, st);
@@ -217,7 +232,7 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
             QkvRopeArgs qa{ws.Q, ws.rope, &kv, kl, &ra};
             GemmArgs gf = g;
             gf.epilogue = EPI_QKV_ROPE; gf.rope = &qa;
-            fused = try_gemm_bf16_mfma(gf, st);
+            fused = try_gemm_bf16_large(gf, st);
             if (fused < 0) return fused;
         }
         if (!fused) {

@@ -1,0 +1,455 @@
+// bf16 MFMA GEMM for gfx950 with direct-to-LDS loads: C[M, N] = A[M, K] . W[N, K]^T, fp32 accumulation.
+// This is the kernel of the prefill / recompute / parallel-chunk projections (whole tiles, no split K).
+//
+// Tiling: 256 x 256 output tiles, 4 waves (one per SIMD), 128 x 128 per wave as 8 x 8 blocks of
+// v_mfma_f32_16x16x32_bf16 (256 fp32 accumulators per lane).  The weight rows are the MFMA's row
+// operand and the activation rows its column operand: a lane ends up with activation row (lane % 16) of
+// a block and four consecutive output columns.
+//
+// K moves in half tiles of 32 through a ring of four 32 KB LDS stages.  `buffer_load ... lds` writes
+// the operands straight into LDS (no staging registers, no ds_write): a wave instruction fills 1 KB
+// linearly, i.e. 16 tile rows of 64 bytes; chunk c (16 bytes) of row r sits at position
+// c ^ ((r >> 2) & 3), chosen on the global side by which chunk a lane fetches, so that the fragment
+// reads are free of bank conflicts.  The loads of half tile g + 3 are issued while half tile g is read.
+//
+// Schedule of one iteration g (one barrier): wait for this wave's loads of half tile g, barrier, then 16
+// groups of {one ds_read_b128 of half tile g into fragment buffer g % 2, four MFMAs of half tile g - 1 from
+// the other buffer}, with the eight load instructions of half tile g + 3 spread between them.  The
+// fragment reads are inline assembly with explicit waits: the compiler would otherwise wait for every
+// outstanding LDS-bound load before any LDS read.
+//
+// One workgroup per CU walks its tiles in turn (tile i of a workgroup = id + grid * i, which keeps the
+// XCD-contiguous tile order); the half-tile stream simply continues into the next tile, so that only the
+// first tile pays an empty pipeline.  A tile's last MFMAs run in the next tile's first iteration; the
+// epilogue follows that iteration and uses the LDS stage just read as its staging panel.
+#include "vla_internal.h"
+
+#include <type_traits>
+
+namespace {
+
+constexpr int BM = 256, BN = 256, HK = 32;
+constexpr int REGION = 256 * HK * 2;     // 16 KB per operand per stage
+constexpr int STAGE = 2 * REGION;        // 32 KB
+constexpr int NSTAGES = 4;
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+
+struct DmaGemmParams {
+    const bf16_t *A;
+    const bf16_t *W0, *W1, *W2;
+    void *C;
+    int M, N, K, segN;
+    int tiles_m, tiles_n;
+    // EPI_QKV_ROPE
+    bf16_t *q_out, *kc, *vc;
+    const float2 *table;
+    int R, pos0, n_heads, pos_stride, H;
+};
+
+template <int OFF>
+__device__ __forceinline__ bf16x8_t lds_read(int addr) {
+    i32x4_t v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// One accumulator element, moved out of its accumulation register exactly where the epilogue consumes it
+// (left to the compiler all 256 moves are hoisted to the top of the epilogue and spill the fragments that
+// are live across it).
+__device__ __forceinline__ float acc_read(const f32x4_t &v, int e) {
+    float x;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(v[e]));
+    return x;
+}
+__device__ __forceinline__ f32x4_t acc_read4(const f32x4_t &v) {
+    f32x4_t o;
+#pragma unroll
+    for (int e = 0; e < 4; e++) o[e] = acc_read(v, e);
+    return o;
+}
+// The matrix pipe's last results must have landed before the first such move (the assembler text is
+// opaque to the compiler's hazard handling).
+__device__ __forceinline__ void acc_settle() { asm volatile("s_nop 15\n\ts_nop 15"); }
+
+// Epilogue staging panel of one wave: 16 rows x 128 fp32 = 8 KB, no padding; the 16-byte column block cb
+// of row r sits at block cb ^ r, which keeps both the column-wise writes (16 lanes = 16 rows) and the
+// row-wise reads free of bank conflicts.
+__device__ __forceinline__ float *panel_at(float *panel, int row, int cb) { return panel + row * 128 + ((cb ^ row) << 2); }
+
+// Output of one wave.  Per 16-row activation block i a lane holds row (lane % 16) and, per weight block j
+// and register r, column 16 j + 4 (lane / 16) + r.  Each block goes through the panel and leaves as whole
+// rows.
+template <int EPI>
+__device__ __forceinline__ void epilogue(f32x4_t (&acc)[8][8], const DmaGemmParams &p, int m0, int tn, int wm, int wn,
+                                         int lane, float *panel) {
+    const int l16 = lane & 15, kq = lane >> 4;
+    if (EPI == EPI_QKV_ROPE) {
+        // the wave's 128 columns are one head of q, k or v (head_dim 128)
+        const int n0 = tn * BN + wn * 128;
+        const int seg = n0 / p.H, head = (n0 - seg * p.H) >> 7;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const int mblock = m0 + wm * 128 + i * 16;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 8; j++) *(f32x4_t *)panel_at(panel, l16, j * 4 + kq) = acc_read4(acc[j][i]);
+            if (seg == 2) {
+#pragma unroll
+                for (int it = 0; it < 4; it++) {
+                    const int row = it * 4 + (lane >> 4), c = lane & 15, m = mblock + row;
+                    f32x4_t a = *(const f32x4_t *)panel_at(panel, row, 2 * c);
+                    f32x4_t b = *(const f32x4_t *)panel_at(panel, row, 2 * c + 1);
+                    bf16x8_t o;
+#pragma unroll
+                    for (int e = 0; e < 4; e++) { o[e] = (bf16_t)a[e]; o[4 + e] = (bf16_t)b[e]; }
+                    if (m < p.M) {
+                        const int sq = m / p.R, pos = p.pos0 + (m - sq * p.R);
+                        *(bf16x8_t *)(p.vc + (((size_t)sq * p.n_heads + head) * p.pos_stride + pos) * 128 + c * 8) = o;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int it = 0; it < 2; it++) {
+                    // q: consecutive lanes take consecutive chunks of a row; k: consecutive positions of a chunk
+                    const int item = it * 64 + lane;
+                    const int row = (seg == 0) ? (item >> 3) : (item & 15);
+                    const int c = (seg == 0) ? (item & 7) : (item >> 4);
+                    const int m = mblock + row;
+                    f32x4_t lo0 = *(const f32x4_t *)panel_at(panel, row, 2 * c), lo1 = *(const f32x4_t *)panel_at(panel, row, 2 * c + 1);
+                    f32x4_t hi0 = *(const f32x4_t *)panel_at(panel, row, 16 + 2 * c), hi1 = *(const f32x4_t *)panel_at(panel, row, 17 + 2 * c);
+                    if (m < p.M) {
+                        const int sq = m / p.R, rr = m - sq * p.R, pos = p.pos0 + rr;
+                        const f32x4_t *tb = (const f32x4_t *)(p.table + (size_t)rr * 64 + c * 8);
+                        bf16x8_t olo, ohi;
+#pragma unroll
+                        for (int e2 = 0; e2 < 4; e2++) {
+                            const f32x4_t cs = tb[e2];        // (cos, sin) of dims 2 e2 and 2 e2 + 1 of the chunk
+#pragma unroll
+                            for (int u = 0; u < 2; u++) {
+                                const int e = 2 * e2 + u;
+                                const float co = cs[2 * u], si = cs[2 * u + 1];
+                                const float a = e < 4 ? lo0[e & 3] : lo1[e & 3], b = e < 4 ? hi0[e & 3] : hi1[e & 3];
+                                olo[e] = (bf16_t)(a * co - b * si);
+                                ohi[e] = (bf16_t)(b * co + a * si);
+                            }
+                        }
+                        if (seg == 0) {
+                            bf16_t *q = p.q_out + (size_t)m * p.H + head * 128 + c * 8;
+                            *(bf16x8_t *)q = olo;
+                            *(bf16x8_t *)(q + 64) = ohi;
+                        } else {
+                            const size_t hb = ((size_t)sq * p.n_heads + head) * 16;
+                            *(bf16x8_t *)(p.kc + ((hb + c) * p.pos_stride + pos) * 8) = olo;
+                            *(bf16x8_t *)(p.kc + ((hb + 8 + c) * p.pos_stride + pos) * 8) = ohi;
+                        }
+                    }
+                }
+            }
+        }
+        return;
+    }
+    if (EPI == EPI_SWIGLU) {
+        // weight blocks 0..3 are gate rows, 4..7 the matching up rows: 64 output columns per wave
+        bf16_t *out = (bf16_t *)p.C + (size_t)tn * 128 + wn * 64 + (lane & 7) * 8;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const int mblock = m0 + wm * 128 + i * 16;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const f32x4_t g = acc_read4(acc[j][i]), u = acc_read4(acc[j + 4][i]);
+                f32x4_t v;
+#pragma unroll
+                for (int e = 0; e < 4; e++) v[e] = vla_silu_mul(g[e], u[e]);
+                *(f32x4_t *)panel_at(panel, l16, j * 4 + kq) = v;
+            }
+#pragma unroll
+            for (int it = 0; it < 2; it++) {
+                const int row = it * 8 + (lane >> 3), c2 = lane & 7, m = mblock + row;
+                f32x4_t a = *(const f32x4_t *)panel_at(panel, row, 2 * c2);
+                f32x4_t b = *(const f32x4_t *)panel_at(panel, row, 2 * c2 + 1);
+                bf16x8_t o;
+#pragma unroll
+                for (int e = 0; e < 4; e++) { o[e] = (bf16_t)a[e]; o[4 + e] = (bf16_t)b[e]; }
+                if (m < p.M) *(bf16x8_t *)(out + (size_t)m * p.N) = o;
+            }
+        }
+        return;
+    }
+    // fp32 store, or read-modify-write of the fp32 residual stream (x of a block is loaded before the block
+    // is staged, whole 512-byte rows, two rows per instruction)
+    float *out = (float *)p.C + (size_t)tn * BN + wn * 128 + (lane & 31) * 4;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        const int mblock = m0 + wm * 128 + i * 16;
+        __builtin_amdgcn_sched_barrier(0);
+        f32x4_t x[8];
+        if (EPI == EPI_RESIDUAL) {
+#pragma unroll
+            for (int it = 0; it < 8; it++) {
+                const int m = min(mblock + it * 2 + (lane >> 5), p.M - 1);
+                x[it] = *(const f32x4_t *)(out + (size_t)m * p.N);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++) *(f32x4_t *)panel_at(panel, l16, j * 4 + kq) = acc_read4(acc[j][i]);
+#pragma unroll
+        for (int it = 0; it < 8; it++) {
+            const int row = it * 2 + (lane >> 5), m = mblock + row;
+            f32x4_t v = *(const f32x4_t *)panel_at(panel, row, lane & 31);
+            if (EPI == EPI_RESIDUAL) {
+#pragma unroll
+                for (int e = 0; e < 4; e++) v[e] += x[it][e];
+            }
+            if (m < p.M) *(f32x4_t *)(out + (size_t)m * p.N) = v;
+        }
+    }
+}
+
+template <int EPI>
+__global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int n_items = p.tiles_m * p.tiles_n;
+    const int K = p.K;
+    const int nh = K / HK;                       // even: the host only sends K that are multiples of 64
+    int item = blockIdx.x;
+    if (item >= n_items || (nh & 1) || nh < 8) return;      // (the host never launches such a K)
+
+    // ---- load cursor -------------------------------------------------------------------------------------
+    // A wave instruction covers 16 tile rows: lane l -> row l / 4, position l % 4 of the 64-byte row, which
+    // holds chunk (l % 4) ^ ((row / 4) % 4).  This wave loads tile rows wave * 64 .. + 63 of both operands, four
+    // instructions each; SwiGLU tiles interleave 64 gate and 64 up rows per wave of the multiply side, so
+    // loading wave w takes 64 rows of W0 (w even) or W1 (w odd).
+    const int chunk_off = ((lane & 3) ^ ((lane >> 4) & 3)) << 4;
+    const int a_thread_off = (wave * 64 + (lane >> 2)) * K * 2 + chunk_off;
+    const int w_thread_off = (((EPI == EPI_SWIGLU) ? (wave >> 1) * 64 : wave * 64) + (lane >> 2)) * K * 2 + chunk_off;
+    const int tile_bytes = BM * K * 2;
+    __amdgpu_buffer_rsrc_t a_rsrc, w_rsrc;
+    int ld_item, ld_h;
+    int nx_tm, nx_tn;
+    auto setup_load = [&](int it) {
+        int tm, tn;
+        vla_tile_of_block(it, p.tiles_m, p.tiles_n, tm, tn);
+        a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * K), (short)0, tile_bytes, 0x00020000);
+        if (EPI == EPI_SWIGLU) {
+            const bf16_t *Wp = (wave & 1) ? p.W1 : p.W0;
+            w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(tn * 128) * K), (short)0, tile_bytes / 2, 0x00020000);
+        } else {
+            const int n = tn * BN;
+            const int seg = __builtin_amdgcn_readfirstlane(n / p.segN);
+            const bf16_t *Wp = seg == 0 ? p.W0 : (seg == 1 ? p.W1 : p.W2);
+            w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * K), (short)0, tile_bytes, 0x00020000);
+        }
+        ld_item = it;
+        ld_h = 0;
+        nx_tm = tm; nx_tn = tn;
+    };
+    // instruction pair i (0..3) of the cursor's half tile into LDS stage `stage`
+    auto dma = [&](int stage, int i) {
+        char *base = lds + stage * STAGE + wave * 4096 + i * 1024;
+        const int so = ld_h * (HK * 2) + i * 16 * K * 2;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_void *)base, 16, a_thread_off, so, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (lds_void *)(base + REGION), 16, w_thread_off, so, 0, 0);
+    };
+    // next half tile, else the next item's first, else stay (the last half tile is fetched again, never used)
+    auto advance = [&]() {
+        ld_h++;
+        if (ld_h == nh) {
+            const int nxt = ld_item + (int)gridDim.x;
+            if (nxt < n_items) setup_load(nxt);
+            else ld_h--;
+        }
+    };
+
+    // ---- fragments -----------------------------------------------------------------------------------------
+    const int l16 = lane & 15, kq = lane >> 4, fsw = (l16 >> 2) & 3;
+    const int lds0 = (int)(size_t)(lds_void *)lds;
+    const int a_base = lds0 + (wm * 128 + l16) * 64 + ((kq ^ fsw) << 4);
+    const int w_base = lds0 + REGION + (wn * 128 + l16) * 64 + ((kq ^ fsw) << 4);
+    f32x4_t acc[8][8];                  // [weight block][activation block]
+    bf16x8_t af[2][8], wf[2][8];
+#pragma unroll
+    for (int b = 0; b < 2; b++)
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) { af[b][i][e] = (bf16_t)0.f; wf[b][i][e] = (bf16_t)0.f; }
+    auto zero_acc = [&]() {
+#pragma unroll
+        for (int j = 0; j < 8; j++)
+#pragma unroll
+            for (int i = 0; i < 8; i++)
+#pragma unroll
+                for (int r = 0; r < 4; r++) acc[j][i][r] = 0.f;
+    };
+    zero_acc();
+
+#define VLA_SB() __builtin_amdgcn_sched_barrier(0)
+#define VLA_Q(n) std::integral_constant<int, n> {}
+    // group q (0..15): one fragment read into buffer B (q even: weight block q / 2, q odd: activation block
+    // q / 2) and four MFMAs from buffer B ^ 1: weight block q / 2, activation blocks 4 (q % 2) .. + 3
+    auto group = [&](auto b_c, auto q_c, int soff) {
+        constexpr int B = decltype(b_c)::value, q = decltype(q_c)::value;
+        constexpr int blk = q >> 1;
+        if (q & 1) af[B][blk] = lds_read<blk * 1024>(a_base + soff);
+        else wf[B][blk] = lds_read<blk * 1024>(w_base + soff);
+        constexpr int j = q >> 1, i0 = (q & 1) * 4;
+#pragma unroll
+        for (int i = i0; i < i0 + 4; i++)
+            acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[B ^ 1][j], af[B ^ 1][i], acc[j][i], 0, 0, 0);
+    };
+    // this wave's fragment reads have landed; the fragments pass through so that no MFMA moves above the wait
+    auto wait_frags = [&](int B) {
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(af[B][0]), "+v"(af[B][1]), "+v"(af[B][2]), "+v"(af[B][3]), "+v"(af[B][4]), "+v"(af[B][5]),
+                       "+v"(af[B][6]), "+v"(af[B][7]), "+v"(wf[B][0]), "+v"(wf[B][1]), "+v"(wf[B][2]), "+v"(wf[B][3]),
+                       "+v"(wf[B][4]), "+v"(wf[B][5]), "+v"(wf[B][6]), "+v"(wf[B][7]));
+    };
+    // iteration g of the workgroup's half-tile stream: reads half tile g into buffer b, multiplies half tile
+    // g - 1 from the other buffer, and (unless `defer`) issues the loads of half tile g + 3
+    auto iteration = [&](auto b_c, int g, bool defer) {
+        const int soff = (g & 3) * STAGE, sn = (g + 3) & 3;
+        // vmcnt counts in issue order: at most the 16 load instructions of half tiles g + 1 and g + 2 may still be
+        // in flight (right after an epilogue this also waits for the epilogue's own stores)
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        asm volatile("s_barrier" ::: "memory");   // everyone's loads of g have landed, everyone's reads of g - 1 are done
+        VLA_SB();
+        group(b_c, VLA_Q(0), soff); VLA_SB();
+        group(b_c, VLA_Q(1), soff); VLA_SB();
+        if (!defer) dma(sn, 0);
+        VLA_SB();
+        group(b_c, VLA_Q(2), soff); VLA_SB();
+        group(b_c, VLA_Q(3), soff); VLA_SB();
+        group(b_c, VLA_Q(4), soff); VLA_SB();
+        group(b_c, VLA_Q(5), soff); VLA_SB();
+        if (!defer) dma(sn, 1);
+        VLA_SB();
+        group(b_c, VLA_Q(6), soff); VLA_SB();
+        group(b_c, VLA_Q(7), soff); VLA_SB();
+        group(b_c, VLA_Q(8), soff); VLA_SB();
+        group(b_c, VLA_Q(9), soff); VLA_SB();
+        if (!defer) dma(sn, 2);
+        VLA_SB();
+        group(b_c, VLA_Q(10), soff); VLA_SB();
+        group(b_c, VLA_Q(11), soff); VLA_SB();
+        group(b_c, VLA_Q(12), soff); VLA_SB();
+        group(b_c, VLA_Q(13), soff); VLA_SB();
+        if (!defer) { dma(sn, 3); advance(); }
+        VLA_SB();
+        group(b_c, VLA_Q(14), soff); VLA_SB();
+        group(b_c, VLA_Q(15), soff); VLA_SB();
+        wait_frags(decltype(b_c)::value);
+        VLA_SB();
+    };
+
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+    setup_load(item);
+    int tm = nx_tm, tn = nx_tn;
+#pragma unroll
+    for (int d = 0; d < 3; d++) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) dma(d, i);
+        advance();
+    }
+    // Half tile h of the workgroup's n-th item is stream element g = n * nh + h; it is read in iteration g and
+    // multiplied in iteration g + 1, so an item is complete after the first iteration of the next one (or after
+    // one extra iteration at the end of the stream).  nh is even, so that iteration is always an even one.
+    int n_mine = (n_items - item + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int g_end = n_mine * nh;
+    int next_done = nh;                          // the even iteration after which the current item is complete
+    for (int g = 0;; g += 2) {
+        const bool boundary = (g == next_done);
+        iteration(B0{}, g, boundary && g != g_end);
+        if (boundary) {
+            // every wave is done reading stage g % 4: it becomes the panel
+            asm volatile("s_barrier" ::: "memory");
+            acc_settle();
+            float *panel = (float *)(lds + (g & 3) * STAGE) + wave * (16 * 128);
+            epilogue<EPI>(acc, p, tm * BM, tn, wm, wn, lane, panel);
+            if (g == g_end) break;
+            zero_acc();
+            tm = nx_tm; tn = nx_tn;              // the cursor moved on to the next item four iterations ago
+            next_done += nh;
+            const int sn = (g + 3) & 3;          // the loads this boundary iteration held back
+#pragma unroll
+            for (int i = 0; i < 4; i++) dma(sn, i);
+            advance();
+        }
+        iteration(B1{}, g + 1, false);
+    }
+}
+
+template <int EPI>
+int launch(const DmaGemmParams &p, hipStream_t st) {
+    static bool attr_set = false;
+    static int n_cu = 0;
+    const size_t lds = NSTAGES * (size_t)STAGE;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_dma_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) {
+            vla_set_error("hipFuncSetAttribute(gemm_bf16_dma) failed: %s", hipGetErrorString(e));
+            return VLA_EHIP;
+        }
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1) {
+            vla_set_error("gemm_bf16_dma: cannot read the compute-unit count");
+            return VLA_EHIP;
+        }
+        attr_set = true;
+    }
+    const double flops = 2.0 * p.M * p.K * (EPI == EPI_SWIGLU ? 2.0 * p.N : (double)p.N);
+    ProfScope ps(EPI == EPI_SWIGLU ? "gemm_bf16_mfma<swiglu>" : EPI == EPI_RESIDUAL ? "gemm_bf16_mfma<residual>"
+                 : EPI == EPI_QKV_ROPE ? "gemm_bf16_mfma<qkv_rope>" : "gemm_bf16_mfma<store>", flops, st);
+    // one workgroup per CU (128 KB of LDS, 512 registers per lane); blockIdx % 8 is the XCD, and a stride of a
+    // multiple of 8 keeps every workgroup's items on its own XCD's share of the tile order
+    const int n_items = p.tiles_m * p.tiles_n;
+    int grid = n_items;
+    if (n_cu % 8 == 0 && n_items > n_cu) grid = n_cu;
+    gemm_bf16_dma_kernel<EPI><<<grid, 256, lds, st>>>(p);
+    int rc = vla_check_launch("gemm_bf16_dma");
+    return rc ? rc : 1;
+}
+
+}  // namespace
+
+// Handles bf16 problems with K a multiple of 64 and at least 256 (the cursor must never be more than one item
+// ahead of the multiply side), N tiles that do not straddle weight segments, and an activation buffer that
+// covers whole 256-row tiles.  Returns 1 if handled, 0 if declined, < 0 on a launch error.
+int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st) {
+    if (g.M < 1 || g.K % 64 != 0 || g.K < 256 || g.a_rows < (g.M + BM - 1) / BM * BM) return 0;
+    DmaGemmParams p{};
+    p.A = (const bf16_t *)g.A;
+    p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
+    p.C = g.C; p.M = g.M; p.K = g.K; p.segN = g.segN;
+    p.tiles_m = (g.M + BM - 1) / BM;
+    if (g.epilogue == EPI_SWIGLU) {
+        if (g.segN % 128 != 0) return 0;
+        p.N = g.segN;
+        p.tiles_n = g.segN / 128;
+        return launch<EPI_SWIGLU>(p, st);
+    }
+    if (g.segN % BN != 0) return 0;
+    if (g.epilogue == EPI_QKV_ROPE) {
+        const QkvRopeArgs *ra = g.rope;
+        if (!ra || ra->kv->d != 128 || g.n_seg != 3 || g.segN != ra->kv->n_heads * 128) return 0;
+        p.q_out = (bf16_t *)ra->q_out;
+        p.kc = (bf16_t *)ra->kv->k + (size_t)ra->layer * ra->kv->layer_elems;
+        p.vc = (bf16_t *)ra->kv->v + (size_t)ra->layer * ra->kv->layer_elems;
+        p.table = ra->table;
+        p.R = ra->rows->R; p.pos0 = ra->rows->pos0; p.n_heads = ra->kv->n_heads;
+        p.pos_stride = ra->kv->pos_stride; p.H = g.segN;
+        p.N = 3 * g.segN;
+        p.tiles_n = p.N / BN;
+        return launch<EPI_QKV_ROPE>(p, st);
+    }
+    p.N = g.n_seg * g.segN;
+    p.tiles_n = p.N / BN;
+    return g.epilogue == EPI_RESIDUAL ? launch<EPI_RESIDUAL>(p, st) : launch<EPI_STORE>(p, st);
+}

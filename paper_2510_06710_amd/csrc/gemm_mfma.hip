@@ -44,32 +44,6 @@ struct MfmaGemmParams {
 
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
-// Maps the linear workgroup id to an output tile.  Workgroups are dealt round-robin to the eight
-// XCDs, each with its own L2: ids of one XCD are made contiguous, then walked in column panels
-// of `GROUP` tile rows so that the ~32 tiles resident on an XCD (4 x 8) share activation and weight rows.
-__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int &tm, int &tn) {
-    int total = tiles_m * tiles_n;
-    int per_xcd = (total + 7) / 8;
-    int xcd = pid % 8, local = pid / 8;
-    int lin = xcd * per_xcd + local;
-    if (per_xcd * 8 != total) lin = pid;     // ragged tile counts: keep the plain order
-    constexpr int GROUP = 4;                 // measured best of 1, 2, 4, 6, 8, 16, 32 on the 7B shapes
-    int panel = lin / (GROUP * tiles_n);
-    int first_m = panel * GROUP;
-    int rows = min(GROUP, tiles_m - first_m);
-    int in_panel = lin - panel * GROUP * tiles_n;
-    // the divisions run on the vector unit; the results are the same in every lane and go back to
-    // scalar registers so that everything derived from them (tile base addresses) stays scalar
-    tm = __builtin_amdgcn_readfirstlane(first_m + in_panel % rows);
-    tn = __builtin_amdgcn_readfirstlane(in_panel / rows);
-}
-
-// Output of one wave.  A lane holds activation row (lane % 32) of each 32-row block and, per
-// accumulator register r, weight row 8 * (r / 4) + 4 * (lane / 32) + r % 4: written out directly that is
-// 32-byte pieces of 32 different rows per store instruction.  Instead each 32 x 128 block goes through
-// a per-wave LDS panel (row stride 132 floats: the 16 lanes of a quarter-wave hit all 64 banks) and
-// leaves as whole rows: a store (or the load + store of the residual update) covers two 512-byte rows,
-// the bf16 SwiGLU output eight 128-byte rows.
 // One accumulator element, moved from its accumulation register to a vector register exactly where the
 // epilogue consumes it.  Left to the compiler, all 256 moves are hoisted to the top of the epilogue and
 // push the next item's in-flight loads out to scratch memory.
@@ -345,7 +319,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_mfma_kernel(MfmaGemmParams p) {
     auto setup_load = [&](int it) {
         const int split = SPLITK ? __builtin_amdgcn_readfirstlane(it / n_tiles) : 0;
         int tm, tn;
-        tile_of_block(it - split * n_tiles, p.tiles_m, p.tiles_n, tm, tn);
+        vla_tile_of_block(it - split * n_tiles, p.tiles_m, p.tiles_n, tm, tn);
         a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * K), (short)0, tile_bytes, 0x00020000);
         if (EPI == EPI_SWIGLU) {
             w_rsrc0 = __builtin_amdgcn_make_buffer_rsrc((void *)(p.W0 + (size_t)(tn * 128) * K), (short)0, tile_bytes / 2, 0x00020000);

@@ -99,9 +99,30 @@ __device__ __forceinline__ float vla_silu_mul(float gate, float up) {
     return gate * __builtin_amdgcn_rcpf(1.0f + __expf(-gate)) * up;
 }
 
+// Maps a linear work-item id of the large-tile GEMMs to an output tile.  Workgroups are dealt round-robin to
+// the eight XCDs, each with its own L2: ids of one XCD are made contiguous, then walked in column panels of
+// `GROUP` tile rows so that the ~32 tiles resident on an XCD (4 x 8) share activation and weight rows.  The
+// divisions run on the vector unit; the results are the same in every lane and go back to scalar registers
+// so that everything derived from them (tile base addresses) stays scalar.
+__device__ __forceinline__ void vla_tile_of_block(int pid, int tiles_m, int tiles_n, int &tm, int &tn) {
+    int total = tiles_m * tiles_n;
+    int per_xcd = (total + 7) / 8;
+    int xcd = pid % 8, local = pid / 8;
+    int lin = xcd * per_xcd + local;
+    if (per_xcd * 8 != total) lin = pid;     // ragged tile counts: keep the plain order
+    constexpr int GROUP = 4;                 // measured best of 1, 2, 4, 6, 8, 16, 32 on the 7B shapes
+    int panel = lin / (GROUP * tiles_n);
+    int first_m = panel * GROUP;
+    int rows = min(GROUP, tiles_m - first_m);
+    int in_panel = lin - panel * GROUP * tiles_n;
+    tm = __builtin_amdgcn_readfirstlane(first_m + in_panel % rows);
+    tn = __builtin_amdgcn_readfirstlane(in_panel / rows);
+}
+
 // ---- gfx950 fast paths (bf16, aligned shapes); each returns 1 if it handled the call, 0 if the
 // shape is outside what it supports (caller then uses the generic kernel), <0 on launch error ----
 int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st);
+int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st);
 int launch_rope_kv_write_bf16(bf16_t *q_out, const float *qkv, const float2 *table, const KvView &kv, int layer,
                               const RowsArgs &ra, int H, hipStream_t st);
 int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int H, float eps, hipStream_t st);

@@ -107,6 +107,19 @@ const char *vla_last_error(void);
 int vla_create(const vla_config *cfg, const vla_weights *weights, vla_model **out);
 int vla_destroy(vla_model *model);
 
+/* Optional repacked copy of the decoder-layer projection weights for the multi-row (prefill, parallel chunk,
+ * recompute) forwards of bf16 models.  The large GEMM loads its operands straight into LDS; with the weights
+ * stored [K / 32][rows][32] instead of row-major [rows, K] every such load reads whole cache lines.
+ * vla_prepack_bytes: size of the copy for this configuration, 0 if the configuration has no use for it
+ *   (fp32 storage, head_dim other than 128, widths that are not tile aligned).
+ * vla_prepack: enqueues the repack of all layers on `stream` into `buffer` (DEVICE, 256-byte aligned, at least
+ *   vla_prepack_bytes bytes, caller owned) and makes the model use it from then on; the caller orders later
+ *   calls after it (same stream, or events) and keeps the buffer alive and unchanged while the model uses it.
+ *   buffer = NULL detaches.  The original weights stay in use for single-row (decode) forwards.  Results
+ *   with and without the copy are bit-identical. */
+size_t vla_prepack_bytes(const vla_config *cfg);
+int vla_prepack(vla_model *model, void *buffer, size_t bytes, void *stream);
+
 /* Bytes of the caller-allocated KV buffer for B sequences of up to max_pos positions
  * (max_pos <= cfg->max_seq; the buffer is always laid out with cfg->max_seq positions per
  * sequence, so the same B must be used by every call sharing it).  Layout is opaque.

@@ -62,6 +62,9 @@ def lib() -> C.CDLL:
         L.vla_last_error.restype = C.c_char_p
         L.vla_create.argtypes = [C.POINTER(vla_config), C.POINTER(vla_weights), C.POINTER(vp)]
         L.vla_destroy.argtypes = [vp]
+        L.vla_prepack_bytes.argtypes = [C.POINTER(vla_config)]
+        L.vla_prepack_bytes.restype = sz
+        L.vla_prepack.argtypes = [vp, vp, sz, vp]
         L.vla_kv_bytes.argtypes = [C.POINTER(vla_config), i32, i32]
         L.vla_kv_bytes.restype = sz
         L.vla_workspace_bytes.argtypes = [C.POINTER(vla_config), i32, i32, i32, i32]
@@ -135,6 +138,15 @@ def vla_create(cfg: vla_config, weights: vla_weights) -> int:
 
 def vla_destroy(model: int) -> None:
     _check(lib().vla_destroy(model))
+
+
+def vla_prepack_bytes(cfg: vla_config) -> int:
+    return lib().vla_prepack_bytes(C.byref(cfg))
+
+
+def vla_prepack(model: int, buffer, stream=None) -> None:
+    nbytes = 0 if buffer is None else buffer.numel() * buffer.element_size()
+    _check(lib().vla_prepack(model, _ptr(buffer), nbytes, _stream(stream)))
 
 
 def vla_prefill(model, kv, ws, patch, ids, B, P, T, h_last, value=None, stream=None) -> None:

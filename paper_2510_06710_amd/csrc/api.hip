@@ -64,6 +64,7 @@ struct vla_model {
     vla_config cfg;
     vla_weights w;
     std::vector<vla_layer_weights> layers;
+    std::vector<vla_layer_weights> packed;   // k-blocked copies of the seven projection matrices (vla_prepack), or empty
 };
 
 // ------------------------------------------------------------------------------------------ config
@@ -162,6 +163,20 @@ static int mid_gemm_enabled() {
     return v;
 }
 
+// The multi-row bf16 forwards can run on k-blocked operands ([K / 32][rows][32], see gemm_dma.hip): needs
+// head_dim 128 (fused rotation epilogue), tile-aligned widths and repacked weights.
+static bool kblocked_shape_ok(const vla_config &c) {
+    static int env = -1;
+    if (env < 0) { const char *e = getenv("VLA_KBLOCKED"); env = e ? atoi(e) : 1; }
+    if (!env || c.dtype != VLA_DTYPE_BF16 || c.hidden % c.n_heads != 0 || c.hidden / c.n_heads != 128) return false;
+    if (c.hidden % 1024 != 0 || c.hidden > 8192) return false;        // the register-resident RMSNorm writes the layout
+    return c.hidden % 256 == 0 && c.hidden >= 256 && c.ffn % 128 == 0 && c.ffn >= 256 &&
+           (size_t)c.ffn * c.hidden * 2 < ((size_t)1 << 31);
+}
+static size_t prepack_layer_bytes(const vla_config &c) {
+    return ((size_t)4 * c.hidden * c.hidden + (size_t)3 * c.hidden * c.ffn) * 2;      // every matrix a multiple of 256 bytes
+}
+
 static int dma_gemm_enabled() {
     static int v = -1;
     if (v < 0) { const char *e = getenv("VLA_GEMM_DMA"); v = e ? atoi(e) : 1; }
@@ -205,12 +220,48 @@ static int run_gemm(const vla_config &c, GemmArgs g, void *skinny_scratch, hipSt
 // All decoder layers over n_seq x R new rows held in ws.X; K, V of the new rows go to `kv`
 // (layer l of it, or layer 0 when `kv` is a one-layer scratch).
 template <typename T>
-static int run_rmsnorm(const vla_config &c, void *out, const float *X, const void *gain, int M, hipStream_t st) {
+static int run_rmsnorm(const vla_config &c, void *out, const float *X, const void *gain, int M, int kb_rows,
+                       hipStream_t st) {
     if (c.dtype == VLA_DTYPE_BF16 && !(force_generic() & 16)) {
-        int r = try_rmsnorm_bf16((bf16_t *)out, X, (const float *)gain, M, c.hidden, c.rms_eps, st);
+        int r = try_rmsnorm_bf16((bf16_t *)out, X, (const float *)gain, M, c.hidden, c.rms_eps, kb_rows, st);
         if (r != 0) return r < 0 ? r : 0;
     }
+    if (kb_rows) { vla_set_error("internal: k-blocked RMSNorm output unavailable for hidden %d", c.hidden); return VLA_ESHAPE; }
     return launch_rmsnorm<T>((T *)out, X, (const float *)gain, M, c.hidden, c.rms_eps, st);
+}
+
+// One decoder layer on k-blocked activations and repacked weights: every GEMM is the direct-to-LDS kernel,
+// whose operands are then whole cache lines (multi-row bf16 forwards at head_dim 128 only).
+static int run_layer_kblocked(const vla_model *m, const Workspace &ws, const RowsArgs &ra, const KvView &kv, int l, int kl,
+                              hipStream_t st) {
+    const vla_config &c = m->cfg;
+    const int H = c.hidden, F = c.ffn, M = ra.n_seq * ra.R;
+    const vla_layer_weights &lw = m->layers[l], &pk = m->packed[l];
+    int rc;
+    auto must = [&](int r, const char *what) {
+        if (r == 0) { vla_set_error("internal: k-blocked path declined at %s", what); return (int)VLA_ESHAPE; }
+        return r < 0 ? r : 0;
+    };
+    if ((rc = must(try_rmsnorm_bf16((bf16_t *)ws.Nrm, ws.X, (const float *)lw.attn_norm, M, H, c.rms_eps, ws.a_rows, st), "attn norm"))) return rc;
+    QkvRopeArgs qa{ws.Q, ws.rope, &kv, kl, &ra};
+    GemmArgs g{};
+    g.A = ws.Nrm; g.W[0] = pk.wq; g.W[1] = pk.wk; g.W[2] = pk.wv; g.n_seg = 3; g.segN = H; g.C = nullptr; g.M = M; g.K = H;
+    g.epilogue = EPI_QKV_ROPE; g.rope = &qa; g.a_rows = ws.a_rows; g.kblocked = 1;
+    if ((rc = must(try_gemm_bf16_dma(g, st), "QKV projection"))) return rc;
+    if ((rc = must(try_attention_prefill_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.Q, kv, kl, ra, H, ws.vt, ws.a_rows, st), "attention"))) return rc;
+    g = GemmArgs{};
+    g.A = ws.AO; g.W[0] = pk.wo; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = H; g.epilogue = EPI_RESIDUAL;
+    g.a_rows = ws.a_rows; g.kblocked = 1;
+    if ((rc = must(try_gemm_bf16_dma(g, st), "O projection"))) return rc;
+    if ((rc = must(try_rmsnorm_bf16((bf16_t *)ws.Nrm, ws.X, (const float *)lw.ffn_norm, M, H, c.rms_eps, ws.a_rows, st), "ffn norm"))) return rc;
+    g = GemmArgs{};
+    g.A = ws.Nrm; g.W[0] = pk.w_gate; g.W[1] = pk.w_up; g.n_seg = 2; g.segN = F; g.C = ws.ACT; g.M = M; g.K = H;
+    g.epilogue = EPI_SWIGLU; g.a_rows = ws.a_rows; g.kblocked = 1;
+    if ((rc = must(try_gemm_bf16_dma(g, st), "gate/up projection"))) return rc;
+    g = GemmArgs{};
+    g.A = ws.ACT; g.W[0] = pk.w_down; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = F; g.epilogue = EPI_RESIDUAL;
+    g.a_rows = ws.a_rows; g.kblocked = 1;
+    return must(try_gemm_bf16_dma(g, st), "down projection");
 }
 
 template <typename T>
@@ -219,10 +270,19 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
     const vla_config &c = m->cfg;
     int H = c.hidden, F = c.ffn, M = ra.n_seq * ra.R, d = H / c.n_heads, rc;
     if ((rc = launch_rope_table(ws.rope, ra.R, ra.pos0, d, c.rope_theta, st))) return rc;
+    // k-blocked operands: repacked weights present, a multi-row forward, every fast path available and the
+    // 32-bit offsets of the loads sufficient
+    const bool kb = !m->packed.empty() && ra.R > 1 && kblocked_shape_ok(c) && dma_gemm_enabled() && force_generic() == 0 &&
+                    ws.vt && (size_t)ra.n_seq * c.n_heads <= 65535 && M >= 1 &&
+                    (size_t)ws.a_rows * (F > H ? F : H) * 2 < ((size_t)1 << 31);
     for (int l = 0; l < c.n_layers; l++) {
         const vla_layer_weights &lw = m->layers[l];
         int kl = kv_single_layer ? 0 : l;
-        if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.attn_norm, M, st))) return rc;
+        if (kb) {
+            if ((rc = run_layer_kblocked(m, ws, ra, kv, l, kl, st))) return rc;
+            continue;
+        }
+        if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.attn_norm, M, 0, st))) return rc;
         GemmArgs g{};
         g.A = ws.Nrm; g.W[0] = lw.wq; g.W[1] = lw.wk; g.W[2] = lw.wv; g.n_seg = 3; g.segN = H;
         g.C = ws.QKV; g.M = M; g.K = H; g.epilogue = EPI_STORE; g.a_rows = ws.a_rows;
@@ -246,14 +306,14 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
             if (ra.R == 1)
                 done = (force_generic() & 8) ? 0 : try_attention_decode_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.Q, kv, kl, ra, H, st);
             else
-                done = (force_generic() & 4) ? 0 : try_attention_prefill_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.Q, kv, kl, ra, H, ws.vt, st);
+                done = (force_generic() & 4) ? 0 : try_attention_prefill_bf16((bf16_t *)ws.AO, (const bf16_t *)ws.Q, kv, kl, ra, H, ws.vt, 0, st);
             if (done < 0) return done;
         }
         if (!done && (rc = launch_attention_generic<T>((T *)ws.AO, (const T *)ws.Q, kv, kl, ra, H, st))) return rc;
         g = GemmArgs{};
         g.A = ws.AO; g.W[0] = lw.wo; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = H; g.epilogue = EPI_RESIDUAL; g.a_rows = ws.a_rows;
         if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
-        if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.ffn_norm, M, st))) return rc;
+        if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.ffn_norm, M, 0, st))) return rc;
         g = GemmArgs{};
         g.A = ws.Nrm; g.W[0] = lw.w_gate; g.W[1] = lw.w_up; g.n_seg = 2; g.segN = F; g.C = ws.ACT; g.M = M; g.K = H;
         g.epilogue = EPI_SWIGLU; g.a_rows = ws.a_rows;
@@ -391,6 +451,42 @@ int vla_create(const vla_config *cfg, const vla_weights *w, vla_model **out) {
     m->layers.assign(w->layers, w->layers + cfg->n_layers);
     m->w.layers = m->layers.data();
     *out = m;
+    return VLA_OK;
+}
+
+size_t vla_prepack_bytes(const vla_config *cfg) {
+    if (check_config(cfg) != VLA_OK) return 0;
+    if (!kblocked_shape_ok(*cfg)) return 0;
+    return prepack_layer_bytes(*cfg) * cfg->n_layers;
+}
+
+int vla_prepack(vla_model *m, void *buffer, size_t bytes, void *stream) {
+    if (!m) { vla_set_error("model is NULL"); return VLA_EINVAL; }
+    if (!buffer) { m->packed.clear(); return VLA_OK; }
+    const vla_config &c = m->cfg;
+    if (!kblocked_shape_ok(c)) { m->packed.clear(); return VLA_OK; }       // nothing to repack for this shape
+    const size_t need = prepack_layer_bytes(c) * c.n_layers;
+    if (bytes < need) { vla_set_error("prepack buffer of %zu bytes, %zu needed", bytes, need); return VLA_EWORKSPACE; }
+    if ((uintptr_t)buffer % 256 != 0) { vla_set_error("prepack buffer must be 256-byte aligned"); return VLA_EINVAL; }
+    hipStream_t st = (hipStream_t)stream;
+    std::vector<vla_layer_weights> packed(c.n_layers);
+    bf16_t *dst = (bf16_t *)buffer;
+    const int H = c.hidden, F = c.ffn;
+    int rc;
+    for (int l = 0; l < c.n_layers; l++) {
+        const vla_layer_weights &lw = m->layers[l];
+        vla_layer_weights pk = lw;                                         // norm gains stay as they are
+        struct { const void *src; const void **slot; int N, K; } mats[7] = {
+            {lw.wq, &pk.wq, H, H}, {lw.wk, &pk.wk, H, H}, {lw.wv, &pk.wv, H, H}, {lw.wo, &pk.wo, H, H},
+            {lw.w_gate, &pk.w_gate, F, H}, {lw.w_up, &pk.w_up, F, H}, {lw.w_down, &pk.w_down, H, F}};
+        for (auto &mt : mats) {
+            if ((rc = launch_weight_kblock(dst, (const bf16_t *)mt.src, mt.N, mt.K, st))) return rc;
+            *mt.slot = dst;
+            dst += (size_t)mt.N * mt.K;
+        }
+        packed[l] = pk;
+    }
+    m->packed.swap(packed);
     return VLA_OK;
 }
 

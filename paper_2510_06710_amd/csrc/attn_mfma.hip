@@ -51,7 +51,7 @@ template <int D>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4))) attn_prefill_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
                                                           const bf16_t *vt, int R, int pos0, int full_from,
                                                           int n_heads, int pos_stride, int ps_pad, int H,
-                                                          int q_blocks) {
+                                                          int q_blocks, int out_kb_rows) {
     constexpr int KS = D / 16;     // k steps of the S^T product
     constexpr int DB = D / 32;     // 32-row blocks of O^T
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -167,7 +167,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4))
     // ---- store: lane holds query `col`, dims b*32 + 8*(i/4) + 4*hh + i%4 -------------------------
     if (qb * 32 + col < R) {
         const float inv = 1.0f / l_run;
-        bf16_t *orow = out + ((size_t)s * R + r) * H + (size_t)h * D;
+        // row-major [M, H], or the GEMM's k-blocked operand layout [H / 32][out_kb_rows][32]
+        const size_t m = (size_t)s * R + r;
+        bf16_t *orow = out_kb_rows ? out + ((size_t)h * (D / 32) * out_kb_rows + m) * 32 : out + m * H + (size_t)h * D;
+        const size_t bstride = out_kb_rows ? (size_t)out_kb_rows * 32 : 32;
 #pragma unroll
         for (int b = 0; b < DB; b++)
 #pragma unroll
@@ -175,7 +178,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4))
                 bf16x4_t o;
 #pragma unroll
                 for (int e = 0; e < 4; e++) o[e] = (bf16_t)(o_acc[b][g * 4 + e] * inv);
-                *(bf16x4_t *)(orow + b * 32 + g * 8 + 4 * hh) = o;
+                *(bf16x4_t *)(orow + b * bstride + g * 8 + 4 * hh) = o;
             }
     }
 }
@@ -190,7 +193,7 @@ size_t attention_prefill_scratch_bytes(int n_seq, int n_heads, int d, int n_keys
 }
 
 int try_attention_prefill_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, int layer, const RowsArgs &ra,
-                               int H, void *vt_scratch, hipStream_t st) {
+                               int H, void *vt_scratch, int out_kb_rows, hipStream_t st) {
     if ((kv.d != 64 && kv.d != 128) || !vt_scratch || ra.R < 2) return 0;
     const int nk = ra.pos0 + ra.R, ps_pad = round_up32(nk);
     const int n_items = ra.n_seq * kv.n_heads;
@@ -216,10 +219,10 @@ int try_attention_prefill_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, i
         dim3 grid((q_blocks + 3) / 4, n_items);
         if (kv.d == 128)
             attn_prefill_kernel<128><<<grid, 256, 0, st>>>(out, q, kc, vt, ra.R, ra.pos0, ra.full_from, kv.n_heads,
-                                                          kv.pos_stride, ps_pad, H, q_blocks);
+                                                          kv.pos_stride, ps_pad, H, q_blocks, out_kb_rows);
         else
             attn_prefill_kernel<64><<<grid, 256, 0, st>>>(out, q, kc, vt, ra.R, ra.pos0, ra.full_from, kv.n_heads,
-                                                         kv.pos_stride, ps_pad, H, q_blocks);
+                                                         kv.pos_stride, ps_pad, H, q_blocks, out_kb_rows);
         if ((rc = vla_check_launch("attn_prefill"))) return rc;
     }
     return 1;

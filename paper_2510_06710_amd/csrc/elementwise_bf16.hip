@@ -92,6 +92,54 @@ __global__ void __launch_bounds__(256) rmsnorm_bf16_kernel(bf16_t *out, const fl
     }
 }
 
+// The same norm with the output in the GEMM's k-blocked operand layout [H / 32][kb_rows][32].  A workgroup
+// takes four consecutive rows, stages their bf16 results in LDS and writes each 32-column block of the four
+// rows as one 256-byte run (a row on its own would leave as 64-byte pieces kb_rows * 64 bytes apart).
+template <int V4>
+__global__ void __launch_bounds__(256) rmsnorm_bf16_kb_kernel(bf16_t *out, const float *X, const float *gain, int M, int H,
+                                                             float eps, int kb_rows) {
+    __shared__ float red[4][4];
+    __shared__ __attribute__((aligned(16))) bf16_t stage[4][1024 * V4];
+    const int t = threadIdx.x;
+    const int m0 = blockIdx.x * 4;
+    const f32x4_t *g = (const f32x4_t *)gain;
+#pragma unroll
+    for (int rr = 0; rr < 4; rr++) {
+        const int m = min(m0 + rr, M - 1);                 // (a clamped row is computed again and not written)
+        const f32x4_t *x = (const f32x4_t *)(X + (size_t)m * H);
+        f32x4_t v[V4];
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < V4; j++) {
+            v[j] = x[j * 256 + t];
+#pragma unroll
+            for (int e = 0; e < 4; e++) ss += v[j][e] * v[j][e];
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        if ((t & 63) == 0) red[rr][t >> 6] = ss;
+        __syncthreads();
+        ss = red[rr][0] + red[rr][1] + red[rr][2] + red[rr][3];
+        const float r = 1.0f / sqrtf(ss / (float)H + eps);
+#pragma unroll
+        for (int j = 0; j < V4; j++) {
+            f32x4_t gg = g[j * 256 + t];
+            bf16x4_t w;
+#pragma unroll
+            for (int e = 0; e < 4; e++) w[e] = (bf16_t)(v[j][e] * r * gg[e]);
+            *(bf16x4_t *)&stage[rr][4 * (j * 256 + t)] = w;
+        }
+    }
+    __syncthreads();
+    // 16-byte piece q: 32-column block q / 16, row (q % 16) / 4, piece q % 4 of that row's 64 bytes
+    constexpr int PIECES = 4 * 1024 * V4 / 8;
+    for (int q = t; q < PIECES; q += 256) {
+        const int kb = q >> 4, rr = (q >> 2) & 3, pc = q & 3;
+        if (m0 + rr < M)
+            *(bf16x8_t *)(out + ((size_t)kb * kb_rows + m0 + rr) * 32 + pc * 8) = *(const bf16x8_t *)&stage[rr][kb * 32 + pc * 8];
+    }
+}
+
 __global__ void __launch_bounds__(256) calibration_copy_kernel(f32x4_t *dst, const f32x4_t *src, size_t n) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
@@ -105,10 +153,25 @@ extern "C" int vla_calibration_copy(void *dst, const void *src, size_t bytes, vo
 }
 
 // Returns 1 if handled (H a multiple of 1024, at most 8192), 0 otherwise.
-int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int H, float eps, hipStream_t st) {
+int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int H, float eps, int kb_rows, hipStream_t st) {
     if (H % 1024 != 0 || H > 8192) return 0;
     if (M == 0) return 1;
     ProfScope ps("rmsnorm", (double)M * H * 6.0, st);
+    if (kb_rows) {
+        const unsigned grid = (unsigned)((M + 3) / 4);
+        switch (H / 1024) {
+            case 1: rmsnorm_bf16_kb_kernel<1><<<grid, 256, 0, st>>>(out, X, gain, M, H, eps, kb_rows); break;
+            case 2: rmsnorm_bf16_kb_kernel<2><<<grid, 256, 0, st>>>(out, X, gain, M, H, eps, kb_rows); break;
+            case 3: rmsnorm_bf16_kb_kernel<3><<<grid, 256, 0, st>>>(out, X, gain, M, H, eps, kb_rows); break;
+            case 4: rmsnorm_bf16_kb_kernel<4><<<grid, 256, 0, st>>>(out, X, gain, M, H, eps, kb_rows); break;
+            case 5: rmsnorm_bf16_kb_kernel<5><<<grid, 256, 0, st>>>(out, X, gain, M, H, eps, kb_rows); break;
+            case 6: rmsnorm_bf16_kb_kernel<6><<<grid, 256, 0, st>>>(out, X, gain, M, H, eps, kb_rows); break;
+            case 7: rmsnorm_bf16_kb_kernel<7><<<grid, 256, 0, st>>>(out, X, gain, M, H, eps, kb_rows); break;
+            default: rmsnorm_bf16_kb_kernel<8><<<grid, 256, 0, st>>>(out, X, gain, M, H, eps, kb_rows); break;
+        }
+        int rc = vla_check_launch("rmsnorm_bf16_kb");
+        return rc ? rc : 1;
+    }
     switch (H / 1024) {
         case 1: rmsnorm_bf16_kernel<1><<<M, 256, 0, st>>>(out, X, gain, H, eps); break;
         case 2: rmsnorm_bf16_kernel<2><<<M, 256, 0, st>>>(out, X, gain, H, eps); break;

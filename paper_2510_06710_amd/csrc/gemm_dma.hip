@@ -18,6 +18,11 @@
 // fragment reads are inline assembly with explicit waits: the compiler would otherwise wait for every
 // outstanding LDS-bound load before any LDS read.
 //
+// Operand layout.  Row-major operands are fetched as 64-byte pieces of 16 rows per instruction, i.e. half
+// cache lines; in the k-blocked layout (KB: [K / 32][rows][32] for the activations and for repacked weights)
+// a half tile of 256 rows is one contiguous 16 KB block and every instruction reads 1 KB of whole lines,
+// which is worth about 10 % of the kernel's time.  The SwiGLU output is then written k-blocked as well.
+//
 // One workgroup per CU walks its tiles in turn (tile i of a workgroup = id + grid * i, which keeps the
 // XCD-contiguous tile order); the half-tile stream simply continues into the next tile, so that only the
 // first tile pays an empty pipeline.  A tile's last MFMAs run in the next tile's first iteration; the
@@ -42,6 +47,8 @@ struct DmaGemmParams {
     void *C;
     int M, N, K, segN;
     int tiles_m, tiles_n;
+    int a_rows;      // k-blocked layout: rows per 32-column block of A (and of the SwiGLU output)
+    int w_rows;      // k-blocked layout: rows per 32-column block of each weight matrix
     // EPI_QKV_ROPE
     bf16_t *q_out, *kc, *vc;
     const float2 *table;
@@ -81,7 +88,7 @@ __device__ __forceinline__ float *panel_at(float *panel, int row, int cb) { retu
 // Output of one wave.  Per 16-row activation block i a lane holds row (lane % 16) and, per weight block j
 // and register r, column 16 j + 4 (lane / 16) + r.  Each block goes through the panel and leaves as whole
 // rows.
-template <int EPI>
+template <int EPI, bool KB>
 __device__ __forceinline__ void epilogue(f32x4_t (&acc)[8][8], const DmaGemmParams &p, int m0, int tn, int wm, int wn,
                                          int lane, float *panel) {
     const int l16 = lane & 15, kq = lane >> 4;
@@ -152,7 +159,10 @@ __device__ __forceinline__ void epilogue(f32x4_t (&acc)[8][8], const DmaGemmPara
     }
     if (EPI == EPI_SWIGLU) {
         // weight blocks 0..3 are gate rows, 4..7 the matching up rows: 64 output columns per wave
-        bf16_t *out = (bf16_t *)p.C + (size_t)tn * 128 + wn * 64 + (lane & 7) * 8;
+        // row-major [M, N], or k-blocked: column c of row m at ((c / 32) * a_rows + m) * 32 + c % 32
+        const int c0 = tn * 128 + wn * 64 + (lane & 7) * 8;
+        bf16_t *out = (bf16_t *)p.C + (KB ? (size_t)(c0 >> 5) * p.a_rows * 32 + (c0 & 31) : (size_t)c0);
+        const size_t row_stride = KB ? 32 : (size_t)p.N;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             const int mblock = m0 + wm * 128 + i * 16;
@@ -173,7 +183,7 @@ __device__ __forceinline__ void epilogue(f32x4_t (&acc)[8][8], const DmaGemmPara
                 bf16x8_t o;
 #pragma unroll
                 for (int e = 0; e < 4; e++) { o[e] = (bf16_t)a[e]; o[4 + e] = (bf16_t)b[e]; }
-                if (m < p.M) *(bf16x8_t *)(out + (size_t)m * p.N) = o;
+                if (m < p.M) *(bf16x8_t *)(out + (size_t)m * row_stride) = o;
             }
         }
         return;
@@ -208,7 +218,7 @@ __device__ __forceinline__ void epilogue(f32x4_t (&acc)[8][8], const DmaGemmPara
     }
 }
 
-template <int EPI>
+template <int EPI, bool KB>
 __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -225,24 +235,30 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
     // instructions each; SwiGLU tiles interleave 64 gate and 64 up rows per wave of the multiply side, so
     // loading wave w takes 64 rows of W0 (w even) or W1 (w odd).
     const int chunk_off = ((lane & 3) ^ ((lane >> 4) & 3)) << 4;
-    const int a_thread_off = (wave * 64 + (lane >> 2)) * K * 2 + chunk_off;
-    const int w_thread_off = (((EPI == EPI_SWIGLU) ? (wave >> 1) * 64 : wave * 64) + (lane >> 2)) * K * 2 + chunk_off;
+    const int row_bytes = KB ? 64 : K * 2;       // distance of consecutive tile rows of one half tile
+    const int a_thread_off = (wave * 64 + (lane >> 2)) * row_bytes + chunk_off;
+    const int w_thread_off = (((EPI == EPI_SWIGLU) ? (wave >> 1) * 64 : wave * 64) + (lane >> 2)) * row_bytes + chunk_off;
     const int tile_bytes = BM * K * 2;
+    // distance of consecutive half tiles: 64 bytes along the row, or one 32-column block of all rows
+    const unsigned a_half = KB ? (unsigned)p.a_rows * 64u : 64u, w_half = KB ? (unsigned)p.w_rows * 64u : 64u;
     __amdgpu_buffer_rsrc_t a_rsrc, w_rsrc;
     int ld_item, ld_h;
     int nx_tm, nx_tn;
     auto setup_load = [&](int it) {
         int tm, tn;
         vla_tile_of_block(it, p.tiles_m, p.tiles_n, tm, tn);
-        a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * K), (short)0, tile_bytes, 0x00020000);
+        if (KB) a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * 32), (short)0, (int)((unsigned)(nh - 1) * a_half + 16384u), 0x00020000);
+        else a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * K), (short)0, tile_bytes, 0x00020000);
         if (EPI == EPI_SWIGLU) {
             const bf16_t *Wp = (wave & 1) ? p.W1 : p.W0;
-            w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(tn * 128) * K), (short)0, tile_bytes / 2, 0x00020000);
+            if (KB) w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(tn * 128) * 32), (short)0, (int)((unsigned)(nh - 1) * w_half + 8192u), 0x00020000);
+            else w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(tn * 128) * K), (short)0, tile_bytes / 2, 0x00020000);
         } else {
             const int n = tn * BN;
             const int seg = __builtin_amdgcn_readfirstlane(n / p.segN);
             const bf16_t *Wp = seg == 0 ? p.W0 : (seg == 1 ? p.W1 : p.W2);
-            w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * K), (short)0, tile_bytes, 0x00020000);
+            if (KB) w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * 32), (short)0, (int)((unsigned)(nh - 1) * w_half + 16384u), 0x00020000);
+            else w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * K), (short)0, tile_bytes, 0x00020000);
         }
         ld_item = it;
         ld_h = 0;
@@ -251,9 +267,9 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
     // instruction pair i (0..3) of the cursor's half tile into LDS stage `stage`
     auto dma = [&](int stage, int i) {
         char *base = lds + stage * STAGE + wave * 4096 + i * 1024;
-        const int so = ld_h * (HK * 2) + i * 16 * K * 2;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_void *)base, 16, a_thread_off, so, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (lds_void *)(base + REGION), 16, w_thread_off, so, 0, 0);
+        const int blk = i * 16 * row_bytes;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_void *)base, 16, a_thread_off, (int)((unsigned)ld_h * a_half) + blk, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (lds_void *)(base + REGION), 16, w_thread_off, (int)((unsigned)ld_h * w_half) + blk, 0, 0);
     };
     // next half tile, else the next item's first, else stay (the last half tile is fetched again, never used)
     auto advance = [&]() {
@@ -371,7 +387,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
             asm volatile("s_barrier" ::: "memory");
             acc_settle();
             float *panel = (float *)(lds + (g & 3) * STAGE) + wave * (16 * 128);
-            epilogue<EPI>(acc, p, tm * BM, tn, wm, wn, lane, panel);
+            epilogue<EPI, KB>(acc, p, tm * BM, tn, wm, wn, lane, panel);
             if (g == g_end) break;
             zero_acc();
             tm = nx_tm; tn = nx_tn;              // the cursor moved on to the next item four iterations ago
@@ -385,13 +401,13 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
     }
 }
 
-template <int EPI>
+template <int EPI, bool KB>
 int launch(const DmaGemmParams &p, hipStream_t st) {
     static bool attr_set = false;
     static int n_cu = 0;
     const size_t lds = NSTAGES * (size_t)STAGE;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_dma_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_dma_kernel<EPI, KB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) {
             vla_set_error("hipFuncSetAttribute(gemm_bf16_dma) failed: %s", hipGetErrorString(e));
             return VLA_EHIP;
@@ -412,28 +428,38 @@ int launch(const DmaGemmParams &p, hipStream_t st) {
     const int n_items = p.tiles_m * p.tiles_n;
     int grid = n_items;
     if (n_cu % 8 == 0 && n_items > n_cu) grid = n_cu;
-    gemm_bf16_dma_kernel<EPI><<<grid, 256, lds, st>>>(p);
+    gemm_bf16_dma_kernel<EPI, KB><<<grid, 256, lds, st>>>(p);
     int rc = vla_check_launch("gemm_bf16_dma");
     return rc ? rc : 1;
+}
+
+template <int EPI>
+int launch_kb(const DmaGemmParams &p, bool kb, hipStream_t st) {
+    return kb ? launch<EPI, true>(p, st) : launch<EPI, false>(p, st);
 }
 
 }  // namespace
 
 // Handles bf16 problems with K a multiple of 64 and at least 256 (the cursor must never be more than one item
 // ahead of the multiply side), N tiles that do not straddle weight segments, and an activation buffer that
-// covers whole 256-row tiles.  Returns 1 if handled, 0 if declined, < 0 on a launch error.
+// covers whole 256-row tiles.  With g.kblocked the activations (a_rows rows per 32-column block), the weights
+// (segN rows per block, each segment repacked on its own) and a SwiGLU output are in the k-blocked layout.
+// Returns 1 if handled, 0 if declined, < 0 on a launch error.
 int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st) {
     if (g.M < 1 || g.K % 64 != 0 || g.K < 256 || g.a_rows < (g.M + BM - 1) / BM * BM) return 0;
+    const bool kb = g.kblocked != 0;
+    if (kb && ((size_t)g.a_rows * g.K * 2 >= ((size_t)1 << 31) || (size_t)g.segN * g.K * 2 >= ((size_t)1 << 31))) return 0;
     DmaGemmParams p{};
     p.A = (const bf16_t *)g.A;
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
     p.C = g.C; p.M = g.M; p.K = g.K; p.segN = g.segN;
+    p.a_rows = g.a_rows; p.w_rows = g.segN;
     p.tiles_m = (g.M + BM - 1) / BM;
     if (g.epilogue == EPI_SWIGLU) {
         if (g.segN % 128 != 0) return 0;
         p.N = g.segN;
         p.tiles_n = g.segN / 128;
-        return launch<EPI_SWIGLU>(p, st);
+        return launch_kb<EPI_SWIGLU>(p, kb, st);
     }
     if (g.segN % BN != 0) return 0;
     if (g.epilogue == EPI_QKV_ROPE) {
@@ -447,9 +473,31 @@ int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st) {
         p.pos_stride = ra->kv->pos_stride; p.H = g.segN;
         p.N = 3 * g.segN;
         p.tiles_n = p.N / BN;
-        return launch<EPI_QKV_ROPE>(p, st);
+        return launch_kb<EPI_QKV_ROPE>(p, kb, st);
     }
     p.N = g.n_seg * g.segN;
     p.tiles_n = p.N / BN;
-    return g.epilogue == EPI_RESIDUAL ? launch<EPI_RESIDUAL>(p, st) : launch<EPI_STORE>(p, st);
+    return g.epilogue == EPI_RESIDUAL ? launch_kb<EPI_RESIDUAL>(p, kb, st) : launch_kb<EPI_STORE>(p, kb, st);
+}
+
+namespace {
+
+// Repack of one weight matrix [N, K] into [K / 32][N][32]: a thread moves one 16-byte piece.
+__global__ void __launch_bounds__(256) weight_kblock_kernel(bf16_t *dst, const bf16_t *src, int N, int K) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;       // (n, 8-column piece)
+    const int pieces = K / 8;
+    if (idx >= (size_t)N * pieces) return;
+    const int n = (int)(idx / pieces), pc = (int)(idx - (size_t)n * pieces);
+    const bf16x8_t v = *(const bf16x8_t *)(src + (size_t)n * K + pc * 8);
+    *(bf16x8_t *)(dst + ((size_t)(pc >> 2) * N + n) * 32 + (pc & 3) * 8) = v;
+}
+
+}  // namespace
+
+int launch_weight_kblock(bf16_t *dst, const bf16_t *src, int N, int K, hipStream_t st) {
+    if (K % 32 != 0) { vla_set_error("weight repack: K = %d is not a multiple of 32", K); return VLA_ESHAPE; }
+    const size_t total = (size_t)N * (K / 8);
+    if (total == 0) return 0;
+    weight_kblock_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(dst, src, N, K);
+    return vla_check_launch("weight_kblock");
 }

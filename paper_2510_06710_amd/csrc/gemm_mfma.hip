@@ -549,7 +549,7 @@ int launch(const MfmaGemmParams &p, hipStream_t st) {
 // (any M: rows beyond M are loaded from the padded buffer and masked on store, and a row's result does
 // not depend on which tile it falls in); anything else is declined (0) and runs on the generic kernel.
 int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
-    if (g.M < 1 || g.K % BK != 0 || g.a_rows < (g.M + BM - 1) / BM * BM) return 0;
+    if (g.kblocked || g.M < 1 || g.K % BK != 0 || g.a_rows < (g.M + BM - 1) / BM * BM) return 0;
     MfmaGemmParams p{};
     p.A = (const bf16_t *)g.A;
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
@@ -585,7 +585,7 @@ int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st) {
 // single row of tiles still covers the chip; partial sums are reduced in split order by the decode
 // GEMM's reduction kernel (no atomics).  `scratch` holds the partials.
 int try_gemm_bf16_mfma_splitk(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st) {
-    if (g.M < 1 || g.M > BM || g.a_rows < BM || g.K % BK != 0 || !scratch || g.epilogue == EPI_QKV_ROPE) return 0;
+    if (g.kblocked || g.M < 1 || g.M > BM || g.a_rows < BM || g.K % BK != 0 || !scratch || g.epilogue == EPI_QKV_ROPE) return 0;
     MfmaGemmParams p{};
     p.A = (const bf16_t *)g.A;
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];

@@ -200,7 +200,7 @@ int launch_epi(const MidParams &p, hipStream_t st) {
 // of 64 and weight segments that are multiples of 64 rows (SwiGLU: 32).  `scratch` holds the partial
 // sums.  Returns 1 if handled, 0 if declined, < 0 on a launch error.
 int try_gemm_bf16_mid(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st) {
-    if (g.M < 1 || g.M > 256 || g.K % BK != 0 || !scratch || g.epilogue == EPI_QKV_ROPE) return 0;
+    if (g.kblocked || g.M < 1 || g.M > 256 || g.K % BK != 0 || !scratch || g.epilogue == EPI_QKV_ROPE) return 0;
     const int bm = g.M <= 128 ? 128 : 256;
     if (g.a_rows < bm) return 0;
     MidParams p{};

@@ -287,7 +287,7 @@ size_t gemm_skinny_scratch_bytes(int M, int max_n) {
 // weight rows.  `scratch` holds the split-K partials (gemm_skinny_scratch_bytes(M, N), with N
 // counting gate and up columns separately).  Returns 1 if handled, 0 if declined.
 int try_gemm_bf16_skinny(const GemmArgs &g, void *scratch, hipStream_t st) {
-    if (g.M < 1 || g.M > 256 || g.K % BK != 0 || g.segN % 128 != 0 || !scratch) return 0;
+    if (g.kblocked || g.M < 1 || g.M > 256 || g.K % BK != 0 || g.segN % 128 != 0 || !scratch) return 0;
     SkinnyParams p{};
     p.A = (const bf16_t *)g.A;
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];

@@ -51,6 +51,8 @@ struct GemmArgs {
     int M, K;
     int epilogue;
     const QkvRopeArgs *rope;   // EPI_QKV_ROPE only
+    int kblocked;           // A (a_rows rows per 32-column block), the weights (segN rows per block, each segment
+                            // on its own) and a SwiGLU output are stored [K / 32][rows][32]: direct-to-LDS kernel only
     int a_rows;             // rows of A that may be read (>= M; contents past M arbitrary): the MFMA kernel
                             // loads whole 256-row tiles and declines if the buffer does not cover them
 };
@@ -123,16 +125,19 @@ __device__ __forceinline__ void vla_tile_of_block(int pid, int tiles_m, int tile
 // shape is outside what it supports (caller then uses the generic kernel), <0 on launch error ----
 int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st);
 int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st);
+int launch_weight_kblock(bf16_t *dst, const bf16_t *src, int N, int K, hipStream_t st);
 int launch_rope_kv_write_bf16(bf16_t *q_out, const float *qkv, const float2 *table, const KvView &kv, int layer,
                               const RowsArgs &ra, int H, hipStream_t st);
-int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int H, float eps, hipStream_t st);
+// kb_rows = 0: row-major output [M, H]; else k-blocked [H / 32][kb_rows][32]
+int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int H, float eps, int kb_rows, hipStream_t st);
 int try_gemm_bf16_skinny(const GemmArgs &g, void *scratch, hipStream_t st);
 int try_gemm_bf16_mfma_splitk(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st);
 int try_gemm_bf16_mid(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st);
 int launch_splitk_reduce(int epilogue, void *C, const float *P, int splits, int M, int N, hipStream_t st);
 size_t gemm_skinny_scratch_bytes(int M, int max_n);
+// out_kb_rows = 0: row-major output [M, H]; else k-blocked [H / 32][out_kb_rows][32]
 int try_attention_prefill_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, int layer,
-                               const RowsArgs &ra, int H, void *vt_scratch, hipStream_t st);
+                               const RowsArgs &ra, int H, void *vt_scratch, int out_kb_rows, hipStream_t st);
 int try_attention_decode_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, int layer,
                               const RowsArgs &ra, int H, hipStream_t st);
 size_t attention_prefill_scratch_bytes(int n_seq, int n_heads, int d, int n_keys);

@@ -12,7 +12,7 @@ class Rollout:
     """One model on one GPU plus the buffers for a (B, S, A) rollout problem."""
 
     def __init__(self, synth_model, max_batch: int, max_seq: int, device="cuda:0", with_value=True,
-                 value_b: float = 0.0, value_dim: int = 1):
+                 value_b: float = 0.0, value_dim: int = 1, prepack: bool = True):
         self.shape = synth_model.shape
         self.device = torch.device(device)
         assert str(synth_model.device).startswith("cuda"), "weights must be generated on the GPU"
@@ -24,6 +24,13 @@ class Rollout:
                                     layers, synth_model.value_w(value_dim) if with_value else None, value_b,
                                     synth_model.value_bias(value_dim) if with_value and value_dim > 1 else None)
         self._bufs = {}
+        # repacked projection weights for the multi-row forwards (bf16 models with tile-aligned widths)
+        self.packed = None
+        nbytes = vb.vla_prepack_bytes(self.cfg)
+        if nbytes and prepack:
+            self.packed = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            vb.vla_prepack(self.model.handle, self.packed)
+            torch.cuda.synchronize(self.device)
 
     def _buf(self, name, nbytes):
         t = self._bufs.get(name)

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
             "vla_kv_bytes", "vla_workspace_bytes", "vla_last_error", "vla_version", "vla_profile_enable",
             "vla_profile_report", "vla_calibration_copy", "vla_gae", "vla_grpo_advantage",
             "vla_policy_objective", "vla_policy_objective_workspace_bytes", "vla_logp_aggregate",
-            "vla_pipeline_time", "vla_profile_lookup", "vla_auto_placement"} <= set(names)
+            "vla_pipeline_time", "vla_profile_lookup", "vla_auto_placement", "vla_prepack", "vla_prepack_bytes"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
     assert vb.vla_version() == 1

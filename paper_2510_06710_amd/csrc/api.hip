@@ -111,7 +111,8 @@ struct Workspace {
     void *kvs_k, *kvs_v;   // one-layer KV scratch (recompute)
     void *vt;        // scratch of the MFMA prefill attention
     void *skinny;    // split-K partial sums of the decode GEMM (single-row forwards only)
-    int a_rows;      // rows allocated for Nrm, AO and ACT (M rounded up to whole 256-row GEMM tiles)
+    int a_rows;      // rows allocated for Nrm, AO and ACT (M rounded up to whole 256-row GEMM tiles, plus the pad of
+                     // the k-blocked layout, whose block stride this is)
     size_t total;
 };
 
@@ -124,7 +125,7 @@ static Workspace plan_workspace(const vla_config &c, char *base, int n_seq, int 
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += align_up(bytes); return (void *)p; };
     // GEMM activation operands are padded to whole tiles of 256 rows: the MFMA kernel reads (and
     // discards the products of) the rows between M and the end of its last tile
-    size_t Mp = (M + 255) / 256 * 256;
+    size_t Mp = (M + 255) / 256 * 256 + VLA_KB_PAD_ROWS;
     w.a_rows = (int)Mp;
     w.X = (float *)take(M * H * 4);
     w.Nrm = take(Mp * H * es);
@@ -174,7 +175,8 @@ static bool kblocked_shape_ok(const vla_config &c) {
            (size_t)c.ffn * c.hidden * 2 < ((size_t)1 << 31);
 }
 static size_t prepack_layer_bytes(const vla_config &c) {
-    return ((size_t)4 * c.hidden * c.hidden + (size_t)3 * c.hidden * c.ffn) * 2;      // every matrix a multiple of 256 bytes
+    const size_t H = c.hidden, F = c.ffn, P = VLA_KB_PAD_ROWS;                       // every matrix a multiple of 256 bytes
+    return (4 * (H + P) * H + 2 * (F + P) * H + (H + P) * F) * 2;
 }
 
 static int dma_gemm_enabled() {
@@ -482,7 +484,7 @@ int vla_prepack(vla_model *m, void *buffer, size_t bytes, void *stream) {
         for (auto &mt : mats) {
             if ((rc = launch_weight_kblock(dst, (const bf16_t *)mt.src, mt.N, mt.K, st))) return rc;
             *mt.slot = dst;
-            dst += (size_t)mt.N * mt.K;
+            dst += (size_t)(mt.N + VLA_KB_PAD_ROWS) * mt.K;
         }
         packed[l] = pk;
     }

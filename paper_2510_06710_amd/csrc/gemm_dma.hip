@@ -306,13 +306,24 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
 
 #define VLA_SB() __builtin_amdgcn_sched_barrier(0)
 #define VLA_Q(n) std::integral_constant<int, n> {}
-    // group q (0..15): one fragment read into buffer B (q even: weight block q / 2, q odd: activation block
-    // q / 2) and four MFMAs from buffer B ^ 1: weight block q / 2, activation blocks 4 (q % 2) .. + 3
+    // group q (0..15): fragment reads into buffer B and four MFMAs from buffer B ^ 1 (weight block q / 2,
+    // activation blocks 4 (q % 2) .. + 3).  Fragment f (0..15; even: weight block f / 2, odd: activation block
+    // f / 2) is read in group f / 2 for f < 8 and in group f - 4 after that: all reads are issued by group 11,
+    // so that the last sixteen MFMAs cover their latency before the end-of-iteration wait.
+    auto read_frag = [&](auto b_c, auto f_c, int soff) {
+        constexpr int B = decltype(b_c)::value, f = decltype(f_c)::value;
+        constexpr int blk = f >> 1;
+        if (f & 1) af[B][blk] = lds_read<blk * 1024>(a_base + soff);
+        else wf[B][blk] = lds_read<blk * 1024>(w_base + soff);
+    };
     auto group = [&](auto b_c, auto q_c, int soff) {
         constexpr int B = decltype(b_c)::value, q = decltype(q_c)::value;
-        constexpr int blk = q >> 1;
-        if (q & 1) af[B][blk] = lds_read<blk * 1024>(a_base + soff);
-        else wf[B][blk] = lds_read<blk * 1024>(w_base + soff);
+        if (q < 4) {
+            read_frag(b_c, std::integral_constant<int, (q < 4 ? 2 * q : 0)>{}, soff);
+            read_frag(b_c, std::integral_constant<int, (q < 4 ? 2 * q + 1 : 0)>{}, soff);
+        } else if (q < 12) {
+            read_frag(b_c, std::integral_constant<int, (q >= 4 && q < 12 ? q + 4 : 0)>{}, soff);
+        }
         constexpr int j = q >> 1, i0 = (q & 1) * 4;
 #pragma unroll
         for (int i = i0; i < i0 + 4; i++)
@@ -443,17 +454,17 @@ int launch_kb(const DmaGemmParams &p, bool kb, hipStream_t st) {
 // Handles bf16 problems with K a multiple of 64 and at least 256 (the cursor must never be more than one item
 // ahead of the multiply side), N tiles that do not straddle weight segments, and an activation buffer that
 // covers whole 256-row tiles.  With g.kblocked the activations (a_rows rows per 32-column block), the weights
-// (segN rows per block, each segment repacked on its own) and a SwiGLU output are in the k-blocked layout.
+// (segN + pad rows per block, each segment repacked on its own) and a SwiGLU output are in the k-blocked layout.
 // Returns 1 if handled, 0 if declined, < 0 on a launch error.
 int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st) {
     if (g.M < 1 || g.K % 64 != 0 || g.K < 256 || g.a_rows < (g.M + BM - 1) / BM * BM) return 0;
     const bool kb = g.kblocked != 0;
-    if (kb && ((size_t)g.a_rows * g.K * 2 >= ((size_t)1 << 31) || (size_t)g.segN * g.K * 2 >= ((size_t)1 << 31))) return 0;
+    if (kb && ((size_t)g.a_rows * g.K * 2 >= ((size_t)1 << 31) || (size_t)(g.segN + VLA_KB_PAD_ROWS) * g.K * 2 >= ((size_t)1 << 31))) return 0;
     DmaGemmParams p{};
     p.A = (const bf16_t *)g.A;
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
     p.C = g.C; p.M = g.M; p.K = g.K; p.segN = g.segN;
-    p.a_rows = g.a_rows; p.w_rows = g.segN;
+    p.a_rows = g.a_rows; p.w_rows = g.segN + VLA_KB_PAD_ROWS;
     p.tiles_m = (g.M + BM - 1) / BM;
     if (g.epilogue == EPI_SWIGLU) {
         if (g.segN % 128 != 0) return 0;
@@ -482,14 +493,15 @@ int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st) {
 
 namespace {
 
-// Repack of one weight matrix [N, K] into [K / 32][N][32]: a thread moves one 16-byte piece.
+// Repack of one weight matrix [N, K] into [K / 32][N + pad][32]: a thread moves one 16-byte piece (the pad rows
+// are never read).
 __global__ void __launch_bounds__(256) weight_kblock_kernel(bf16_t *dst, const bf16_t *src, int N, int K) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;       // (n, 8-column piece)
     const int pieces = K / 8;
     if (idx >= (size_t)N * pieces) return;
     const int n = (int)(idx / pieces), pc = (int)(idx - (size_t)n * pieces);
     const bf16x8_t v = *(const bf16x8_t *)(src + (size_t)n * K + pc * 8);
-    *(bf16x8_t *)(dst + ((size_t)(pc >> 2) * N + n) * 32 + (pc & 3) * 8) = v;
+    *(bf16x8_t *)(dst + ((size_t)(pc >> 2) * (N + VLA_KB_PAD_ROWS) + n) * 32 + (pc & 3) * 8) = v;
 }
 
 }  // namespace

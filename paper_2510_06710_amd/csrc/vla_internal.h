@@ -43,6 +43,11 @@ struct QkvRopeArgs {
     const RowsArgs *rows;
 };
 
+// k-blocked layouts ([K / 32][rows][32]) pad the row count of a block by this much: with a power-of-two row
+// count the 32-column blocks of one row panel would sit a power-of-two distance apart and fall into the same
+// L2 sets (measured: 2.4 times the L2 misses of the row-major layout without the pad).
+constexpr int VLA_KB_PAD_ROWS = 32;
+
 struct GemmArgs {
     const void *A;          // [M, K] row-major (lda = K), storage dtype (or fp32 for fp32 models)
     const void *W[3];       // up to three weight segments, each [segN, K] row-major

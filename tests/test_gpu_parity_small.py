@@ -226,3 +226,27 @@ def test_pipelined_rollout_equals_plain_calls_and_respects_the_schedule():
                 assert when[("observation", j, t - 1)] <= when[("generate", j, t)]
     # the overlap the mode is for: sub-batch 1 is being generated while sub-batch 0 is in the simulator
     assert when[("generate", 1, 0)] < when[("observation", 0, 0)]
+
+
+def test_prepacked_weights_give_bit_identical_results():
+    """The repacked (k-blocked) weight copy and the k-blocked activations change the memory layout of the
+    multi-row forwards, not their arithmetic: rollout and recompute outputs are bit-identical with and
+    without vla_prepack."""
+    from paper_2510_06710_amd import binding as vb
+    from paper_2510_06710_amd.harness import Rollout
+    wl = vi.Workload("h1024", vi.ModelShape(n_layers=2, hidden=1024, n_heads=8, ffn=1024, vocab=512, dtype="bf16"),
+                     batch=9, n_patches=30, n_instr=7, n_action=3)
+    synth = vi.SynthModel(wl.shape, 5, device="cuda:0")
+    patch, ids = vi.observation(wl, 5, device="cuda:0")
+    g = vi.gumbel_noise(wl, 5, device="cuda:0")
+    outs = []
+    for prepack in (True, False):
+        run = Rollout(synth, wl.batch, wl.prefix + wl.n_action, value_b=vi.VALUE_BIAS, prepack=prepack)
+        assert (run.packed is not None) == prepack and vb.vla_prepack_bytes(run.cfg) > 0
+        h, v = run.prefill(patch, ids)
+        b, lp, en, z = run.decode(h, wl.prefix, wl.n_action, 0, None, 1.0, g)
+        rlp, ren, rv, rz = run.recompute(patch, ids, b, wl.n_action)
+        torch.cuda.synchronize()
+        outs.append([x.cpu() for x in (h, v, b, lp, en, z, rlp, ren, rv, rz)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)

@@ -116,7 +116,7 @@ def bench_recompute(args, wl, torch, vi, vb, Rollout):
     roofline = None
     if dom:
         ach = dom["work"] / (dom["ms"] * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel<EPI_SWIGLU, k-blocked> (gate/up projection)",
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel<EPI_SWIGLU, k-blocked, unit barrier> (gate/up projection)",
                     "achieved": ach, "peak": MI355X_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / MI355X_BF16_TFLOPS,
                     "launches": dom["count"], "avg_launch_ms": dom["ms"] / dom["count"], "traffic": None}
     out = {"metric": "stored rollouts/sec, log-prob recompute (7B shape), % MFMA roofline", "value": N / (ms * 1e-3),
@@ -294,13 +294,13 @@ def main():
     if dom in prof_prefill:
         r = prof_prefill[dom]
         achieved = r["work"] / (r["ms"] * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel<EPI_SWIGLU, k-blocked> (gate/up projection, prefill)",
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel<EPI_SWIGLU, k-blocked, unit barrier> (gate/up projection, prefill)",
                     "achieved": achieved, "peak": MI355X_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / MI355X_BF16_TFLOPS, "launches": r["count"],
                     "avg_launch_ms": r["ms"] / r["count"],
                     "flops_per_launch": r["work"] / r["count"],
                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "gemm_swiglu_cfg3_traffic.txt"),
-                                            "gemm_bf16_dma_kernel<2, true>")}
+                                            "gemm_bf16_dma_kernel<2, true, true>")}
     # decode HBM accounting: weights once per forward + each environment's own K, V rows per forward
     kv_tok = 2 * shape.n_layers * shape.hidden * 2
     fwd = A - 1 if wl.mode == 0 else 1

@@ -112,13 +112,13 @@ __device__ __forceinline__ float vla_silu_mul(float gate, float up) {
 // `GROUP` tile rows so that the ~32 tiles resident on an XCD (4 x 8) share activation and weight rows.  The
 // divisions run on the vector unit; the results are the same in every lane and go back to scalar registers
 // so that everything derived from them (tile base addresses) stays scalar.
-__device__ __forceinline__ void vla_tile_of_block(int pid, int tiles_m, int tiles_n, int &tm, int &tn) {
+__device__ __forceinline__ void vla_tile_of_block(int pid, int tiles_m, int tiles_n, int &tm, int &tn, int GROUP = 4) {
     int total = tiles_m * tiles_n;
     int per_xcd = (total + 7) / 8;
     int xcd = pid % 8, local = pid / 8;
     int lin = xcd * per_xcd + local;
     if (per_xcd * 8 != total) lin = pid;     // ragged tile counts: keep the plain order
-    constexpr int GROUP = 4;                 // measured best of 1, 2, 4, 6, 8, 16, 32 on the 7B shapes
+    // GROUP = 4: measured best of 1, 2, 4, 6, 8, 16, 32 on the 7B shapes (the QKV projection passes 2)
     int panel = lin / (GROUP * tiles_n);
     int first_m = panel * GROUP;
     int rows = min(GROUP, tiles_m - first_m);

@@ -205,7 +205,8 @@ static int run_gemm(const vla_config &c, GemmArgs g, void *skinny_scratch, hipSt
             // that the work is MFMA bound and the large tile with split K does better
             if (g.M > 128 && !(force_generic() & 1)) {
                 const size_t sb = gemm_skinny_scratch_bytes(g.M, 2 * c.ffn > 3 * c.hidden ? 2 * c.ffn : 3 * c.hidden);
-                r = mid_gemm_enabled() ? try_gemm_bf16_mid(g, skinny_scratch, sb, st) : 0;
+                if (dma_gemm_enabled() && mid_gemm_enabled() != 3) r = try_gemm_bf16_dma_splitk(g, skinny_scratch, sb, st);
+                if (r == 0) r = mid_gemm_enabled() ? try_gemm_bf16_mid(g, skinny_scratch, sb, st) : 0;
                 if (r == 0) r = try_gemm_bf16_mfma_splitk(g, skinny_scratch, sb, st);
             }
             if (r == 0 && mid_gemm_enabled() == 2)

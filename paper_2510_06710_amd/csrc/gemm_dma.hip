@@ -54,6 +54,8 @@ struct DmaGemmParams {
     const float2 *table;
     int R, pos0, n_heads, pos_stride, H;
     int group;
+    int splits;      // > 1: K is cut into `splits` equal ranges; item = range * tiles + tile, and range r of an
+                     // EPI_STORE launch writes its fp32 partial product to C + r * M * N
 };
 
 template <int OFF>
@@ -91,7 +93,7 @@ __device__ __forceinline__ float *panel_at(float *panel, int row, int cb) { retu
 // rows.
 template <int EPI, bool KB>
 __device__ __forceinline__ void epilogue(f32x4_t (&acc)[8][8], const DmaGemmParams &p, int m0, int tn, int wm, int wn,
-                                         int lane, float *panel) {
+                                         int lane, float *panel, size_t c_off) {
     const int l16 = lane & 15, kq = lane >> 4;
     if (EPI == EPI_QKV_ROPE) {
         // the wave's 128 columns are one head of q, k or v (head_dim 128)
@@ -191,7 +193,7 @@ __device__ __forceinline__ void epilogue(f32x4_t (&acc)[8][8], const DmaGemmPara
     }
     // fp32 store, or read-modify-write of the fp32 residual stream (x of a block is loaded before the block
     // is staged, whole 512-byte rows, two rows per instruction)
-    float *out = (float *)p.C + (size_t)tn * BN + wn * 128 + (lane & 31) * 4;
+    float *out = (float *)p.C + c_off + (size_t)tn * BN + wn * 128 + (lane & 31) * 4;
 #pragma unroll
     for (int i = 0; i < 8; i++) {
         const int mblock = m0 + wm * 128 + i * 16;
@@ -224,9 +226,10 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave >> 1, wn = wave & 1;
-    const int n_items = p.tiles_m * p.tiles_n;
+    const int n_tiles = p.tiles_m * p.tiles_n;
+    const int n_items = n_tiles * p.splits;
     const int K = p.K;
-    const int nh = K / HK;                       // even: the host only sends K that are multiples of 64
+    const int nh = K / HK / p.splits;            // half tiles per item; even: the host sees to it
     int item = blockIdx.x;
     if (item >= n_items || (nh & 1) || nh < 8) return;      // (the host never launches such a K)
 
@@ -244,26 +247,30 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
     const unsigned a_half = KB ? (unsigned)p.a_rows * 64u : 64u, w_half = KB ? (unsigned)p.w_rows * 64u : 64u;
     __amdgpu_buffer_rsrc_t a_rsrc, w_rsrc;
     int ld_item, ld_h;
-    int nx_tm, nx_tn;
+    int nx_tm, nx_tn, nx_split;
     auto setup_load = [&](int it) {
         int tm, tn;
-        vla_tile_of_block(it, p.tiles_m, p.tiles_n, tm, tn, p.group);
-        if (KB) a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * 32), (short)0, (int)((unsigned)(nh - 1) * a_half + 16384u), 0x00020000);
-        else a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * K), (short)0, tile_bytes, 0x00020000);
+        const int split = __builtin_amdgcn_readfirstlane(it / n_tiles);
+        vla_tile_of_block(it - split * n_tiles, p.tiles_m, p.tiles_n, tm, tn, p.group);
+        // first element of this item's K range within a row panel: k-blocked, whole 32-column blocks; row-major, columns
+        const size_t a_k0 = KB ? (size_t)split * nh * (a_half / 2) : (size_t)split * nh * HK;
+        const size_t w_k0 = KB ? (size_t)split * nh * (w_half / 2) : (size_t)split * nh * HK;
+        if (KB) a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * 32 + a_k0), (short)0, (int)((unsigned)(nh - 1) * a_half + 16384u), 0x00020000);
+        else a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * K + a_k0), (short)0, tile_bytes, 0x00020000);
         if (EPI == EPI_SWIGLU) {
             const bf16_t *Wp = (wave & 1) ? p.W1 : p.W0;
-            if (KB) w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(tn * 128) * 32), (short)0, (int)((unsigned)(nh - 1) * w_half + 8192u), 0x00020000);
-            else w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(tn * 128) * K), (short)0, tile_bytes / 2, 0x00020000);
+            if (KB) w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(tn * 128) * 32 + w_k0), (short)0, (int)((unsigned)(nh - 1) * w_half + 8192u), 0x00020000);
+            else w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(tn * 128) * K + w_k0), (short)0, tile_bytes / 2, 0x00020000);
         } else {
             const int n = tn * BN;
             const int seg = __builtin_amdgcn_readfirstlane(n / p.segN);
             const bf16_t *Wp = seg == 0 ? p.W0 : (seg == 1 ? p.W1 : p.W2);
-            if (KB) w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * 32), (short)0, (int)((unsigned)(nh - 1) * w_half + 16384u), 0x00020000);
-            else w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * K), (short)0, tile_bytes, 0x00020000);
+            if (KB) w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * 32 + w_k0), (short)0, (int)((unsigned)(nh - 1) * w_half + 16384u), 0x00020000);
+            else w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * K + w_k0), (short)0, tile_bytes, 0x00020000);
         }
         ld_item = it;
         ld_h = 0;
-        nx_tm = tm; nx_tn = tn;
+        nx_tm = tm; nx_tn = tn; nx_split = split;
     };
     // instruction pair i (0..3) of the cursor's half tile into LDS stage `stage`
     auto dma = [&](int stage, int i) {
@@ -426,7 +433,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
             VLA_SB();
         };
         setup_load(item);
-        int tm = nx_tm, tn = nx_tn;
+        int tm = nx_tm, tn = nx_tn, split = nx_split;
 #pragma unroll
         for (int d = 0; d < 2; d++) {
 #pragma unroll
@@ -443,7 +450,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
                 asm volatile("s_barrier" ::: "memory");
                 acc_settle();
                 float *panel = (float *)(lds + (g & 3) * STAGE) + wave * (16 * 128);
-                epilogue<EPI, KB>(acc, p, tm * BM, tn, wm, wn, lane, panel);
+                epilogue<EPI, KB>(acc, p, tm * BM, tn, wm, wn, lane, panel, (size_t)split * p.M * p.N);
                 if (g == g_end) break;
                 zero_acc();
                 // the loads this boundary iteration held back (half tiles g + 2 and g + 3, both of the next item)
@@ -453,14 +460,14 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
 #pragma unroll
                 for (int i = 0; i < 4; i++) dma((g + 3) & 3, i);
                 advance();
-                tm = nx_tm; tn = nx_tn;
+                tm = nx_tm; tn = nx_tn; split = nx_split;
                 next_done += nh;
             }
             iteration_ub(B1{}, g + 1, false);
         }
     } else {
     setup_load(item);
-    int tm = nx_tm, tn = nx_tn;
+    int tm = nx_tm, tn = nx_tn, split = nx_split;
 #pragma unroll
     for (int d = 0; d < 3; d++) {
 #pragma unroll
@@ -481,10 +488,10 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
             asm volatile("s_barrier" ::: "memory");
             acc_settle();
             float *panel = (float *)(lds + (g & 3) * STAGE) + wave * (16 * 128);
-            epilogue<EPI, KB>(acc, p, tm * BM, tn, wm, wn, lane, panel);
+            epilogue<EPI, KB>(acc, p, tm * BM, tn, wm, wn, lane, panel, (size_t)split * p.M * p.N);
             if (g == g_end) break;
             zero_acc();
-            tm = nx_tm; tn = nx_tn;              // the cursor moved on to the next item four iterations ago
+            tm = nx_tm; tn = nx_tn; split = nx_split;   // the cursor moved on to the next item four iterations ago
             next_done += nh;
             const int sn = (g + 3) & 3;          // the loads this boundary iteration held back
 #pragma unroll
@@ -497,7 +504,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
 }
 
 template <int EPI, bool KB, bool UB = false>
-int launch(const DmaGemmParams &p, hipStream_t st) {
+int launch_plain(const DmaGemmParams &p, hipStream_t st) {
     static bool attr_set = false;
     static int n_cu = 0;
     const size_t lds = NSTAGES * (size_t)STAGE;
@@ -515,17 +522,22 @@ int launch(const DmaGemmParams &p, hipStream_t st) {
         }
         attr_set = true;
     }
-    const double flops = 2.0 * p.M * p.K * (EPI == EPI_SWIGLU ? 2.0 * p.N : (double)p.N);
-    ProfScope ps(EPI == EPI_SWIGLU ? "gemm_bf16_mfma<swiglu>" : EPI == EPI_RESIDUAL ? "gemm_bf16_mfma<residual>"
-                 : EPI == EPI_QKV_ROPE ? "gemm_bf16_mfma<qkv_rope>" : "gemm_bf16_mfma<store>", flops, st);
     // one workgroup per CU (128 KB of LDS, 512 registers per lane); blockIdx % 8 is the XCD, and a stride of a
     // multiple of 8 keeps every workgroup's items on its own XCD's share of the tile order
-    const int n_items = p.tiles_m * p.tiles_n;
+    const int n_items = p.tiles_m * p.tiles_n * p.splits;
     int grid = n_items;
     if (n_cu % 8 == 0 && n_items > n_cu) grid = n_cu;
     gemm_bf16_dma_kernel<EPI, KB, UB><<<grid, 256, lds, st>>>(p);
     int rc = vla_check_launch("gemm_bf16_dma");
     return rc ? rc : 1;
+}
+
+template <int EPI, bool KB, bool UB = false>
+int launch(const DmaGemmParams &p, hipStream_t st) {
+    const double flops = 2.0 * p.M * p.K * (EPI == EPI_SWIGLU ? 2.0 * p.N : (double)p.N);
+    ProfScope ps(EPI == EPI_SWIGLU ? "gemm_bf16_mfma<swiglu>" : EPI == EPI_RESIDUAL ? "gemm_bf16_mfma<residual>"
+                 : EPI == EPI_QKV_ROPE ? "gemm_bf16_mfma<qkv_rope>" : "gemm_bf16_mfma<store>", flops, st);
+    return launch_plain<EPI, KB, UB>(p, st);
 }
 
 template <int EPI>
@@ -557,6 +569,7 @@ int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st) {
     p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
     p.C = g.C; p.M = g.M; p.K = g.K; p.segN = g.segN;
     p.a_rows = g.a_rows; p.w_rows = g.segN + VLA_KB_PAD_ROWS;
+    p.splits = 1;
     {
         // tile rows per column panel of the walk: 4, except for the QKV projection (1.9 % faster with 2 at
         // M = 73728: 5.73 against 5.84 ms; the other projections within 0.5 % either way); VLA_GEMM_GROUP overrides
@@ -588,6 +601,47 @@ int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st) {
     p.N = g.n_seg * g.segN;
     p.tiles_n = p.N / BN;
     return g.epilogue == EPI_RESIDUAL ? launch_kb<EPI_RESIDUAL>(p, kb, st) : launch_kb<EPI_STORE>(p, kb, st);
+}
+
+// Split-K form for forwards of at most 256 rows (one tile row): the K range is cut into 2, 4 or 8 equal parts so
+// that tiles x parts workgroups are busy, each part's fp32 product goes to `scratch` ([parts][M][N], for SwiGLU
+// N = gate columns then up columns) and launch_splitk_reduce adds the parts in order and applies the epilogue.
+// Takes the QKV projection (fp32 output) and the gate/up projection; declines everything else, and problems
+// where no such split leaves at least a fifth of the CUs more busy than without it.  Row-major operands.
+int try_gemm_bf16_dma_splitk(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st) {
+    if (g.kblocked || g.M < 1 || g.M > BM || g.a_rows < BM || g.K % 64 != 0 || !scratch) return 0;
+    if (g.epilogue != EPI_STORE && g.epilogue != EPI_SWIGLU) return 0;
+    if (g.segN % BN != 0) return 0;
+    static int n_cu = 0;
+    if (!n_cu) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1) {
+            vla_set_error("gemm_bf16_dma: cannot read the compute-unit count");
+            return VLA_EHIP;
+        }
+    }
+    const int n_seg = g.epilogue == EPI_SWIGLU ? 2 : g.n_seg;
+    const int N = n_seg * g.segN, tiles = N / BN, nh = g.K / HK;
+    int splits = 1;
+    while (splits < 8 && tiles * splits * 2 <= n_cu && (nh / (splits * 2)) % 2 == 0 && nh / (splits * 2) >= 8 &&
+           nh % (splits * 2) == 0 && (size_t)(splits * 2) * g.M * N * sizeof(float) <= scratch_bytes)
+        splits *= 2;
+    if (splits < 2 || tiles * splits * 5 < n_cu * 3) return 0;
+    DmaGemmParams p{};
+    p.A = (const bf16_t *)g.A;
+    p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
+    p.C = scratch; p.M = g.M; p.K = g.K; p.segN = g.segN;
+    p.a_rows = g.a_rows; p.w_rows = 0; p.group = 4; p.splits = splits;
+    p.tiles_m = 1; p.N = N; p.tiles_n = tiles;
+    int rc;
+    {
+        ProfScope ps(g.epilogue == EPI_SWIGLU ? "gemm_dma_splitk<swiglu>" : "gemm_dma_splitk<store>", 2.0 * g.M * g.K * (double)N, st);
+        rc = launch_plain<EPI_STORE, false>(p, st);
+        if (rc != 1) return rc;
+    }
+    if ((rc = launch_splitk_reduce(g.epilogue, g.C, (const float *)scratch, splits, g.M, g.epilogue == EPI_SWIGLU ? g.segN : N, st))) return rc;
+    return 1;
 }
 
 namespace {

@@ -131,6 +131,7 @@ __device__ __forceinline__ void vla_tile_of_block(int pid, int tiles_m, int tile
 // shape is outside what it supports (caller then uses the generic kernel), <0 on launch error ----
 int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st);
 int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st);
+int try_gemm_bf16_dma_splitk(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st);
 int launch_weight_kblock(bf16_t *dst, const bf16_t *src, int N, int K, hipStream_t st);
 int launch_rope_kv_write_bf16(bf16_t *q_out, const float *qkv, const float2 *table, const KvView &kv, int layer,
                               const RowsArgs &ra, int H, hipStream_t st);

@@ -278,6 +278,12 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
     const bool kb = !m->packed.empty() && ra.R > 1 && kblocked_shape_ok(c) && dma_gemm_enabled() && force_generic() == 0 &&
                     ws.vt && (size_t)ra.n_seq * c.n_heads <= 65535 && M >= 1 &&
                     (size_t)ws.a_rows * (F > H ? F : H) * 2 < ((size_t)1 << 31);
+    // Single-row bf16 forwards: the split-K GEMMs leave their partial sums to the kernel that follows (rotation + KV
+    // write after the QKV projection, residual add + next RMSNorm after the O and down projections), which adds them
+    // in the order the stand-alone reduction would.
+    const bool fuse_reduce = c.dtype == VLA_DTYPE_BF16 && ra.R == 1 && ws.skinny && !(force_generic() & (2 | 16)) &&
+                             H % 1024 == 0 && H <= 8192;
+    bool have_nrm = false;                 // the previous layer's down projection already wrote this layer's Nrm
     for (int l = 0; l < c.n_layers; l++) {
         const vla_layer_weights &lw = m->layers[l];
         int kl = kv_single_layer ? 0 : l;
@@ -285,7 +291,9 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
             if ((rc = run_layer_kblocked(m, ws, ra, kv, l, kl, st))) return rc;
             continue;
         }
-        if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.attn_norm, M, 0, st))) return rc;
+        if (!have_nrm && (rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.attn_norm, M, 0, st))) return rc;
+        have_nrm = false;
+        int ds = 0;
         GemmArgs g{};
         g.A = ws.Nrm; g.W[0] = lw.wq; g.W[1] = lw.wk; g.W[2] = lw.wv; g.n_seg = 3; g.segN = H;
         g.C = ws.QKV; g.M = M; g.K = H; g.epilogue = EPI_STORE; g.a_rows = ws.a_rows;
@@ -299,8 +307,11 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
             if (fused < 0) return fused;
         }
         if (!fused) {
+            if (fuse_reduce) g.deferred_splits = &ds;
             if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
-            if (c.dtype == VLA_DTYPE_BF16 && !(force_generic() & 16)) rc = launch_rope_kv_write_bf16((bf16_t *)ws.Q, ws.QKV, ws.rope, kv, kl, ra, H, st);
+            if (c.dtype == VLA_DTYPE_BF16 && !(force_generic() & 16))
+                rc = launch_rope_kv_write_bf16((bf16_t *)ws.Q, ds ? (const float *)ws.skinny : ws.QKV, ds ? ds : 1, (size_t)M * 3 * H,
+                                               ws.rope, kv, kl, ra, H, st);
             else rc = launch_rope_kv_write<T>((T *)ws.Q, ws.QKV, ws.rope, kv, kl, ra, H, st);
             if (rc) return rc;
         }
@@ -315,15 +326,30 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
         if (!done && (rc = launch_attention_generic<T>((T *)ws.AO, (const T *)ws.Q, kv, kl, ra, H, st))) return rc;
         g = GemmArgs{};
         g.A = ws.AO; g.W[0] = lw.wo; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = H; g.epilogue = EPI_RESIDUAL; g.a_rows = ws.a_rows;
+        ds = 0;
+        if (fuse_reduce) g.deferred_splits = &ds;
         if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
-        if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.ffn_norm, M, 0, st))) return rc;
+        if (ds) {
+            rc = try_reduce_residual_rmsnorm_bf16((bf16_t *)ws.Nrm, ws.X, (const float *)ws.skinny, ds, M, H, (const float *)lw.ffn_norm, c.rms_eps, st);
+            if (rc == 0) { vla_set_error("internal: fused reduction declined"); return VLA_ESHAPE; }
+            if (rc < 0) return rc;
+        } else if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.ffn_norm, M, 0, st))) return rc;
         g = GemmArgs{};
         g.A = ws.Nrm; g.W[0] = lw.w_gate; g.W[1] = lw.w_up; g.n_seg = 2; g.segN = F; g.C = ws.ACT; g.M = M; g.K = H;
         g.epilogue = EPI_SWIGLU; g.a_rows = ws.a_rows;
         if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
         g = GemmArgs{};
         g.A = ws.ACT; g.W[0] = lw.w_down; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = F; g.epilogue = EPI_RESIDUAL; g.a_rows = ws.a_rows;
+        ds = 0;
+        if (fuse_reduce) g.deferred_splits = &ds;
         if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
+        if (ds) {
+            const float *next_gain = l + 1 < c.n_layers ? (const float *)m->layers[l + 1].attn_norm : nullptr;
+            rc = try_reduce_residual_rmsnorm_bf16((bf16_t *)ws.Nrm, ws.X, (const float *)ws.skinny, ds, M, H, next_gain, c.rms_eps, st);
+            if (rc == 0) { vla_set_error("internal: fused reduction declined"); return VLA_ESHAPE; }
+            if (rc < 0) return rc;
+            have_nrm = next_gain != nullptr;
+        }
     }
     return 0;
 }

@@ -19,7 +19,31 @@ __device__ __forceinline__ bf16x8_t pack8(const float *v) {
     return o;
 }
 
-__global__ void __launch_bounds__(256) rope_kv_write_bf16_kernel(bf16_t *q_out, const float *qkv, const float2 *table,
+// Sum of up to eight partial copies of two 8-float pieces (p and p + off), added in copy order; all loads are
+// issued before the first addition so that their latencies overlap.
+__device__ __forceinline__ void load8x2_sum(const float *p, int off, int splits, size_t split_stride, float (&a)[8], float (&b)[8]) {
+    f32x4_t w[8][4];
+#pragma unroll
+    for (int k = 0; k < 8; k++) {
+        if (k < splits) {
+            const float *q = p + (size_t)k * split_stride;
+            w[k][0] = *(const f32x4_t *)q; w[k][1] = *(const f32x4_t *)(q + 4);
+            w[k][2] = *(const f32x4_t *)(q + off); w[k][3] = *(const f32x4_t *)(q + off + 4);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; e++) { a[e] = w[0][0][e]; a[4 + e] = w[0][1][e]; b[e] = w[0][2][e]; b[4 + e] = w[0][3][e]; }
+#pragma unroll
+    for (int k = 1; k < 8; k++) {
+        if (k < splits) {
+#pragma unroll
+            for (int e = 0; e < 4; e++) { a[e] += w[k][0][e]; a[4 + e] += w[k][1][e]; b[e] += w[k][2][e]; b[4 + e] += w[k][3][e]; }
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256) rope_kv_write_bf16_kernel(bf16_t *q_out, const float *qkv, int splits, size_t split_stride,
+                                                                const float2 *table,
                                                                 bf16_t *kc, bf16_t *vc, size_t total, int R, int pos0,
                                                                 int n_heads, int d, int pos_stride, int H) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -33,9 +57,9 @@ __global__ void __launch_bounds__(256) rope_kv_write_bf16_kernel(bf16_t *q_out, 
     const float *q = qkv + m * 3 * (size_t)H + (size_t)h * d + c * 8;
     const float *k = q + H, *v = q + 2 * (size_t)H;
     float qa[8], qb[8], ka[8], kb[8], va[8], vb[8], cs[16];
-    load8(q, qa); load8(q + half, qb);
-    load8(k, ka); load8(k + half, kb);
-    load8(v, va); load8(v + half, vb);
+    load8x2_sum(q, half, splits, split_stride, qa, qb);
+    load8x2_sum(k, half, splits, split_stride, ka, kb);
+    load8x2_sum(v, half, splits, split_stride, va, vb);
     const float *tb = (const float *)(table + (size_t)r * half + c * 8);     // 8 x (cos, sin)
     load8(tb, cs); load8(tb + 8, cs + 8);
     float qlo[8], qhi[8], klo[8], khi[8];
@@ -74,6 +98,65 @@ __global__ void __launch_bounds__(256) rmsnorm_bf16_kernel(bf16_t *out, const fl
 #pragma unroll
         for (int e = 0; e < 4; e++) ss += v[j][e] * v[j][e];
     }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    if ((t & 63) == 0) red[t >> 6] = ss;
+    __syncthreads();
+    ss = red[0] + red[1] + red[2] + red[3];
+    const float r = 1.0f / sqrtf(ss / (float)H + eps);
+    const f32x4_t *g = (const f32x4_t *)gain;
+    bf16x4_t *o = (bf16x4_t *)(out + (size_t)blockIdx.x * H);
+#pragma unroll
+    for (int j = 0; j < V4; j++) {
+        f32x4_t gg = g[j * 256 + t];
+        bf16x4_t w;
+#pragma unroll
+        for (int e = 0; e < 4; e++) w[e] = (bf16_t)(v[j][e] * r * gg[e]);
+        o[j * 256 + t] = w;
+    }
+}
+
+// Split-K reduction of a residual projection fused with the RMSNorm that follows it: x[m] += sum of the partial
+// rows (in split order, the same additions the stand-alone reduction makes), then the norm of the new row exactly
+// as rmsnorm_bf16_kernel computes it.  gain == NULL: no norm output.
+template <int V4>
+__global__ void __launch_bounds__(256) reduce_residual_rmsnorm_kernel(bf16_t *out, float *X, const float *P, int splits,
+                                                                     size_t split_stride, const float *gain, int H, float eps) {
+    __shared__ float red[4];
+    const int t = threadIdx.x;
+    f32x4_t *x = (f32x4_t *)(X + (size_t)blockIdx.x * H);
+    const f32x4_t *p0 = (const f32x4_t *)(P + (size_t)blockIdx.x * H);
+    f32x4_t v[V4];
+    float ss = 0.f;
+    // every load of the row (partial sums and x) is issued before the first store, then the pieces are added in
+    // split order
+    f32x4_t w[V4][8];
+#pragma unroll
+    for (int j = 0; j < V4; j++) {
+#pragma unroll
+        for (int k = 0; k < 8; k++)
+            if (k < splits) w[j][k] = *(const f32x4_t *)((const float *)(p0 + j * 256 + t) + (size_t)k * split_stride);
+        v[j] = x[j * 256 + t];
+    }
+#pragma unroll
+    for (int j = 0; j < V4; j++) {
+        f32x4_t s = w[j][0];
+#pragma unroll
+        for (int k = 1; k < 8; k++) {
+            if (k < splits) {
+#pragma unroll
+                for (int e = 0; e < 4; e++) s[e] += w[j][k][e];
+            }
+        }
+        f32x4_t xv = v[j];
+#pragma unroll
+        for (int e = 0; e < 4; e++) xv[e] += s[e];
+        x[j * 256 + t] = xv;
+        v[j] = xv;
+#pragma unroll
+        for (int e = 0; e < 4; e++) ss += xv[e] * xv[e];
+    }
+    if (!gain) return;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
     if ((t & 63) == 0) red[t >> 6] = ss;
@@ -186,14 +269,34 @@ int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int 
     return rc ? rc : 1;
 }
 
-int launch_rope_kv_write_bf16(bf16_t *q_out, const float *qkv, const float2 *table, const KvView &kv, int layer,
-                              const RowsArgs &ra, int H, hipStream_t st) {
+int try_reduce_residual_rmsnorm_bf16(bf16_t *out, float *X, const float *P, int splits, int M, int H, const float *gain,
+                                     float eps, hipStream_t st) {
+    if (H % 1024 != 0 || H > 8192 || splits < 1 || splits > 8) return 0;
+    if (M == 0) return 1;
+    ProfScope ps("reduce_residual_norm", (double)M * H * ((splits + 2) * 4.0 + (gain ? 2.0 : 0.0)), st);
+    const size_t stride = (size_t)M * H;
+    switch (H / 1024) {
+        case 1: reduce_residual_rmsnorm_kernel<1><<<M, 256, 0, st>>>(out, X, P, splits, stride, gain, H, eps); break;
+        case 2: reduce_residual_rmsnorm_kernel<2><<<M, 256, 0, st>>>(out, X, P, splits, stride, gain, H, eps); break;
+        case 3: reduce_residual_rmsnorm_kernel<3><<<M, 256, 0, st>>>(out, X, P, splits, stride, gain, H, eps); break;
+        case 4: reduce_residual_rmsnorm_kernel<4><<<M, 256, 0, st>>>(out, X, P, splits, stride, gain, H, eps); break;
+        case 5: reduce_residual_rmsnorm_kernel<5><<<M, 256, 0, st>>>(out, X, P, splits, stride, gain, H, eps); break;
+        case 6: reduce_residual_rmsnorm_kernel<6><<<M, 256, 0, st>>>(out, X, P, splits, stride, gain, H, eps); break;
+        case 7: reduce_residual_rmsnorm_kernel<7><<<M, 256, 0, st>>>(out, X, P, splits, stride, gain, H, eps); break;
+        default: reduce_residual_rmsnorm_kernel<8><<<M, 256, 0, st>>>(out, X, P, splits, stride, gain, H, eps); break;
+    }
+    int rc = vla_check_launch("reduce_residual_rmsnorm");
+    return rc ? rc : 1;
+}
+
+int launch_rope_kv_write_bf16(bf16_t *q_out, const float *qkv, int splits, size_t split_stride, const float2 *table,
+                              const KvView &kv, int layer, const RowsArgs &ra, int H, hipStream_t st) {
     const size_t total = (size_t)ra.n_seq * ra.R * kv.n_heads * (kv.d / 16);
     if (total == 0) return 0;
-    ProfScope ps("rope_kv_write", (double)ra.n_seq * ra.R * H * (3 * 4.0 + 3 * 2.0), st);
+    ProfScope ps("rope_kv_write", (double)ra.n_seq * ra.R * H * (3 * 4.0 * splits + 3 * 2.0), st);
     bf16_t *kc = (bf16_t *)kv.k + (size_t)layer * kv.layer_elems;
     bf16_t *vc = (bf16_t *)kv.v + (size_t)layer * kv.layer_elems;
-    rope_kv_write_bf16_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(q_out, qkv, table, kc, vc, total, ra.R, ra.pos0,
+    rope_kv_write_bf16_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(q_out, qkv, splits, split_stride, table, kc, vc, total, ra.R, ra.pos0,
                                                                               kv.n_heads, kv.d, kv.pos_stride, H);
     return vla_check_launch("rope_kv_write_bf16");
 }

@@ -640,7 +640,8 @@ int try_gemm_bf16_dma_splitk(const GemmArgs &g, void *scratch, size_t scratch_by
         rc = launch_plain<EPI_STORE, false>(p, st);
         if (rc != 1) return rc;
     }
-    if ((rc = launch_splitk_reduce(g.epilogue, g.C, (const float *)scratch, splits, g.M, g.epilogue == EPI_SWIGLU ? g.segN : N, st))) return rc;
+    if (g.deferred_splits && g.epilogue == EPI_STORE) *g.deferred_splits = splits;
+    else if ((rc = launch_splitk_reduce(g.epilogue, g.C, (const float *)scratch, splits, g.M, g.epilogue == EPI_SWIGLU ? g.segN : N, st))) return rc;
     return 1;
 }
 

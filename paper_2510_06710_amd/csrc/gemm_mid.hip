@@ -232,6 +232,7 @@ int try_gemm_bf16_mid(const GemmArgs &g, void *scratch, size_t scratch_bytes, hi
         else rc = launch_epi<EPI_STORE>(p, st);         // store and residual differ only in the reduction
         if (rc) return rc;
     }
-    if ((rc = launch_splitk_reduce(g.epilogue, g.C, p.P, splits, g.M, p.N, st))) return rc;
+    if (g.deferred_splits && (g.epilogue == EPI_STORE || g.epilogue == EPI_RESIDUAL)) *g.deferred_splits = splits;
+    else if ((rc = launch_splitk_reduce(g.epilogue, g.C, p.P, splits, g.M, p.N, st))) return rc;
     return 1;
 }

@@ -309,6 +309,9 @@ int try_gemm_bf16_skinny(const GemmArgs &g, void *scratch, hipStream_t st) {
         else rc = launch_epi<EPI_STORE>(p, n_tiles, st);
         if (rc) return rc;
     }
-    if (splits > 1 && (rc = launch_splitk_reduce(g.epilogue, g.C, p.P, splits, g.M, p.N, st))) return rc;
+    if (splits > 1) {
+        if (g.deferred_splits && (g.epilogue == EPI_STORE || g.epilogue == EPI_RESIDUAL)) *g.deferred_splits = splits;
+        else if ((rc = launch_splitk_reduce(g.epilogue, g.C, p.P, splits, g.M, p.N, st))) return rc;
+    }
     return 1;
 }

@@ -61,6 +61,9 @@ struct GemmArgs {
                             // on its own) and a SwiGLU output are stored [K / 32][rows][32]: direct-to-LDS kernel only
     int a_rows;             // rows of A that may be read (>= M; contents past M arbitrary): the MFMA kernel
                             // loads whole 256-row tiles and declines if the buffer does not cover them
+    int *deferred_splits;   // not NULL (EPI_STORE and EPI_RESIDUAL of the split-K kernels): the kernel leaves its n
+                            // partial products [n][M][N] at the start of the scratch buffer, puts n here and does not
+                            // reduce them (the caller's next kernel adds them in order); 0 here: C is complete
 };
 
 // ---- generic (any shape, fp32 or bf16 storage) kernels: kernels_generic.hip -----------------
@@ -133,8 +136,13 @@ int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st);
 int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st);
 int try_gemm_bf16_dma_splitk(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st);
 int launch_weight_kblock(bf16_t *dst, const bf16_t *src, int N, int K, hipStream_t st);
-int launch_rope_kv_write_bf16(bf16_t *q_out, const float *qkv, const float2 *table, const KvView &kv, int layer,
-                              const RowsArgs &ra, int H, hipStream_t st);
+// qkv: `splits` partial copies of the fp32 [M, 3H] projection, `split_stride` floats apart, added in order
+int launch_rope_kv_write_bf16(bf16_t *q_out, const float *qkv, int splits, size_t split_stride, const float2 *table,
+                              const KvView &kv, int layer, const RowsArgs &ra, int H, hipStream_t st);
+// x[m] += sum of the `splits` partial rows P[k][m] (in order); then, if gain != NULL, out[m] = RMSNorm(x[m]) * gain as
+// bf16, row-major.  Returns 1 if handled (H a multiple of 1024, at most 8192), 0 otherwise.
+int try_reduce_residual_rmsnorm_bf16(bf16_t *out, float *X, const float *P, int splits, int M, int H, const float *gain,
+                                     float eps, hipStream_t st);
 // kb_rows = 0: row-major output [M, H]; else k-blocked [H / 32][kb_rows][32]
 int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int H, float eps, int kb_rows, hipStream_t st);
 int try_gemm_bf16_skinny(const GemmArgs &g, void *scratch, hipStream_t st);

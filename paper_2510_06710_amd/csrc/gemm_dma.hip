@@ -1,5 +1,7 @@
 // bf16 MFMA GEMM for gfx950 with direct-to-LDS loads: C[M, N] = A[M, K] . W[N, K]^T, fp32 accumulation.
-// This is the kernel of the prefill / recompute / parallel-chunk projections (whole tiles, no split K).
+// This is the kernel of the prefill / recompute / parallel-chunk projections (whole tiles), and, with K cut into
+// equal ranges whose fp32 partial products go to a scratch buffer, of the QKV and gate/up projections of decode
+// forwards of 129..256 rows.
 //
 // Tiling: 256 x 256 output tiles, 4 waves (one per SIMD), 128 x 128 per wave as 8 x 8 blocks of
 // v_mfma_f32_16x16x32_bf16 (256 fp32 accumulators per lane).  The weight rows are the MFMA's row
@@ -17,6 +19,11 @@
 // the other buffer}, with the eight load instructions of half tile g + 3 spread between them.  The
 // fragment reads are inline assembly with explicit waits: the compiler would otherwise wait for every
 // outstanding LDS-bound load before any LDS read.
+//
+// Unit-barrier variant of that schedule (UB, used by the gate/up projection): one wait and one barrier per pair of
+// half tiles.  At the start of even iteration g the pair (g, g + 1) has landed and every wave has finished reading
+// (g - 2, g - 1), whose two stages take the sixteen load instructions of (g + 2, g + 3), all issued during
+// iteration g: half the barriers, for a prefetch distance of two half tiles instead of three.
 //
 // Operand layout.  Row-major operands are fetched as 64-byte pieces of 16 rows per instruction, i.e. half
 // cache lines; in the k-blocked layout (KB: [K / 32][rows][32] for the activations and for repacked weights)

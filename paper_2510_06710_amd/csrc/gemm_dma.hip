@@ -198,33 +198,48 @@ __device__ __forceinline__ void epilogue(f32x4_t (&acc)[8][8], const DmaGemmPara
         }
         return;
     }
-    // fp32 store, or read-modify-write of the fp32 residual stream (x of a block is loaded before the block
-    // is staged, whole 512-byte rows, two rows per instruction)
-    float *out = (float *)p.C + c_off + (size_t)tn * BN + wn * 128 + (lane & 31) * 4;
+    // fp32 store, or read-modify-write of the fp32 residual stream: whole 512-byte rows, two rows per instruction,
+    // through a buffer descriptor over this wave's 128 x 128 block (rows past M fall outside it: their loads
+    // return zero and their stores are dropped, so no clamp and no predicate).  x is read XD 16-row blocks ahead of
+    // the block being staged, so that a memory latency is paid once per tile and not once per block.
+    const int rows_in = min(128, p.M - (m0 + wm * 128));
+    float *wave_out = (float *)p.C + c_off + (size_t)(m0 + wm * 128) * p.N + (size_t)tn * BN + wn * 128;
+    __amdgpu_buffer_rsrc_t c_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)wave_out, (short)0, rows_in > 0 ? rows_in * p.N * 4 : 0, 0x00020000);
+    const int voff = ((lane >> 5) * p.N + (lane & 31) * 4) * 4;
+    const int row2 = 2 * p.N * 4;                      // bytes between the row pairs of consecutive instructions
+    constexpr int XD = 2;
+    i32x4_t x[XD][8];
+    // (the stride passes through an empty assembler statement per block: otherwise all 64 offsets of a tile are
+    // computed once, before the main loop, and held in registers across it)
+    auto load_x = [&](i32x4_t (&xb)[8], int i) {
+        int r2 = row2;
+        asm volatile("" : "+v"(r2));
+#pragma unroll
+        for (int it = 0; it < 8; it++) xb[it] = __builtin_amdgcn_raw_buffer_load_b128(c_rsrc, voff + (i * 8 + it) * r2, 0, 0);
+    };
+    if (EPI == EPI_RESIDUAL) {
+#pragma unroll
+        for (int i = 0; i < XD; i++) load_x(x[i], i);
+    }
 #pragma unroll
     for (int i = 0; i < 8; i++) {
-        const int mblock = m0 + wm * 128 + i * 16;
         __builtin_amdgcn_sched_barrier(0);
-        f32x4_t x[8];
-        if (EPI == EPI_RESIDUAL) {
-#pragma unroll
-            for (int it = 0; it < 8; it++) {
-                const int m = min(mblock + it * 2 + (lane >> 5), p.M - 1);
-                x[it] = *(const f32x4_t *)(out + (size_t)m * p.N);
-            }
-        }
+        int r2 = row2;
+        asm volatile("" : "+v"(r2));
 #pragma unroll
         for (int j = 0; j < 8; j++) *(f32x4_t *)panel_at(panel, l16, j * 4 + kq) = acc_read4(acc[j][i]);
 #pragma unroll
         for (int it = 0; it < 8; it++) {
-            const int row = it * 2 + (lane >> 5), m = mblock + row;
+            const int row = it * 2 + (lane >> 5);
             f32x4_t v = *(const f32x4_t *)panel_at(panel, row, lane & 31);
             if (EPI == EPI_RESIDUAL) {
+                const f32x4_t xv = __builtin_bit_cast(f32x4_t, x[i % XD][it]);
 #pragma unroll
-                for (int e = 0; e < 4; e++) v[e] += x[it][e];
+                for (int e = 0; e < 4; e++) v[e] += xv[e];
             }
-            if (m < p.M) *(f32x4_t *)(out + (size_t)m * p.N) = v;
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(i32x4_t, v), c_rsrc, voff + (i * 8 + it) * r2, 0, 0);
         }
+        if (EPI == EPI_RESIDUAL && i + XD < 8) load_x(x[i % XD], i + XD);
     }
 }
 

@@ -14,6 +14,8 @@
 // O^T are per-lane scalars, with one lane-xor-32 exchange per key block.
 #include "vla_internal.h"
 
+#include <type_traits>
+
 namespace {
 
 // V [position][d] of the cache -> VT [d/32][ps_pad/4][32][4]: for a block of 32 head dims, the four
@@ -190,26 +192,29 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4))
 // transposed copy of V is needed in memory.  The arithmetic per wave is the same (same MFMA operand roles, same
 // split of the probabilities into two bf16 terms).
 //
+// The fetching is the job of one extra wave: it holds no queries and no accumulators, so its registers take two
+// whole key blocks (16 KB each), and the query waves need no staging registers at all.  In step kb it issues the
+// loads of block kb + 2 into the register set that block kb held and writes block kb + 1 from the other set to
+// LDS stage (kb + 1) % 2 while the query waves work on stage kb % 2; one barrier per step.
+//
 // LDS per stage: K  [16 dim chunks][32 keys][8]            8 KB, read back as 16-byte row operands;
 //                VT [128 dims][32 key slots + 8 pad]      10 KB; key 16u + 8a + 4h + c (a, h in {0,1}, c < 4) sits in
 //                   slot 16u + 8h + 4a + c, so that the eight keys a lane feeds to k slots (h, 0..7) of product u
 //                   are one 16-byte read; the 80-byte row stride makes those reads conflict free.
-// Two stages: block j + 1 is fetched into registers before block j is computed and written to the other stage
-// afterwards, one barrier per block.
 constexpr int ATT_K_BYTES = 16 * 32 * 16;
 constexpr int ATT_VT_STRIDE = 80;                      // bytes per dim row of VT
 constexpr int ATT_VT_BYTES = 128 * ATT_VT_STRIDE;
 constexpr int ATT_STAGE = ATT_K_BYTES + ATT_VT_BYTES;
 
 template <int NW>
-__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW == 4 ? 3 : 1)))
-attn_prefill_shared_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
+__global__ void __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(NW == 3 ? 3 : 1)))
+attn_prefill_loader_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
                                                                      const bf16_t *vc, int R, int pos0, int full_from,
                                                                      int n_heads, int pos_stride, int H, int q_blocks,
                                                                      int out_kb_rows) {
-    constexpr int D = 128, KS = D / 16, DB = D / 32, NT = NW * 64;
-    constexpr int K_UNITS = (512 + NT - 1) / NT;       // 16-byte units of a K block per thread
-    constexpr int V_UNITS = (256 + NT - 1) / NT;       // (key pair, 8 dims) units of a V block per thread
+    constexpr int D = 128, KS = D / 16, DB = D / 32;
+    constexpr int K_UNITS = 8;                         // 16-byte units of a K block per lane of the loading wave
+    constexpr int V_UNITS = 4;                         // (key pair, 8 dims) units of a V block per lane
     __shared__ __attribute__((aligned(16))) unsigned char lds[2 * ATT_STAGE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int item = blockIdx.y;                       // sequence * n_heads + head
@@ -217,7 +222,7 @@ attn_prefill_shared_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
     const int nk = pos0 + R;
     const int col = lane & 31, hh = lane >> 5;
     const int qb = blockIdx.x * NW + wave;
-    const bool active = qb < q_blocks;                 // waves past the last query block only help loading
+    const bool active = qb < q_blocks && wave < NW;
     const int r = min(qb * 32 + col, R - 1);
     const int qpos = pos0 + r;
     const int limit = (qpos >= full_from) ? nk : qpos + 1;          // keys [0, limit) are visible to this lane
@@ -233,45 +238,40 @@ attn_prefill_shared_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
     const bf16_t *vh = vc + (size_t)item * pos_stride * D;
 
     bf16x8_t qf[KS];
-    {
+    if (wave < NW) {
         const bf16_t *qrow = qbuf + ((size_t)s * R + r) * H + (size_t)h * D;
 #pragma unroll
         for (int kk = 0; kk < KS; kk++) qf[kk] = *(const bf16x8_t *)(qrow + kk * 16 + hh * 8);
     }
 
-    // ---- staging: global -> registers -> LDS -------------------------------------------------------------
-    bf16x8_t kreg[K_UNITS], vreg[V_UNITS][2];
-    auto fetch = [&](int kb) {
+    // ---- the loading wave: global -> registers -> LDS, two key blocks in flight ------------------------------
+    if (wave == NW) {
+        bf16x8_t kreg[2][K_UNITS], vreg[2][V_UNITS][2];
+        auto fetch = [&](auto set_c, int kb) {
+            constexpr int SET = decltype(set_c)::value;
 #pragma unroll
-        for (int u = 0; u < K_UNITS; u++) {
-            int q = tid + u * NT;                      // (dim chunk, key)
-            if (512 % NT == 0 || q < 512) {
+            for (int u = 0; u < K_UNITS; u++) {
+                int q = lane + u * 64;                     // (dim chunk, key)
                 int c = q >> 5, key = min(kb * 32 + (q & 31), nk - 1);
-                kreg[u] = *(const bf16x8_t *)((const char *)kh + (unsigned)(c * pos_stride + key) * 16u);
+                kreg[SET][u] = *(const bf16x8_t *)((const char *)kh + (unsigned)(c * pos_stride + key) * 16u);
             }
-        }
 #pragma unroll
-        for (int u = 0; u < V_UNITS; u++) {
-            int q = tid + u * NT;                      // (key pair, dim chunk): 16 lanes cover one key pair's 128 dims
-            if (256 % NT == 0 || q < 256) {
+            for (int u = 0; u < V_UNITS; u++) {
+                int q = lane + u * 64;                     // (key pair, dim chunk): 16 lanes cover one key pair's 128 dims
                 int t = q >> 4, c = q & 15;
                 int k0 = min(kb * 32 + 2 * t, nk - 1), k1 = min(kb * 32 + 2 * t + 1, nk - 1);
-                vreg[u][0] = *(const bf16x8_t *)((const char *)vh + (unsigned)(k0 * D + c * 8) * 2u);
-                vreg[u][1] = *(const bf16x8_t *)((const char *)vh + (unsigned)(k1 * D + c * 8) * 2u);
+                vreg[SET][u][0] = *(const bf16x8_t *)((const char *)vh + (unsigned)(k0 * D + c * 8) * 2u);
+                vreg[SET][u][1] = *(const bf16x8_t *)((const char *)vh + (unsigned)(k1 * D + c * 8) * 2u);
             }
-        }
-    };
-    auto stash = [&](int stage) {
-        unsigned char *kb_lds = lds + stage * ATT_STAGE, *vt_lds = kb_lds + ATT_K_BYTES;
+        };
+        auto stash = [&](auto set_c, int stage) {
+            constexpr int SET = decltype(set_c)::value;
+            unsigned char *kb_lds = lds + stage * ATT_STAGE, *vt_lds = kb_lds + ATT_K_BYTES;
 #pragma unroll
-        for (int u = 0; u < K_UNITS; u++) {
-            int q = tid + u * NT;
-            if (512 % NT == 0 || q < 512) *(bf16x8_t *)(kb_lds + q * 16) = kreg[u];
-        }
+            for (int u = 0; u < K_UNITS; u++) *(bf16x8_t *)(kb_lds + (lane + u * 64) * 16) = kreg[SET][u];
 #pragma unroll
-        for (int u = 0; u < V_UNITS; u++) {
-            int q = tid + u * NT;
-            if (256 % NT == 0 || q < 256) {
+            for (int u = 0; u < V_UNITS; u++) {
+                int q = lane + u * 64;
                 int t = q >> 4, c = q & 15;
                 // key 2t = 16u' + 8a + 4h' + c' with c' even: slot 16u' + 8h' + 4a + c'
                 int slot = (t >> 3) * 16 + ((t >> 1) & 1) * 8 + ((t >> 2) & 1) * 4 + (t & 1) * 2;
@@ -279,13 +279,31 @@ attn_prefill_shared_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
                 for (int e = 0; e < 8; e++) {
                     typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
                     bf16x2_t pr;
-                    pr[0] = vreg[u][0][e];
-                    pr[1] = vreg[u][1][e];
+                    pr[0] = vreg[SET][u][0][e];
+                    pr[1] = vreg[SET][u][1][e];
                     *(bf16x2_t *)(vt_lds + (c * 8 + e) * ATT_VT_STRIDE + slot * 2) = pr;
                 }
             }
+        };
+        using SA = std::integral_constant<int, 0>;
+        using SB = std::integral_constant<int, 1>;
+        fetch(SA{}, 0);
+        if (n_kb > 1) fetch(SB{}, 1);
+        stash(SA{}, 0);
+        __syncthreads();                                   // block 0 is in stage 0
+        // iteration kb: the other waves work on stage kb % 2; this one fetches block kb + 2 into the register set
+        // that block kb held and moves block kb + 1 from the other set into stage (kb + 1) % 2
+        for (int kb = 0; kb < n_kb; kb += 2) {
+            if (kb + 2 < n_kb) fetch(SA{}, kb + 2);
+            if (kb + 1 < n_kb) stash(SB{}, (kb + 1) & 1);
+            __syncthreads();
+            if (kb + 1 >= n_kb) break;
+            if (kb + 3 < n_kb) fetch(SB{}, kb + 3);
+            if (kb + 2 < n_kb) stash(SA{}, kb & 1);
+            __syncthreads();
         }
-    };
+        return;
+    }
 
     f32x16_t o_acc[DB];
 #pragma unroll
@@ -295,17 +313,13 @@ attn_prefill_shared_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
     float m_run = -INFINITY, l_run = 0.f;
     const float c2 = 1.4426950408889634f / sqrtf((float)D);        // logits scale folded into the base-2 exponent
 
-    fetch(0);
-    stash(0);
-    __syncthreads();
+    __syncthreads();                                       // block 0 is in stage 0
     // An empty statement that reads the query fragments: their loads are waited for here, once.  Otherwise the
     // waits the compiler places in the loop must allow for a fragment still in flight on entry, and on every
     // later pass those same waits drain the prefetch of the next key block.
 #pragma unroll
     for (int kk = 0; kk < KS; kk++) asm volatile("" ::"v"(qf[kk]));
     for (int kb = 0; kb < n_kb; kb++) {
-        const bool more = kb + 1 < n_kb;
-        if (more) fetch(kb + 1);
         if (kb < my_nkb) {
             const unsigned char *k_lds = lds + (kb & 1) * ATT_STAGE, *vt_lds = k_lds + ATT_K_BYTES;
             // ---- S^T block: rows = keys kb*32 .. +31, columns = the wave's 32 queries -----------------------
@@ -362,7 +376,6 @@ attn_prefill_shared_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
                 }
             }
         }
-        if (more) stash((kb + 1) & 1);
         __syncthreads();
     }
     // ---- store: lane holds query `col`, dims b*32 + 8*(i/4) + 4*hh + i%4 -------------------------------------
@@ -384,11 +397,11 @@ attn_prefill_shared_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
 }
 
 template <int NW>
-int launch_shared(bf16_t *out, const bf16_t *q, const bf16_t *kc, const bf16_t *vc, const RowsArgs &ra, const KvView &kv,
+int launch_loader(bf16_t *out, const bf16_t *q, const bf16_t *kc, const bf16_t *vc, const RowsArgs &ra, const KvView &kv,
                   int H, int q_blocks, int n_items, int out_kb_rows, hipStream_t st) {
     dim3 grid((q_blocks + NW - 1) / NW, n_items);
-    attn_prefill_shared_kernel<NW><<<grid, NW * 64, 0, st>>>(out, q, kc, vc, ra.R, ra.pos0, ra.full_from, kv.n_heads,
-                                                            kv.pos_stride, H, q_blocks, out_kb_rows);
+    attn_prefill_loader_kernel<NW><<<grid, (NW + 1) * 64, 0, st>>>(out, q, kc, vc, ra.R, ra.pos0, ra.full_from, kv.n_heads,
+                                                                  kv.pos_stride, H, q_blocks, out_kb_rows);
     return vla_check_launch("attn_prefill");
 }
 
@@ -430,10 +443,15 @@ int try_attention_prefill_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, i
         // its own key block in flight, which hides the memory latency that one large workgroup per CU (nine waves
         // for 288 queries, every key block fetched once) exposes between its lockstep steps; measured 23.5 ms
         // against 26.0 ms per 7B prefill step at 256 x 288 rows.
-        switch (q_blocks <= 2 ? q_blocks : 4) {
-        case 1: rc = launch_shared<1>(out, q, kc, vc, ra, kv, H, q_blocks, n_items, out_kb_rows, st); break;
-        case 2: rc = launch_shared<2>(out, q, kc, vc, ra, kv, H, q_blocks, n_items, out_kb_rows, st); break;
-        default: rc = launch_shared<4>(out, q, kc, vc, ra, kv, H, q_blocks, n_items, out_kb_rows, st); break;
+        // One wave per 32-query block, at most three of them plus the loading wave per workgroup: three such
+        // workgroups fit a CU (36 KB LDS, 158 registers), each with two key blocks in flight.  Larger workgroups
+        // fetch every key block fewer times but leave fewer independent workgroups per CU to cover the dependent
+        // chain of a step (QK, softmax, PV); measured per 7B prefill step at 256 x 288 rows, with every wave also
+        // loading: nine waves 26.0 ms, five or six 36-37 ms, four 21.6 ms; three + loading wave 19.9 ms.
+        switch (q_blocks <= 2 ? q_blocks : 3) {
+        case 1: rc = launch_loader<1>(out, q, kc, vc, ra, kv, H, q_blocks, n_items, out_kb_rows, st); break;
+        case 2: rc = launch_loader<2>(out, q, kc, vc, ra, kv, H, q_blocks, n_items, out_kb_rows, st); break;
+        default: rc = launch_loader<3>(out, q, kc, vc, ra, kv, H, q_blocks, n_items, out_kb_rows, st); break;
         }
         return rc ? rc : 1;
     }

@@ -77,6 +77,22 @@ def test_aligned_bf16_chunk_and_recompute_fast_kernels():
                                                         oracle_recompute(wl, 11, ref["bins"]), "bf16"))
 
 
+@pytest.mark.parametrize("prefix,slots", [(131, 70), (97, 33)])
+def test_aligned_bf16_longer_prefix_several_query_groups(prefix, slots):
+    """Prefixes of more than 96 rows take several workgroups of the prefill attention per (sequence, head) (three
+    32-query waves each), with a ragged last query block and a ragged last key block; the parallel chunk then runs
+    70 (33) slot rows at position offset `prefix` against prefix + slots keys."""
+    wl = vi.scaled(ALIGNED, batch=3, n_patches=prefix - 11, n_instr=11, n_action=slots, mode=1)
+    ref = oracle_rollout(wl, 15)
+    case = GpuCase(wl, 15)
+    _print(f"aligned prefix {prefix} chunk {slots}", compare_rollout(case.rollout(), ref, "bf16", autoregressive=False))
+    _print(f"aligned prefix {prefix} recompute", compare_recompute(case.recompute(ref["bins"]),
+                                                                  oracle_recompute(wl, 15, ref["bins"]), "bf16"))
+    wl = vi.scaled(ALIGNED, batch=3, n_patches=prefix - 11, n_instr=11, n_action=3)
+    _print(f"aligned prefix {prefix} autoregressive",
+           compare_rollout(GpuCase(wl, 16).rollout(), oracle_rollout(wl, 16), "bf16", autoregressive=True))
+
+
 def test_tiny_bf16_rollout():
     wl = vi.scaled(TINY, dtype="bf16")
     ref = oracle_rollout(wl, 2)

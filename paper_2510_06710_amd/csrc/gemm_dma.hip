@@ -11,8 +11,10 @@
 // K moves in half tiles of 32 through a ring of four 32 KB LDS stages.  `buffer_load ... lds` writes
 // the operands straight into LDS (no staging registers, no ds_write): a wave instruction fills 1 KB
 // linearly, i.e. 16 tile rows of 64 bytes; chunk c (16 bytes) of row r sits at position
-// c ^ ((r >> 2) & 3), chosen on the global side by which chunk a lane fetches, so that the fragment
-// reads are free of bank conflicts.  The loads of half tile g + 3 are issued while half tile g is read.
+// c ^ ((r >> 1) & 3), chosen on the global side by which chunk a lane fetches, so that the fragment
+// reads are free of bank conflicts: a ds_read_b128 is served eight lanes (128 bytes) at a time, and the eight
+// 64-byte rows of such a group then cover the eight 16-byte slots of 128 bytes (with (r >> 2) & 3, which would
+// suit 256 bytes per step, SQ_LDS_BANK_CONFLICT showed every read taking twice as long).  The loads of half tile g + 3 are issued while half tile g is read.
 //
 // Schedule of one iteration g (one barrier): wait for this wave's loads of half tile g, barrier, then 16
 // groups of {one ds_read_b128 of half tile g into fragment buffer g % 2, four MFMAs of half tile g - 1 from
@@ -257,10 +259,10 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
 
     // ---- load cursor -------------------------------------------------------------------------------------
     // A wave instruction covers 16 tile rows: lane l -> row l / 4, position l % 4 of the 64-byte row, which
-    // holds chunk (l % 4) ^ ((row / 4) % 4).  This wave loads tile rows wave * 64 .. + 63 of both operands, four
+    // holds chunk (l % 4) ^ ((row / 2) % 4).  This wave loads tile rows wave * 64 .. + 63 of both operands, four
     // instructions each; SwiGLU tiles interleave 64 gate and 64 up rows per wave of the multiply side, so
     // loading wave w takes 64 rows of W0 (w even) or W1 (w odd).
-    const int chunk_off = ((lane & 3) ^ ((lane >> 4) & 3)) << 4;
+    const int chunk_off = ((lane & 3) ^ ((lane >> 3) & 3)) << 4;
     const int row_bytes = KB ? 64 : K * 2;       // distance of consecutive tile rows of one half tile
     const int a_thread_off = (wave * 64 + (lane >> 2)) * row_bytes + chunk_off;
     const int w_thread_off = (((EPI == EPI_SWIGLU) ? (wave >> 1) * 64 : wave * 64) + (lane >> 2)) * row_bytes + chunk_off;
@@ -312,7 +314,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
     };
 
     // ---- fragments -----------------------------------------------------------------------------------------
-    const int l16 = lane & 15, kq = lane >> 4, fsw = (l16 >> 2) & 3;
+    const int l16 = lane & 15, kq = lane >> 4, fsw = (l16 >> 1) & 3;
     const int lds0 = (int)(size_t)(lds_void *)lds;
     const int a_base = lds0 + (wm * 128 + l16) * 64 + ((kq ^ fsw) << 4);
     const int w_base = lds0 + REGION + (wn * 128 + l16) * 64 + ((kq ^ fsw) << 4);

@@ -198,12 +198,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4))
 // LDS stage (kb + 1) % 2 while the query waves work on stage kb % 2; one barrier per step.
 //
 // LDS per stage: K  [16 dim chunks][32 keys][8]            8 KB, read back as 16-byte row operands;
-//                VT [128 dims][32 key slots + 8 pad]      10 KB; key 16u + 8a + 4h + c (a, h in {0,1}, c < 4) sits in
-//                   slot 16u + 8h + 4a + c, so that the eight keys a lane feeds to k slots (h, 0..7) of product u
-//                   are one 16-byte read; the 80-byte row stride makes those reads conflict free.
+//                VT [4 groups of 8 key slots][128 dims (+ one 16-byte pad per 8 dims)][8 slots]   9 KB; key
+//                   16u + 8a + 4h + c (a, h in {0,1}, c < 4) sits in slot 16u + 8h + 4a + c, so that the eight keys
+//                   a lane feeds to k slots (h, 0..7) of product u are the 16-byte unit (group 2u + h, its dim).
+//                   Eight lanes = eight consecutive dims read 128 contiguous bytes: no bank conflicts.  The
+//                   loading wave writes 4 bytes (a key pair of one dim) per lane, sixteen lanes eight dims apart:
+//                   the pad puts those 144 instead of 128 bytes apart, a 2-way conflict instead of a 16-way one.
 constexpr int ATT_K_BYTES = 16 * 32 * 16;
-constexpr int ATT_VT_STRIDE = 80;                      // bytes per dim row of VT
-constexpr int ATT_VT_BYTES = 128 * ATT_VT_STRIDE;
+constexpr int ATT_VT_GROUP = 128 + 16;                 // 16-byte units per group of eight key slots: 128 dims + 1 pad per 8 dims
+constexpr int ATT_VT_BYTES = 4 * ATT_VT_GROUP * 16;
 constexpr int ATT_STAGE = ATT_K_BYTES + ATT_VT_BYTES;
 
 template <int NW>
@@ -281,7 +284,7 @@ attn_prefill_loader_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
                     bf16x2_t pr;
                     pr[0] = vreg[SET][u][0][e];
                     pr[1] = vreg[SET][u][1][e];
-                    *(bf16x2_t *)(vt_lds + (c * 8 + e) * ATT_VT_STRIDE + slot * 2) = pr;
+                    *(bf16x2_t *)(vt_lds + ((slot >> 3) * ATT_VT_GROUP + c * 9 + e) * 16 + (slot & 7) * 2) = pr;
                 }
             }
         };
@@ -370,7 +373,7 @@ attn_prefill_loader_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
             for (int u = 0; u < 2; u++) {
 #pragma unroll
                 for (int b = 0; b < DB; b++) {
-                    bf16x8_t vf = *(const bf16x8_t *)(vt_lds + (b * 32 + col) * ATT_VT_STRIDE + (16 * u + 8 * hh) * 2);
+                    bf16x8_t vf = *(const bf16x8_t *)(vt_lds + ((2 * u + hh) * ATT_VT_GROUP + (b * 32 + col) + ((b * 32 + col) >> 3)) * 16);
                     o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], o_acc[b], 0, 0, 0);
                     o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pl[u], o_acc[b], 0, 0, 0);
                 }

@@ -80,14 +80,18 @@ def cpu_baseline(wl, vi, sample_layers=8):
                       f"{wl.n_action} action tokens), fp64 numpy, {dt:.1f} s measured, scaled by layers"}
 
 
+RECOMPUTE_MICRO_BATCH = 256
+
+
 def bench_recompute(args, wl, torch, vi, vb, Rollout):
     """The log-prob recompute workload (cfg5): a step is one vla_logprob_recompute call over all stored
-    rollouts (internally micro-batched by max_batch = 128)."""
+    rollouts, internally micro-batched by max_batch = 256 (75,264 rows per pass: 294 row tiles of the GEMMs, whose
+    O / down projections then fill 18.4 rounds of the 256 CUs instead of the 9.2 rounds that 128 rollouts give)."""
     dev = "cuda:0"
     torch.cuda.set_device(0)
     N, S, A, shape = wl.batch, wl.prefix, wl.n_action, wl.shape
     synth = vi.SynthModel(shape, 0, device=dev)
-    run = Rollout(synth, min(N, 128), S + A, device=dev, value_b=vi.VALUE_BIAS)
+    run = Rollout(synth, min(N, RECOMPUTE_MICRO_BATCH), S + A, device=dev, value_b=vi.VALUE_BIAS)
     patch, ids = vi.observation(wl, 0, device=dev)
     bins = vi.stored_bins(wl, 0, device=dev)
     slot = synth.slot_embed(A) if wl.mode == 1 else None
@@ -124,7 +128,7 @@ def bench_recompute(args, wl, torch, vi, vb, Rollout):
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
            "config": {"workload": wl.name, "rollouts": N, "prefix": S, "action_tokens": A, "rows_per_rollout": rows,
-                      "micro_batch": min(N, 128), "layers": shape.n_layers, "hidden": shape.hidden},
+                      "micro_batch": min(N, RECOMPUTE_MICRO_BATCH), "layers": shape.n_layers, "hidden": shape.hidden},
            "roofline": roofline,
            "phases": {"recompute_tokens_per_s": N * rows / (ms * 1e-3), "mfma_TFLOPs": flops / (ms * 1e-3) / 1e12,
                       "mfma_frac": flops / (ms * 1e-3) / 1e12 / MI355X_BF16_TFLOPS},

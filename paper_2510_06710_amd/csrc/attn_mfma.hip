@@ -214,18 +214,37 @@ __global__ void __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per
 attn_prefill_loader_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
                                                                      const bf16_t *vc, int R, int pos0, int full_from,
                                                                      int n_heads, int pos_stride, int H, int q_blocks,
-                                                                     int out_kb_rows) {
+                                                                     int out_kb_rows, int n_items, int n_groups) {
     constexpr int D = 128, KS = D / 16, DB = D / 32;
     constexpr int K_UNITS = 8;                         // 16-byte units of a K block per lane of the loading wave
     constexpr int V_UNITS = 4;                         // (key pair, 8 dims) units of a V block per lane
     __shared__ __attribute__((aligned(16))) unsigned char lds[2 * ATT_STAGE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int item = blockIdx.y;                       // sequence * n_heads + head
+    // Workgroup ids are dealt round-robin to the eight XCDs.  With an odd number of groups per (sequence, head) item
+    // the plain order (group fastest) gives every XCD the same mix of long and short groups.  With an even number,
+    // group g of every item would land on the same few XCDs (four groups: XCDs g and g + 4 only), so there the ids
+    // of one XCD, taken in order, walk (item, group) with the group fastest.
+    int item, grp;                                     // item = sequence * n_heads + head
+    {
+        const int w = blockIdx.x;
+        const int remapped = (n_groups & 1) ? 0 : (n_items & ~7) * n_groups;
+        if (w < remapped) {
+            const int local = w >> 3, il = local / n_groups;
+            item = il * 8 + (w & 7);
+            grp = local - il * n_groups;
+        } else {
+            item = w / n_groups;
+            grp = w - item * n_groups;
+        }
+    }
     const int s = item / n_heads, h = item - s * n_heads;
     const int nk = pos0 + R;
     const int col = lane & 31, hh = lane >> 5;
-    const int qb = blockIdx.x * NW + wave;
-    const bool active = qb < q_blocks && wave < NW;
+    // Query blocks are grouped from the last one down: a ragged group then holds the first blocks, which see the
+    // fewest keys, and the groups with the most key blocks are dispatched first.
+    const int qb0 = q_blocks - (grp + 1) * NW;
+    const int qb = max(qb0 + wave, 0);
+    const bool active = qb0 + wave >= 0 && wave < NW;
     const int r = min(qb * 32 + col, R - 1);
     const int qpos = pos0 + r;
     const int limit = (qpos >= full_from) ? nk : qpos + 1;          // keys [0, limit) are visible to this lane
@@ -234,7 +253,7 @@ attn_prefill_loader_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
     const int w_last = min(qb * 32 + 31, R - 1), w_first = min(qb * 32, R - 1);
     const int my_nkb = active ? (limit_of_row(w_last) + 31) >> 5 : 0;
     const int my_full_kb = limit_of_row(w_first) >> 5;              // blocks below this need no mask
-    const int g_last = min((int)(blockIdx.x + 1) * NW * 32, R) - 1;
+    const int g_last = min((qb0 + NW) * 32, R) - 1;
     const int n_kb = (limit_of_row(g_last) + 31) >> 5;
 
     const bf16_t *kh = kc + (size_t)item * D * pos_stride;
@@ -402,9 +421,9 @@ attn_prefill_loader_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
 template <int NW>
 int launch_loader(bf16_t *out, const bf16_t *q, const bf16_t *kc, const bf16_t *vc, const RowsArgs &ra, const KvView &kv,
                   int H, int q_blocks, int n_items, int out_kb_rows, hipStream_t st) {
-    dim3 grid((q_blocks + NW - 1) / NW, n_items);
-    attn_prefill_loader_kernel<NW><<<grid, (NW + 1) * 64, 0, st>>>(out, q, kc, vc, ra.R, ra.pos0, ra.full_from, kv.n_heads,
-                                                                  kv.pos_stride, H, q_blocks, out_kb_rows);
+    const int n_groups = (q_blocks + NW - 1) / NW;
+    attn_prefill_loader_kernel<NW><<<dim3(n_groups * n_items), (NW + 1) * 64, 0, st>>>(
+        out, q, kc, vc, ra.R, ra.pos0, ra.full_from, kv.n_heads, kv.pos_stride, H, q_blocks, out_kb_rows, n_items, n_groups);
     return vla_check_launch("attn_prefill");
 }
 

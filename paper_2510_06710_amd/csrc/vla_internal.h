@@ -117,10 +117,9 @@ __device__ __forceinline__ float vla_silu_mul(float gate, float up) {
 // so that everything derived from them (tile base addresses) stays scalar.
 __device__ __forceinline__ void vla_tile_of_block(int pid, int tiles_m, int tiles_n, int &tm, int &tn, int GROUP = 4) {
     int total = tiles_m * tiles_n;
-    int per_xcd = (total + 7) / 8;
-    int xcd = pid % 8, local = pid / 8;
-    int lin = xcd * per_xcd + local;
-    if (per_xcd * 8 != total) lin = pid;     // ragged tile counts: keep the plain order
+    int q = total >> 3, r = total & 7;       // XCDs below r hold q + 1 ids, the others q
+    int xcd = pid & 7, local = pid >> 3;
+    int lin = xcd * q + min(xcd, r) + local;
     // GROUP = 4: measured best of 1, 2, 4, 6, 8, 16, 32 on the 7B shapes (the QKV projection passes 2)
     int panel = lin / (GROUP * tiles_n);
     int first_m = panel * GROUP;

@@ -214,57 +214,52 @@ __global__ void __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per
 attn_prefill_loader_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
                                                                      const bf16_t *vc, int R, int pos0, int full_from,
                                                                      int n_heads, int pos_stride, int H, int q_blocks,
-                                                                     int out_kb_rows, int n_items, int n_groups) {
+                                                                     int out_kb_rows, int n_items, int n_groups, int n_wgs) {
     constexpr int D = 128, KS = D / 16, DB = D / 32;
     constexpr int K_UNITS = 8;                         // 16-byte units of a K block per lane of the loading wave
     constexpr int V_UNITS = 4;                         // (key pair, 8 dims) units of a V block per lane
     __shared__ __attribute__((aligned(16))) unsigned char lds[2 * ATT_STAGE];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // Workgroup ids are dealt round-robin to the eight XCDs.  With an odd number of groups per (sequence, head) item
-    // the plain order (group fastest) gives every XCD the same mix of long and short groups.  With an even number,
-    // group g of every item would land on the same few XCDs (four groups: XCDs g and g + 4 only), so there the ids
-    // of one XCD, taken in order, walk (item, group) with the group fastest.
-    int item, grp;                                     // item = sequence * n_heads + head
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: the two roles below are exclusive code paths
+    // A (sequence, head) item has n_groups groups of NW query blocks, counted from the last block down: group 0 sees
+    // the most key blocks, and when the block count is not a multiple of NW the last group is a ragged one that holds
+    // the first blocks, which see the fewest keys.  One workgroup per group, except that the ragged group rides
+    // along with the full group before it (n_wgs = n_groups - 1; the two are taken one after the other): a
+    // workgroup of its own that lasts one or two key blocks costs about as much slot time in launching as in work
+    // (at 294 rows = 10 blocks: 0.91 -> 0.72 ms per launch of 8192 items; pairing long with short groups throughout
+    // was also tried and is slower where nothing is ragged, 0.65 against 0.58 ms at 288 rows).
+    // Workgroup ids are dealt round-robin to the eight XCDs.  With an odd n_wgs the plain order (workgroup of the
+    // item fastest) gives every XCD the same mix; with an even one, workgroup j of every item would land on the
+    // same few XCDs, so there the ids of one XCD, taken in order, walk (item, j) with j fastest.
+    int item, wg_j;                                    // item = sequence * n_heads + head
     {
         const int w = blockIdx.x;
-        const int remapped = (n_groups & 1) ? 0 : (n_items & ~7) * n_groups;
+        const int remapped = (n_wgs & 1) ? 0 : (n_items & ~7) * n_wgs;
         if (w < remapped) {
-            const int local = w >> 3, il = local / n_groups;
+            const int local = w >> 3, il = local / n_wgs;
             item = il * 8 + (w & 7);
-            grp = local - il * n_groups;
+            wg_j = local - il * n_wgs;
         } else {
-            item = w / n_groups;
-            grp = w - item * n_groups;
+            item = w / n_wgs;
+            wg_j = w - item * n_wgs;
         }
     }
+    const int second_grp = (n_wgs != n_groups && wg_j == n_wgs - 1) ? n_groups - 1 : -1;
     const int s = item / n_heads, h = item - s * n_heads;
     const int nk = pos0 + R;
     const int col = lane & 31, hh = lane >> 5;
-    // Query blocks are grouped from the last one down: a ragged group then holds the first blocks, which see the
-    // fewest keys, and the groups with the most key blocks are dispatched first.
-    const int qb0 = q_blocks - (grp + 1) * NW;
-    const int qb = max(qb0 + wave, 0);
-    const bool active = qb0 + wave >= 0 && wave < NW;
-    const int r = min(qb * 32 + col, R - 1);
-    const int qpos = pos0 + r;
-    const int limit = (qpos >= full_from) ? nk : qpos + 1;          // keys [0, limit) are visible to this lane
-    // visible keys grow with the row, so the last row of the wave / of the workgroup gives the block counts
-    auto limit_of_row = [&](int row) { int p = pos0 + row; return (p >= full_from) ? nk : p + 1; };
-    const int w_last = min(qb * 32 + 31, R - 1), w_first = min(qb * 32, R - 1);
-    const int my_nkb = active ? (limit_of_row(w_last) + 31) >> 5 : 0;
-    const int my_full_kb = limit_of_row(w_first) >> 5;              // blocks below this need no mask
-    const int g_last = min((qb0 + NW) * 32, R) - 1;
-    const int n_kb = (limit_of_row(g_last) + 31) >> 5;
-
     const bf16_t *kh = kc + (size_t)item * D * pos_stride;
     const bf16_t *vh = vc + (size_t)item * pos_stride * D;
-
-    bf16x8_t qf[KS];
-    if (wave < NW) {
-        const bf16_t *qrow = qbuf + ((size_t)s * R + r) * H + (size_t)h * D;
-#pragma unroll
-        for (int kk = 0; kk < KS; kk++) qf[kk] = *(const bf16x8_t *)(qrow + kk * 16 + hh * 8);
-    }
+    // visible keys grow with the row, so the last row of a wave / of a group gives the block counts
+    auto limit_of_row = [&](int row) { int p = pos0 + row; return (p >= full_from) ? nk : p + 1; };
+    // key blocks that group `grp` walks (its last query row sees the most keys)
+    auto key_blocks_of_group = [&](int grp) {
+        const int g_last = min((q_blocks - grp * NW) * 32, R) - 1;
+        return (limit_of_row(g_last) + 31) >> 5;
+    };
+    // After the last key block of a group every wave has passed the barrier that follows it, so the next group's
+    // block 0 can go into stage 0 at once.  The role test is the outermost branch: what either role keeps across
+    // its groups (addresses, masks) stays in that role's registers.
 
     // ---- the loading wave: global -> registers -> LDS, two key blocks in flight ------------------------------
     if (wave == NW) {
@@ -309,112 +304,143 @@ attn_prefill_loader_kernel(bf16_t *out, const bf16_t *qbuf, const bf16_t *kc,
         };
         using SA = std::integral_constant<int, 0>;
         using SB = std::integral_constant<int, 1>;
-        fetch(SA{}, 0);
-        if (n_kb > 1) fetch(SB{}, 1);
-        stash(SA{}, 0);
-        __syncthreads();                                   // block 0 is in stage 0
-        // iteration kb: the other waves work on stage kb % 2; this one fetches block kb + 2 into the register set
-        // that block kb held and moves block kb + 1 from the other set into stage (kb + 1) % 2
-        for (int kb = 0; kb < n_kb; kb += 2) {
-            if (kb + 2 < n_kb) fetch(SA{}, kb + 2);
-            if (kb + 1 < n_kb) stash(SB{}, (kb + 1) & 1);
-            __syncthreads();
-            if (kb + 1 >= n_kb) break;
-            if (kb + 3 < n_kb) fetch(SB{}, kb + 3);
-            if (kb + 2 < n_kb) stash(SA{}, kb & 1);
-            __syncthreads();
+        for (int part = 0; part < 2; part++) {
+            const int grp = part ? second_grp : wg_j;
+            if (grp < 0) break;
+            const int n_kb = key_blocks_of_group(grp);
+            // The first two blocks have the same addresses for both groups.  Hiding that from the compiler keeps it
+            // from holding those addresses in registers across the whole loop (they would spill).
+            int kb0 = 0;
+            asm volatile("" : "+s"(kb0));
+            fetch(SA{}, kb0);
+            if (n_kb > 1) fetch(SB{}, kb0 + 1);
+            stash(SA{}, 0);
+            __syncthreads();                               // block 0 is in stage 0
+            // iteration kb: the other waves work on stage kb % 2; this one fetches block kb + 2 into the register
+            // set that block kb held and moves block kb + 1 from the other set into stage (kb + 1) % 2
+            for (int kb = 0; kb < n_kb; kb += 2) {
+                if (kb + 2 < n_kb) fetch(SA{}, kb + 2);
+                if (kb + 1 < n_kb) stash(SB{}, (kb + 1) & 1);
+                __syncthreads();
+                if (kb + 1 >= n_kb) break;
+                if (kb + 3 < n_kb) fetch(SB{}, kb + 3);
+                if (kb + 2 < n_kb) stash(SA{}, kb & 1);
+                __syncthreads();
+            }
         }
         return;
     }
 
-    f32x16_t o_acc[DB];
-#pragma unroll
-    for (int b = 0; b < DB; b++)
-#pragma unroll
-        for (int i = 0; i < 16; i++) o_acc[b][i] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
-    const float c2 = 1.4426950408889634f / sqrtf((float)D);        // logits scale folded into the base-2 exponent
+    // ---- the query waves --------------------------------------------------------------------------------------
+    for (int part = 0; part < 2; part++) {
+        const int grp = part ? second_grp : wg_j;
+        if (grp < 0) break;
+        const int n_kb = key_blocks_of_group(grp);
+        const int qb0 = q_blocks - (grp + 1) * NW;
+        const int qb = max(qb0 + wave, 0);
+        const bool active = qb0 + wave >= 0;
+        const int r = min(qb * 32 + col, R - 1);
+        const int qpos = pos0 + r;
+        const int limit = (qpos >= full_from) ? nk : qpos + 1;      // keys [0, limit) are visible to this lane
+        const int w_last = min(qb * 32 + 31, R - 1), w_first = min(qb * 32, R - 1);
+        const int my_nkb = active ? (limit_of_row(w_last) + 31) >> 5 : 0;
+        const int my_full_kb = limit_of_row(w_first) >> 5;          // blocks below this need no mask
 
-    __syncthreads();                                       // block 0 is in stage 0
-    // An empty statement that reads the query fragments: their loads are waited for here, once.  Otherwise the
-    // waits the compiler places in the loop must allow for a fragment still in flight on entry, and on every
-    // later pass those same waits drain the prefetch of the next key block.
+        bf16x8_t qf[KS];
+        {
+            const bf16_t *qrow = qbuf + ((size_t)s * R + r) * H + (size_t)h * D;
 #pragma unroll
-    for (int kk = 0; kk < KS; kk++) asm volatile("" ::"v"(qf[kk]));
-    for (int kb = 0; kb < n_kb; kb++) {
-        if (kb < my_nkb) {
-            const unsigned char *k_lds = lds + (kb & 1) * ATT_STAGE, *vt_lds = k_lds + ATT_K_BYTES;
-            // ---- S^T block: rows = keys kb*32 .. +31, columns = the wave's 32 queries -----------------------
-            f32x16_t st;
-#pragma unroll
-            for (int i = 0; i < 16; i++) st[i] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < KS; kk++) {
-                bf16x8_t kf = *(const bf16x8_t *)(k_lds + ((kk * 2 + hh) * 32 + col) * 16);
-                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st, 0, 0, 0);
-            }
-            // register i of this lane is key kb*32 + 8*(i/4) + 4*hh + i%4 for query `col`
-            if (kb >= my_full_kb) {
-#pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    int key = kb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
-                    st[i] = (key < limit) ? st[i] : -INFINITY;
-                }
-            }
-            float bmax = st[0];
-#pragma unroll
-            for (int i = 1; i < 16; i++) bmax = fmaxf(bmax, st[i]);
-            bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
-            const float m_new = fmaxf(m_run, bmax);    // every query sees key 0: finite from block 0 on
-            const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-            const float mc = m_new * c2;
-            float psum = 0.f;
-            bf16x8_t pf[2], pl[2];                      // p = bf16 head + bf16 tail: ~16 significant bits into P.V
-#pragma unroll
-            for (int i = 0; i < 16; i++) {
-                float p = __builtin_amdgcn_exp2f(fmaf(st[i], c2, -mc));
-                psum += p;
-                bf16_t ph = (bf16_t)p;
-                pf[i >> 3][i & 7] = ph;
-                pl[i >> 3][i & 7] = (bf16_t)(p - (float)ph);
-            }
-            psum += __shfl_xor(psum, 32, 64);
-            l_run = l_run * corr + psum;
-            m_run = m_new;
-            if (!__all(corr == 1.0f)) {
-#pragma unroll
-                for (int b = 0; b < DB; b++)
-#pragma unroll
-                    for (int i = 0; i < 16; i++) o_acc[b][i] *= corr;
-            }
-            // ---- O^T += V^T . P^T: k slot (hh, e) of product u is key kb*32 + 16u + 8*(e/4) + 4hh + e%4 ------
-#pragma unroll
-            for (int u = 0; u < 2; u++) {
-#pragma unroll
-                for (int b = 0; b < DB; b++) {
-                    bf16x8_t vf = *(const bf16x8_t *)(vt_lds + ((2 * u + hh) * ATT_VT_GROUP + (b * 32 + col) + ((b * 32 + col) >> 3)) * 16);
-                    o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], o_acc[b], 0, 0, 0);
-                    o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pl[u], o_acc[b], 0, 0, 0);
-                }
-            }
+            for (int kk = 0; kk < KS; kk++) qf[kk] = *(const bf16x8_t *)(qrow + kk * 16 + hh * 8);
         }
-        __syncthreads();
-    }
-    // ---- store: lane holds query `col`, dims b*32 + 8*(i/4) + 4*hh + i%4 -------------------------------------
-    if (active && qb * 32 + col < R) {
-        const float inv = 1.0f / l_run;
-        const size_t m = (size_t)s * R + r;
-        bf16_t *orow = out_kb_rows ? out + ((size_t)h * (D / 32) * out_kb_rows + m) * 32 : out + m * H + (size_t)h * D;
-        const size_t bstride = out_kb_rows ? (size_t)out_kb_rows * 32 : 32;
+        f32x16_t o_acc[DB];
 #pragma unroll
         for (int b = 0; b < DB; b++)
 #pragma unroll
-            for (int g = 0; g < 4; g++) {
-                bf16x4_t o;
+            for (int i = 0; i < 16; i++) o_acc[b][i] = 0.f;
+        float m_run = -INFINITY, l_run = 0.f;
+        const float c2 = 1.4426950408889634f / sqrtf((float)D);    // logits scale folded into the base-2 exponent
+
+        __syncthreads();                                   // block 0 is in stage 0
+        // An empty statement that reads the query fragments: their loads are waited for here, once.  Otherwise the
+        // waits the compiler places in the loop must allow for a fragment still in flight on entry, and on every
+        // later pass those same waits drain the prefetch of the next key block.
 #pragma unroll
-                for (int e = 0; e < 4; e++) o[e] = (bf16_t)(o_acc[b][g * 4 + e] * inv);
-                *(bf16x4_t *)(orow + b * bstride + g * 8 + 4 * hh) = o;
+        for (int kk = 0; kk < KS; kk++) asm volatile("" ::"v"(qf[kk]));
+        for (int kb = 0; kb < n_kb; kb++) {
+            if (kb < my_nkb) {
+                const unsigned char *k_lds = lds + (kb & 1) * ATT_STAGE, *vt_lds = k_lds + ATT_K_BYTES;
+                // ---- S^T block: rows = keys kb*32 .. +31, columns = the wave's 32 queries -------------------
+                f32x16_t st;
+#pragma unroll
+                for (int i = 0; i < 16; i++) st[i] = 0.f;
+#pragma unroll
+                for (int kk = 0; kk < KS; kk++) {
+                    bf16x8_t kf = *(const bf16x8_t *)(k_lds + ((kk * 2 + hh) * 32 + col) * 16);
+                    st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st, 0, 0, 0);
+                }
+                // register i of this lane is key kb*32 + 8*(i/4) + 4*hh + i%4 for query `col`
+                if (kb >= my_full_kb) {
+#pragma unroll
+                    for (int i = 0; i < 16; i++) {
+                        int key = kb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
+                        st[i] = (key < limit) ? st[i] : -INFINITY;
+                    }
+                }
+                float bmax = st[0];
+#pragma unroll
+                for (int i = 1; i < 16; i++) bmax = fmaxf(bmax, st[i]);
+                bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+                const float m_new = fmaxf(m_run, bmax);    // every query sees key 0: finite from block 0 on
+                const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+                const float mc = m_new * c2;
+                float psum = 0.f;
+                bf16x8_t pf[2], pl[2];                      // p = bf16 head + bf16 tail: ~16 significant bits into P.V
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    float p = __builtin_amdgcn_exp2f(fmaf(st[i], c2, -mc));
+                    psum += p;
+                    bf16_t ph = (bf16_t)p;
+                    pf[i >> 3][i & 7] = ph;
+                    pl[i >> 3][i & 7] = (bf16_t)(p - (float)ph);
+                }
+                psum += __shfl_xor(psum, 32, 64);
+                l_run = l_run * corr + psum;
+                m_run = m_new;
+                if (!__all(corr == 1.0f)) {
+#pragma unroll
+                    for (int b = 0; b < DB; b++)
+#pragma unroll
+                        for (int i = 0; i < 16; i++) o_acc[b][i] *= corr;
+                }
+                // ---- O^T += V^T . P^T: k slot (hh, e) of product u is key kb*32 + 16u + 8*(e/4) + 4hh + e%4 --
+#pragma unroll
+                for (int u = 0; u < 2; u++) {
+#pragma unroll
+                    for (int b = 0; b < DB; b++) {
+                        bf16x8_t vf = *(const bf16x8_t *)(vt_lds + ((2 * u + hh) * ATT_VT_GROUP + (b * 32 + col) + ((b * 32 + col) >> 3)) * 16);
+                        o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], o_acc[b], 0, 0, 0);
+                        o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pl[u], o_acc[b], 0, 0, 0);
+                    }
+                }
             }
+            __syncthreads();
+        }
+        // ---- store: lane holds query `col`, dims b*32 + 8*(i/4) + 4*hh + i%4 ---------------------------------
+        if (active && qb * 32 + col < R) {
+            const float inv = 1.0f / l_run;
+            const size_t m = (size_t)s * R + r;
+            bf16_t *orow = out_kb_rows ? out + ((size_t)h * (D / 32) * out_kb_rows + m) * 32 : out + m * H + (size_t)h * D;
+            const size_t bstride = out_kb_rows ? (size_t)out_kb_rows * 32 : 32;
+#pragma unroll
+            for (int b = 0; b < DB; b++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    bf16x4_t o;
+#pragma unroll
+                    for (int e = 0; e < 4; e++) o[e] = (bf16_t)(o_acc[b][g * 4 + e] * inv);
+                    *(bf16x4_t *)(orow + b * bstride + g * 8 + 4 * hh) = o;
+                }
+        }
     }
 }
 
@@ -422,8 +448,14 @@ template <int NW>
 int launch_loader(bf16_t *out, const bf16_t *q, const bf16_t *kc, const bf16_t *vc, const RowsArgs &ra, const KvView &kv,
                   int H, int q_blocks, int n_items, int out_kb_rows, hipStream_t st) {
     const int n_groups = (q_blocks + NW - 1) / NW;
-    attn_prefill_loader_kernel<NW><<<dim3(n_groups * n_items), (NW + 1) * 64, 0, st>>>(
-        out, q, kc, vc, ra.R, ra.pos0, ra.full_from, kv.n_heads, kv.pos_stride, H, q_blocks, out_kb_rows, n_items, n_groups);
+    // a ragged last group shares the workgroup of the group before it; VLA_ATTN_PAIR = 0 gives it its own (read
+    // at every call: the tests switch it)
+    const char *pe = getenv("VLA_ATTN_PAIR");
+    const bool merge = n_groups > 1 && q_blocks % NW != 0 && !(pe && atoi(pe) == 0);
+    const int n_wgs = merge ? n_groups - 1 : n_groups;
+    attn_prefill_loader_kernel<NW><<<dim3(n_wgs * n_items), (NW + 1) * 64, 0, st>>>(
+        out, q, kc, vc, ra.R, ra.pos0, ra.full_from, kv.n_heads, kv.pos_stride, H, q_blocks, out_kb_rows, n_items, n_groups,
+        n_wgs);
     return vla_check_launch("attn_prefill");
 }
 

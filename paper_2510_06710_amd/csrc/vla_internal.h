@@ -111,21 +111,42 @@ __device__ __forceinline__ float vla_silu_mul(float gate, float up) {
 }
 
 // Maps a linear work-item id of the large-tile GEMMs to an output tile.  Workgroups are dealt round-robin to
-// the eight XCDs, each with its own L2: ids of one XCD are made contiguous, then walked in column panels of
-// `GROUP` tile rows so that the ~32 tiles resident on an XCD (4 x 8) share activation and weight rows.  The
-// divisions run on the vector unit; the results are the same in every lane and go back to scalar registers
-// so that everything derived from them (tile base addresses) stays scalar.
+// the eight XCDs, each with its own L2.  The ids of XCD y, taken in order, walk the tile rows y, y + 8, y + 16, ...
+// in column panels of `GROUP` of those rows, so that the ~32 tiles resident on an XCD (4 x 8) share activation and
+// weight rows in its L2 -- and all eight XCDs start at tile column 0 and move through the columns together, so
+// that a weight panel that one XCD pulls from memory is found in the memory-side cache by the other seven
+// (contiguous ranges of rows per XCD do the same only when the tile count per XCD is a whole number of panels).
+// The row sets differ by one row at most while the ids are dealt evenly: an XCD that is through with its own rows
+// takes, at the end, the tiles that the other XCDs' shares of ids do not reach.
+// The arithmetic is the same in every lane; the results go back to scalar registers so that everything derived
+// from them (tile base addresses) stays scalar.
 __device__ __forceinline__ void vla_tile_of_block(int pid, int tiles_m, int tiles_n, int &tm, int &tn, int GROUP = 4) {
-    int total = tiles_m * tiles_n;
-    int q = total >> 3, r = total & 7;       // XCDs below r hold q + 1 ids, the others q
-    int xcd = pid & 7, local = pid >> 3;
-    int lin = xcd * q + min(xcd, r) + local;
+    const int total = tiles_m * tiles_n;
+    const int q = total >> 3, r = total & 7;                 // XCDs below r are dealt q + 1 ids, the others q
+    const int rows_lo = tiles_m >> 3, extra = tiles_m & 7;   // XCDs below `extra` own rows_lo + 1 tile rows
+    auto ids_of = [&](int z) { return q + (z < r ? 1 : 0); };
+    auto tiles_of = [&](int z) { return (rows_lo + (z < extra ? 1 : 0)) * tiles_n; };
+    const int xcd = pid & 7, local = pid >> 3;
+    int y = xcd, l = local;                                  // tile l of XCD y's own rows
+    if (local >= tiles_of(xcd)) {
+        int e = local - tiles_of(xcd);                       // index into the tiles left over, pooled in XCD order
+        for (int z = 0; z < 8; z++)
+            if (z < xcd) e += max(ids_of(z) - tiles_of(z), 0);
+        for (int z = 0; z < 8; z++) {
+            const int left = tiles_of(z) - ids_of(z);
+            if (left > 0) {
+                if (e < left) { y = z; l = ids_of(z) + e; break; }
+                e -= left;
+            }
+        }
+    }
+    const int rows_y = rows_lo + (y < extra ? 1 : 0);
     // GROUP = 4: measured best of 1, 2, 4, 6, 8, 16, 32 on the 7B shapes (the QKV projection passes 2)
-    int panel = lin / (GROUP * tiles_n);
-    int first_m = panel * GROUP;
-    int rows = min(GROUP, tiles_m - first_m);
-    int in_panel = lin - panel * GROUP * tiles_n;
-    tm = __builtin_amdgcn_readfirstlane(first_m + in_panel % rows);
+    const int panel = l / (GROUP * tiles_n);
+    const int first = panel * GROUP;
+    const int rows = min(GROUP, rows_y - first);
+    const int in_panel = l - panel * GROUP * tiles_n;
+    tm = __builtin_amdgcn_readfirstlane(y + 8 * (first + in_panel % rows));
     tn = __builtin_amdgcn_readfirstlane(in_panel / rows);
 }
 

@@ -139,7 +139,11 @@ size_t vla_workspace_bytes(const vla_config *cfg, int entry, int B, int S, int A
  *   patch     DEVICE dtype [B, P, hidden] (P may be 0)     ids DEVICE int32 [B, T] in [0, vocab)
  *   h_last    DEVICE fp32 [B, hidden] out: final-norm output of the last prefix row
  *   value     DEVICE fp32 [B, value_dim] out or NULL: value_w . h_last + bias (section IV-C.2)
- * Requires P + T >= 1, B <= max_batch, P + T <= max_seq. */
+ * Requires P + T >= 1, B <= max_batch, P + T <= max_seq, and B * (P + T) rows within what one
+ * pass can hold: the residual stream [rows, hidden] fp32 and the widest activation
+ * [rows + 256 + pad, max(hidden, ffn)] in the storage dtype each below 2 GiB (32-bit byte
+ * offsets in the kernels; 97,254 rows at the 7B shape in bf16).  Beyond that VLA_ESHAPE: split
+ * the batch over several calls (each with its own kv). */
 int vla_prefill(vla_model *model, void *kv, void *ws, size_t ws_bytes,
                 const void *patch, const int32_t *ids, int B, int P, int T,
                 float *h_last, float *value, void *stream);
@@ -161,7 +165,8 @@ int vla_prefill(vla_model *model, void *kv, void *ws, size_t ws_bytes,
  *   gumbel     DEVICE fp32 [B, A, 256] or NULL
  *   bins       DEVICE int32 [B, A] out                     logp, entropy DEVICE fp32 [B, A] out
  *   logits     DEVICE fp32 [B, A, 256] out or NULL: untempered z, for parity checks
- * Requires A >= 1 and S + A - 1 <= max_seq (mode 0), S + A <= max_seq (mode 1). */
+ * Requires A >= 1 and S + A - 1 <= max_seq (mode 0), S + A <= max_seq (mode 1); mode 1 also
+ * B * A rows within one pass (see vla_prefill). */
 int vla_decode_actions(vla_model *model, void *kv, void *ws, size_t ws_bytes,
                        const float *h_last, int B, int S, int A, int mode,
                        const void *slot_embed, float temperature, const float *gumbel,
@@ -178,8 +183,9 @@ int vla_decode_actions(vla_model *model, void *kv, void *ws, size_t ws_bytes,
  *   logp   DEVICE fp32 [N, A] out: log-prob of the stored bin at the given temperature
  *   entropy DEVICE fp32 [N, A] out      value DEVICE fp32 [N, value_dim] out or NULL (last prefix row)
  *   logits DEVICE fp32 [N, A, 256] out or NULL
- * N may exceed max_batch: rollouts are processed in internal micro-batches and the result does
- * not depend on the split. */
+ * N may exceed max_batch: rollouts are processed in internal micro-batches of max_batch rollouts
+ * (fewer if that many rows do not fit one pass, see vla_prefill) and the result does not depend
+ * on the split. */
 int vla_logprob_recompute(vla_model *model, void *ws, size_t ws_bytes,
                           const void *patch, const int32_t *ids, const int32_t *bins,
                           int N, int P, int T, int A, int mode, const void *slot_embed,

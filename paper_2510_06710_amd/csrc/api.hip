@@ -146,7 +146,35 @@ static Workspace plan_workspace(const vla_config &c, char *base, int n_seq, int 
     return w;
 }
 
-static int recompute_micro_batch(const vla_config &c, int N) { return N < c.max_batch ? N : c.max_batch; }
+// The kernels index a pass's activation buffers with 32-bit byte offsets: the residual stream ([rows, H] fp32) and
+// the widest activation operand ([rows rounded up to tiles + pad, max(H, F)] in the storage dtype) must each stay
+// below 2 GiB.  7B shape, bf16: 97,254 rows per pass (the benchmark's largest pass has 75,264).
+static long max_rows_per_pass(const vla_config &c) {
+    const long lim = 0x7fffffffL;
+    long wide = c.ffn > c.hidden ? c.ffn : c.hidden;
+    long by_x = lim / ((long)c.hidden * 4);
+    long by_act = lim / (wide * (long)elt_size(c)) - 256 - VLA_KB_PAD_ROWS;
+    return by_x < by_act ? by_x : by_act;
+}
+
+static int check_rows_per_pass(const vla_config &c, long n_seq, long rows_per_seq) {
+    long lim = max_rows_per_pass(c);
+    if (n_seq * rows_per_seq > lim) {
+        vla_set_error("%ld sequences x %ld rows exceed the %ld rows one pass can hold at this shape: split the batch",
+                      n_seq, rows_per_seq, lim);
+        return VLA_ESHAPE;
+    }
+    return VLA_OK;
+}
+
+// rollouts per pass of the recompute: the capacity, cut down to what one pass can hold (at least 1).  R is S + A,
+// the rows of the longer of the two modes, for either mode: the size query does not know the mode.
+static int recompute_micro_batch(const vla_config &c, int N, int R) {
+    long mb = N < c.max_batch ? N : c.max_batch;
+    long fit = max_rows_per_pass(c) / (R > 0 ? R : 1);
+    if (mb > fit) mb = fit;
+    return mb > 0 ? (int)mb : 1;
+}
 
 // ------------------------------------------------------------------------------------------ forward
 // Triage knob: VLA_FORCE_GENERIC is a bit mask that sends a step to the shape-generic kernel even
@@ -420,7 +448,7 @@ static int recompute_impl(vla_model *m, void *wsbuf, const void *patch, const in
     int S = P + T_, H = c.hidden, rc;
     int R = (mode == VLA_MODE_AR) ? S + A - 1 : S + A;
     int first = (mode == VLA_MODE_AR) ? S - 1 : S;          // row that predicts action token 1
-    int mb = recompute_micro_batch(c, N);
+    int mb = recompute_micro_batch(c, N, S + A);
     const T *head = (const T *)m->w.lm_head + (size_t)(c.vocab - VLA_N_BINS) * H;
     Workspace ws = plan_workspace(c, (char *)wsbuf, mb, R, R, mb * (A + 1), true);
     for (int n0 = 0; n0 < N; n0 += mb) {
@@ -542,17 +570,19 @@ size_t vla_workspace_bytes(const vla_config *cfg, int entry, int B, int S, int A
     switch (entry) {
         case VLA_ENTRY_PREFILL:
             if (B > cfg->max_batch || S > cfg->max_seq) { vla_set_error("B or S exceeds capacity"); return 0; }
+            if (check_rows_per_pass(*cfg, B, S)) return 0;
             return plan_workspace(*cfg, nullptr, B, S, S, 0, false).total;
         case VLA_ENTRY_DECODE: {
             if (B > cfg->max_batch || S + a > cfg->max_seq + 1) { vla_set_error("B or S + A exceeds capacity"); return 0; }
+            if (check_rows_per_pass(*cfg, B, a)) return 0;
             size_t ar = plan_workspace(*cfg, nullptr, B, 1, S + a, B, false).total;
             size_t ch = (S + a <= cfg->max_seq) ? plan_workspace(*cfg, nullptr, B, a, S + a, B * a, false).total : 0;
             return ar > ch ? ar : ch;
         }
         case VLA_ENTRY_RECOMPUTE: {
             if (S + a > cfg->max_seq + 1) { vla_set_error("S + A exceeds capacity"); return 0; }
-            int mb = recompute_micro_batch(*cfg, B);
             int R = (S + a <= cfg->max_seq) ? S + a : S + a - 1;
+            int mb = recompute_micro_batch(*cfg, B, S + a);
             return plan_workspace(*cfg, nullptr, mb, R, R, mb * (a + 1), true).total;
         }
         default:
@@ -572,6 +602,7 @@ int vla_prefill(vla_model *m, void *kv, void *ws, size_t ws_bytes, const void *p
         vla_set_error("B %d / S %d exceed capacity %d / %d", B, P + T, c.max_batch, c.max_seq);
         return VLA_ESHAPE;
     }
+    if (int rc = check_rows_per_pass(c, B, P + T)) return rc;
     size_t need = plan_workspace(c, nullptr, B, P + T, P + T, 0, false).total;
     if (ws_bytes < need) { vla_set_error("workspace %zu bytes, need %zu", ws_bytes, need); return VLA_EWORKSPACE; }
     hipStream_t st = (hipStream_t)stream;
@@ -594,6 +625,7 @@ int vla_decode_actions(vla_model *m, void *kv, void *ws, size_t ws_bytes, const 
         vla_set_error("B %d / positions %d exceed capacity %d / %d", B, rows, c.max_batch, c.max_seq);
         return VLA_ESHAPE;
     }
+    if (int rc = check_rows_per_pass(c, B, mode == VLA_MODE_AR ? 1 : A)) return rc;
     size_t need = (mode == VLA_MODE_AR) ? plan_workspace(c, nullptr, B, 1, S + A, B, false).total
                                         : plan_workspace(c, nullptr, B, A, S + A, B * A, false).total;
     if (ws_bytes < need) { vla_set_error("workspace %zu bytes, need %zu", ws_bytes, need); return VLA_EWORKSPACE; }
@@ -616,7 +648,7 @@ int vla_logprob_recompute(vla_model *m, void *ws, size_t ws_bytes, const void *p
     const vla_config &c = m->cfg;
     int S = P + T, R = (mode == VLA_MODE_AR) ? S + A - 1 : S + A;
     if (R > c.max_seq) { vla_set_error("rows per rollout %d exceed max_seq %d", R, c.max_seq); return VLA_ESHAPE; }
-    int mb = recompute_micro_batch(c, N);
+    int mb = recompute_micro_batch(c, N, S + A);
     size_t need = plan_workspace(c, nullptr, mb, R, R, mb * (A + 1), true).total;
     if (ws_bytes < need) { vla_set_error("workspace %zu bytes, need %zu", ws_bytes, need); return VLA_EWORKSPACE; }
     hipStream_t st = (hipStream_t)stream;

@@ -493,15 +493,12 @@ int try_attention_prefill_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, i
     };
     if (kv.d == 128 && shared_keys_enabled()) {
         ProfScope ps("attn_prefill", 4.0 * kv.d * pair_count() * n_items, st);
-        // One wave per 32-query block, at most four waves per workgroup: three such workgroups fit a CU, each with
-        // its own key block in flight, which hides the memory latency that one large workgroup per CU (nine waves
-        // for 288 queries, every key block fetched once) exposes between its lockstep steps; measured 23.5 ms
-        // against 26.0 ms per 7B prefill step at 256 x 288 rows.
         // One wave per 32-query block, at most three of them plus the loading wave per workgroup: three such
-        // workgroups fit a CU (36 KB LDS, 158 registers), each with two key blocks in flight.  Larger workgroups
+        // workgroups fit a CU (35 KB LDS, 159 registers), each with two key blocks in flight.  Larger workgroups
         // fetch every key block fewer times but leave fewer independent workgroups per CU to cover the dependent
         // chain of a step (QK, softmax, PV); measured per 7B prefill step at 256 x 288 rows, with every wave also
-        // loading: nine waves 26.0 ms, five or six 36-37 ms, four 21.6 ms; three + loading wave 19.9 ms.
+        // loading: nine waves 26.0 ms, five or six 36-37 ms, four 21.6 ms; three + loading wave 19.9 ms (18.1 ms
+        // with the padded V^T staging layout).
         switch (q_blocks <= 2 ? q_blocks : 3) {
         case 1: rc = launch_loader<1>(out, q, kc, vc, ra, kv, H, q_blocks, n_items, out_kb_rows, st); break;
         case 2: rc = launch_loader<2>(out, q, kc, vc, ra, kv, H, q_blocks, n_items, out_kb_rows, st); break;

@@ -87,6 +87,16 @@ def test_size_queries():
     assert small < big == capped                 # micro-batched beyond max_batch
     with pytest.raises(vb.VlaError):
         vb.vla_kv_bytes(cfg, 257, 10)
+    # one pass holds at most 97,254 rows at this shape (activation buffers below 2 GiB)
+    wide = vb.make_config(vi.SHAPE_7B, 512, 296)
+    assert vb.vla_workspace_bytes(wide, vb.VLA_ENTRY_PREFILL, 330, 294, 7) > 0          # 97,020 rows
+    with pytest.raises(vb.VlaError, match="split the batch"):
+        vb.vla_workspace_bytes(wide, vb.VLA_ENTRY_PREFILL, 331, 294, 7)                  # 97,314 rows
+    # the recompute cuts its micro-batch to what fits instead: 329 rollouts of 295 rows (the longer of its two
+    # modes), not 512
+    assert (vb.vla_workspace_bytes(wide, vb.VLA_ENTRY_RECOMPUTE, 512, 288, 7)
+            == vb.vla_workspace_bytes(wide, vb.VLA_ENTRY_RECOMPUTE, 329, 288, 7)
+            > vb.vla_workspace_bytes(wide, vb.VLA_ENTRY_RECOMPUTE, 328, 288, 7))
     with pytest.raises(vb.VlaError):
         vb.vla_workspace_bytes(cfg, 9, 1, 1, 1)
 

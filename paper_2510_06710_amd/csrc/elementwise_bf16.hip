@@ -184,7 +184,11 @@ __global__ void __launch_bounds__(256) rmsnorm_bf16_kb_kernel(bf16_t *out, const
     __shared__ float red[4][4];
     __shared__ __attribute__((aligned(16))) bf16_t stage[4][1024 * V4];
     const int t = threadIdx.x;
-    const int m0 = blockIdx.x * 4;
+    // Rows from the last one down: the GEMM before this kernel wrote the residual stream in ascending tile rows and
+    // the GEMM after it starts at tile row 0, so the rows read first here and the rows that GEMM reads first are
+    // the ones most recently written, part of which the memory-side cache still holds (22.1 -> 21.4 ms per 7B
+    // prefill step at 256 x 288 rows).
+    const int m0 = (int)(gridDim.x - 1 - blockIdx.x) * 4;
     const f32x4_t *g = (const f32x4_t *)gain;
 #pragma unroll
     for (int rr = 0; rr < 4; rr++) {

@@ -126,6 +126,26 @@ def test_oft_chunk_sampled_envs_vs_golden(model7b, golden, golden_ops):
         print(f"[parity] cfg4 env {e} vs exact oracle: {st}", flush=True)
 
 
+def test_chunk_rollout_then_chunk_recompute_rho_one_at_7b(model7b):
+    """The parallel-chunk recompute (prefix and slot rows in one teacher-forced pass of 344 rows per environment:
+    eleven query blocks, so the prefill attention merges a ragged group into the workgroup before it) against the
+    chunk decode of the same model (slot rows at an offset against the cached prefix): rho = 1 for all 128 x 56
+    slots, the logits of every slot within the deep bf16 bound, values equal."""
+    wl = vi.WORKLOADS["cfg4_7b_oft_b128"]
+    model7b.wl = wl
+    model7b.slot = model7b.synth.slot_embed(wl.n_action)
+    out = model7b.rollout(sampled=False)
+    rc = model7b.recompute(out["bins"])
+    rho = np.exp(rc["logp"] - out["logp"])
+    err = np.max(np.abs(rc["logits"] - out["logits"]))
+    print(f"\n[parity] 7B chunk rho range {rho.min():.5f} .. {rho.max():.5f}, max logit difference {err:.4f}", flush=True)
+    assert rho.shape == (wl.batch, wl.n_action)
+    assert np.max(np.abs(rho - 1.0)) < TOL["bf16_deep"]["logp"]
+    assert err < TOL["bf16_deep"]["logits"]
+    assert np.max(np.abs(rc["value"] - out["value"])) < TOL["bf16_deep"]["value"]
+    assert np.max(np.abs(rc["ent"] - out["ent"])) < TOL["bf16_deep"]["ent"]
+
+
 def test_recompute_sampled_rollouts_vs_golden(model7b, golden, golden_ops):
     wl = vi.WORKLOADS["cfg5_7b_recompute_n512"]
     model7b.wl = wl

@@ -78,13 +78,14 @@ def test_aligned_bf16_chunk_and_recompute_fast_kernels():
 
 
 @pytest.mark.parametrize("prefix,slots,pairing", [(131, 70, None), (97, 33, None), (131, 70, "0"), (200, 9, None),
-                                                  (294, 5, None), (294, 5, "0"), (288, 7, None)])
+                                                  (294, 5, None), (294, 5, "0"), (288, 7, None), (49, 100, None)])
 def test_aligned_bf16_longer_prefix_several_query_groups(prefix, slots, pairing, monkeypatch):
     """Prefixes of more than 96 rows take several groups of three 32-query blocks of the prefill attention per
     (sequence, head), with a ragged last query block and a ragged last key block; the parallel chunk then runs
     the slot rows at position offset `prefix` against prefix + slots keys.  A ragged group of fewer than three
     blocks shares the workgroup of the group before it (5, 4, 7 and 10 blocks: 2, 2, 3 and 4 groups per item);
-    VLA_ATTN_PAIR = 0 gives it a workgroup of its own; 288 rows have no ragged group."""
+    VLA_ATTN_PAIR = 0 gives it a workgroup of its own; 288 rows have no ragged group; 100 slot rows after a prefix
+    of 49 are four blocks at a position offset, every key visible to every row."""
     if pairing is not None:
         monkeypatch.setenv("VLA_ATTN_PAIR", pairing)
     wl = vi.scaled(ALIGNED, batch=3, n_patches=prefix - 11, n_instr=11, n_action=slots, mode=1)

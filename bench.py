@@ -38,19 +38,32 @@ def profile_report(vb):
     return out
 
 
-def read_traffic(path, kernel):
-    """HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/*.txt, 'key: value')."""
+def read_traffic(path, kernel, source):
+    """HBM bytes per launch of `kernel`, measured in separate rocprofv3 --pmc runs (hardware counters cannot be
+    read inside a timed run) and kept in profiles/*.txt as 'key: value' lines.  The figure is only quoted while the
+    file names this kernel and carries the SHA-256 of the kernel's source file as it is in the tree now; after any
+    change to that source the traffic is reported as null until the counters have been collected again.
+    Returns (bytes or None, provenance dict)."""
+    import hashlib
+    prov = {"file": os.path.relpath(path, ROOT), "how": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, separate runs, "
+            "scaled by the same counters on a 1 GiB copy kernel", "kernel_source": os.path.relpath(source, ROOT)}
     try:
         vals = {}
         for line in open(path):
             if ":" in line and not line.startswith("#"):
                 k, v = line.split(":", 1)
                 vals[k.strip()] = v.strip()
-        if vals.get("kernel") != kernel:
-            return None
-        return float(vals["hbm_bytes_per_launch"])
-    except Exception:
-        return None
+        sha = hashlib.sha256(open(source, "rb").read()).hexdigest()
+        prov["source_sha256_in_tree"] = sha[:16]
+        prov["source_sha256_measured"] = vals.get("kernel_source_sha256", "")[:16]
+        prov["current"] = vals.get("kernel") == kernel and vals.get("kernel_source_sha256") == sha
+        if not prov["current"]:
+            return None, prov
+        return float(vals["hbm_bytes_per_launch"]), prov
+    except Exception as e:                      # missing or unreadable file: no figure
+        prov["current"] = False
+        prov["error"] = str(e)
+        return None, prov
 
 
 def cpu_baseline(wl, vi, sample_layers=8):
@@ -116,7 +129,7 @@ def bench_recompute(args, wl, torch, vi, vb, Rollout):
     vb.lib().vla_profile_enable(0)
     rows = S + A - 1 if wl.mode == 0 else S + A
     flops = N * rows * 2.0 * shape.layer_params * shape.n_layers
-    dom = prof.get("gemm_bf16_mfma<swiglu>")
+    dom = prof.get("gemm_bf16_dma<swiglu>")
     roofline = None
     if dom:
         ach = dom["work"] / (dom["ms"] * 1e-3) / 1e12
@@ -293,18 +306,20 @@ def main():
     vb.lib().vla_profile_enable(0)
 
     shape = wl.shape
-    dom = "gemm_bf16_mfma<swiglu>"          # gate/up projection: the largest share of the step
+    dom = "gemm_bf16_dma<swiglu>"           # gate/up projection: the largest share of the step
     roofline = None
     if dom in prof_prefill:
         r = prof_prefill[dom]
         achieved = r["work"] / (r["ms"] * 1e-3) / 1e12
+        traffic, traffic_source = read_traffic(os.path.join(ROOT, "profiles", "gemm_swiglu_cfg3_traffic.txt"),
+                                               "gemm_bf16_dma_kernel<2, true, true>",
+                                               os.path.join(ROOT, "paper_2510_06710_amd", "csrc", "gemm_dma.hip"))
         roofline = {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel<EPI_SWIGLU, k-blocked, unit barrier> (gate/up projection, prefill)",
                     "achieved": achieved, "peak": MI355X_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / MI355X_BF16_TFLOPS, "launches": r["count"],
                     "avg_launch_ms": r["ms"] / r["count"],
                     "flops_per_launch": r["work"] / r["count"],
-                    "traffic": read_traffic(os.path.join(ROOT, "profiles", "gemm_swiglu_cfg3_traffic.txt"),
-                                            "gemm_bf16_dma_kernel<2, true, true>")}
+                    "traffic": traffic if wl.name == "cfg3_7b_b256" else None, "traffic_source": traffic_source}
     # decode HBM accounting: weights once per forward + each environment's own K, V rows per forward
     kv_tok = 2 * shape.n_layers * shape.hidden * 2
     fwd = A - 1 if wl.mode == 0 else 1

@@ -255,8 +255,8 @@ int vla_logp_aggregate(const float *logp, size_t n_out, int inner, float *out, v
  * vla_pipeline_time -- k = 1, collocated mode: *out = m_chunks (t_gen + t_sim), the section's t_1.
  *   k = 2, hybrid mode with fine-grained pipelining: the environments are split in two sub-batches that
  *   take turns on the Generation and on the Simulator partition (times are then per sub-batch):
- *   *out = 2 m_chunks max(t_gen, t_sim) + min(t_gen, t_sim).  The section leaves t_2 as "estimated
- *   under pipelined execution"; this is the makespan of the schedule it describes.  Other k: VLA_EINVAL.
+ *   *out = 2 m_chunks max(t_gen, t_sim) + min(t_gen, t_sim).  The section gives no formula for
+ *   t_2, only that it is an estimate for pipelined execution; this is the makespan of the schedule it describes.  Other k: VLA_EINVAL.
  *
  * vla_profile_lookup -- profile[i] is a component's measured time at batch 2^i, i < n_prof (the
  *   section profiles batch sizes 2^0 ... n_S); other batches are interpolated linearly between the two

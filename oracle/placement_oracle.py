@@ -3,8 +3,8 @@ the automatic placement search (section IV-A: collocated mode, hybrid mode with 
 pipelining, auto-placement algorithm).  Plain Python, written as an event-by-event simulation of the
 schedule the section describes; the library's closed forms are checked against it.
 
-Readings of the section (it gives t_1 in closed form and only says that t_2 is "estimated ... under
-pipelined execution"):
+Readings of the section (it gives t_1 in closed form and no formula for t_2, only that it is an estimate for
+pipelined execution):
   * one rollout epoch is m chunk steps; in each, Generation turns observations into actions (time
     t_G(b) for b environments per Generation GPU) and the Simulator turns actions into the next
     observations (t_S(b) per Simulator GPU); observations o_0 are available at time 0;

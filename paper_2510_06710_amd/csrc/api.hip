@@ -222,8 +222,11 @@ static int try_gemm_bf16_large(const GemmArgs &g, hipStream_t st) {
     return try_gemm_bf16_mfma(g, st);
 }
 
-// Kernel choice depends on the storage type and on whether the forward has one row per sequence
-// (decode) -- never on M itself, so a row's result is the same whatever batch it is part of.
+// Kernel choice depends on the storage type, on whether the forward has one row per sequence (decode) and, for
+// decode forwards, on the batch: up to 128 rows stream the weights through the skinny kernel, larger batches use
+// the split-K tile kernels.  The K ranges, and with them the order in which a row's products are summed, therefore
+// differ between batch sizes on either side of 128 (each configuration by itself is deterministic, and within one
+// call a row's result does not depend on the other rows).
 template <typename T>
 static int run_gemm(const vla_config &c, GemmArgs g, void *skinny_scratch, hipStream_t st) {
     if (c.dtype == VLA_DTYPE_BF16) {

@@ -559,8 +559,8 @@ int launch_plain(const DmaGemmParams &p, hipStream_t st) {
 template <int EPI, bool KB, bool UB = false>
 int launch(const DmaGemmParams &p, hipStream_t st) {
     const double flops = 2.0 * p.M * p.K * (EPI == EPI_SWIGLU ? 2.0 * p.N : (double)p.N);
-    ProfScope ps(EPI == EPI_SWIGLU ? "gemm_bf16_mfma<swiglu>" : EPI == EPI_RESIDUAL ? "gemm_bf16_mfma<residual>"
-                 : EPI == EPI_QKV_ROPE ? "gemm_bf16_mfma<qkv_rope>" : "gemm_bf16_mfma<store>", flops, st);
+    ProfScope ps(EPI == EPI_SWIGLU ? "gemm_bf16_dma<swiglu>" : EPI == EPI_RESIDUAL ? "gemm_bf16_dma<residual>"
+                 : EPI == EPI_QKV_ROPE ? "gemm_bf16_dma<qkv_rope>" : "gemm_bf16_dma<store>", flops, st);
     return launch_plain<EPI, KB, UB>(p, st);
 }
 

@@ -238,9 +238,10 @@ __global__ void __launch_bounds__(256) attention_generic_kernel(T *out, const T 
                                                                int pos_stride, int H) {
     extern __shared__ float smem[];
     int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int per_wave = pos_stride + d;
+    const int n_keys = pos0 + R;            // the most keys any row of this launch sees
+    int per_wave = n_keys + d;
     float *sc = smem + (size_t)wave * per_wave;
-    float *qs = sc + pos_stride;
+    float *qs = sc + n_keys;
     size_t item = (size_t)blockIdx.x * 4 + wave;
     size_t total = (size_t)n_seq * n_heads * R;
     if (item >= total) return;      // whole wave leaves together; no block-level barrier below
@@ -469,7 +470,21 @@ int launch_attention_generic(T *out, const T *q, const KvView &kv, int layer, co
     if (total == 0) return 0;
     const T *kc = (const T *)kv.k + (size_t)layer * kv.layer_elems;
     const T *vc = (const T *)kv.v + (size_t)layer * kv.layer_elems;
-    size_t lds = (size_t)4 * (kv.pos_stride + kv.d) * sizeof(float);
+    // scores of the visible keys + the query, per wave; above the 64 KB default the limit is raised once per
+    // instantiation (8192 keys at head_dim 256 need 132 KB of the CU's 160 KB)
+    size_t lds = (size_t)4 * (ra.pos0 + ra.R + kv.d) * sizeof(float);
+    if (lds > 64 * 1024) {
+        static bool raised = false;
+        if (lds > 160 * 1024) { vla_set_error("attention_generic: %d keys need %zu bytes of LDS", ra.pos0 + ra.R, lds); return VLA_ESHAPE; }
+        if (!raised) {
+            if (hipFuncSetAttribute((const void *)attention_generic_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    160 * 1024) != hipSuccess) {
+                vla_set_error("attention_generic: cannot raise the dynamic LDS limit");
+                return VLA_EHIP;
+            }
+            raised = true;
+        }
+    }
     attention_generic_kernel<T><<<(unsigned)((total + 3) / 4), 256, lds, st>>>(
         out, q, kc, vc, ra.n_seq, ra.R, ra.pos0, ra.full_from, kv.n_heads, kv.d, kv.pos_stride, H);
     return vla_check_launch("attention_generic");

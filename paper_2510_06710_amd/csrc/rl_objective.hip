@@ -37,14 +37,17 @@ __global__ void grpo_advantage_kernel(const float *R, int n_groups, int G, float
     const int g = blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= n_groups) return;
     const float *r = R + (size_t)g * G;
-    float mean = 0.f;
-    for (int i = 0; i < G; i++) mean += r[i];
+    float mean = 0.f, lo = r[0], hi = r[0];
+    for (int i = 0; i < G; i++) { mean += r[i]; lo = fminf(lo, r[i]); hi = fmaxf(hi, r[i]); }
     mean /= (float)G;
     float var = 0.f;
     for (int i = 0; i < G; i++) var += (r[i] - mean) * (r[i] - mean);
     const float sd = sqrtf(var / (float)G);
-    for (int i = 0; i < G; i++) adv[(size_t)g * G + i] = sd > 0.f ? (r[i] - mean) / sd : 0.f;
-    if (keep) keep[g] = sd > 0.f ? 1 : 0;
+    // a group of identical returns is recognised by max == min: the rounded mean of equal values that fp32 does
+    // not represent exactly (0.1 x G) can differ from them and leave a tiny non-zero deviation
+    const bool spread = hi > lo && sd > 0.f;
+    for (int i = 0; i < G; i++) adv[(size_t)g * G + i] = spread ? (r[i] - mean) / sd : 0.f;
+    if (keep) keep[g] = spread ? 1 : 0;
 }
 
 // One workgroup per trajectory: sums of the masked surrogate, the valid count and the clipped count.
@@ -57,13 +60,17 @@ __global__ void __launch_bounds__(256) objective_rows_kernel(const float *logp_n
     float s = 0.f, cnt = 0.f, clipped = 0.f;
     for (int t = threadIdx.x; t < T; t += 256) {
         const size_t o = (size_t)i * T + t;
-        const float m = (mask && !mask[o]) ? 0.f : 1.f;
+        // a masked step is never read: padding may hold anything (NaN, inf), and NaN * 0 would poison the sums
+        if (mask && !mask[o]) {
+            if (per_step) per_step[o] = 0.f;
+            continue;
+        }
         const float a = adv_per_step ? adv[o] : adv[i];
         const float rho = expf(logp_new[o] - logp_old[o]);
         const float u = rho * a, c = fminf(fmaxf(rho, lo), hi) * a;
-        const float v = fminf(u, c) * m;
+        const float v = fminf(u, c);
         if (per_step) per_step[o] = v;
-        s += v; cnt += m; clipped += (c < u) ? m : 0.f;
+        s += v; cnt += 1.f; clipped += (c < u) ? 1.f : 0.f;
     }
     s = block_sum_256(s, red);
     cnt = block_sum_256(cnt, red);
@@ -96,6 +103,17 @@ __global__ void logp_aggregate_kernel(const float *logp, size_t n_out, int inner
     float s = 0.f;
     for (int j = 0; j < inner; j++) s += logp[i * inner + j];
     out[i] = s;
+}
+
+int policy_objective_launch(const float *logp_new, const float *logp_old, const float *adv, int adv_per_step,
+                            const int32_t *mask, int n_traj, int T, float clip_low, float clip_high, int per_trajectory,
+                            float *rows, float *objective, float *per_step, float *clip_frac, hipStream_t st) {
+    objective_rows_kernel<<<n_traj, 256, 0, st>>>(logp_new, logp_old, adv, adv_per_step, mask, T, 1.0f - clip_low,
+                                                  1.0f + clip_high, per_step, rows);
+    int rc = vla_check_launch("policy_objective_rows");
+    if (rc) return rc;
+    objective_final_kernel<<<1, 256, 0, st>>>(rows, n_traj, per_trajectory, objective, clip_frac);
+    return vla_check_launch("policy_objective_final");
 }
 
 }  // namespace
@@ -135,13 +153,8 @@ int vla_policy_objective(const float *logp_new, const float *logp_old, const flo
         vla_set_error("policy_objective: workspace %zu bytes, need %zu", ws_bytes, vla_policy_objective_workspace_bytes(n_traj));
         return VLA_EWORKSPACE;
     }
-    hipStream_t st = (hipStream_t)stream;
-    objective_rows_kernel<<<n_traj, 256, 0, st>>>(logp_new, logp_old, adv, adv_per_step, mask, T, 1.0f - clip_low,
-                                                  1.0f + clip_high, per_step, (float *)ws);
-    int rc = vla_check_launch("policy_objective_rows");
-    if (rc) return rc;
-    objective_final_kernel<<<1, 256, 0, st>>>((const float *)ws, n_traj, per_trajectory, objective, clip_frac);
-    return vla_check_launch("policy_objective_final");
+    return policy_objective_launch(logp_new, logp_old, adv, adv_per_step, mask, n_traj, T, clip_low, clip_high,
+                                   per_trajectory, (float *)ws, objective, per_step, clip_frac, (hipStream_t)stream);
 }
 
 int vla_logp_aggregate(const float *logp, size_t n_out, int inner, float *out, void *stream) {

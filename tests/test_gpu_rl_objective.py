@@ -100,3 +100,44 @@ def test_recompute_feeds_the_objective_rho_one_on_policy():
                             None, frac)
     torch.cuda.synchronize()
     assert abs(obj.item() - A.mean()) < 1e-4 and frac.item() == 0.0
+
+
+def test_policy_objective_never_reads_masked_steps():
+    """Padding behind the valid-action mask (appendix I-C) may hold anything: NaN, inf, log-probs whose
+    difference overflows exp.  The result equals that of clean padding."""
+    rng = np.random.default_rng(11)
+    n, T = 64, 80
+    lo = -np.abs(rng.standard_normal((n, T))).astype(np.float32)
+    ln = (lo + 0.2 * rng.standard_normal((n, T))).astype(np.float32)
+    A = rng.standard_normal((n, T)).astype(np.float32)
+    m = (np.arange(T)[None, :] < rng.integers(0, T + 1, n)[:, None]).astype(np.int32)
+    ref_obj, ref_s, ref_frac = ro.opolicy_objective(ln, lo, A, m, np.float32(0.2), np.float32(0.28), True)
+    dirty_new, dirty_old, dirty_adv = ln.copy(), lo.copy(), A.copy()
+    pad = m == 0
+    dirty_new[pad] = np.where(rng.uniform(size=pad.sum()) < 0.5, np.nan, np.inf).astype(np.float32)
+    dirty_old[pad] = np.float32(-np.inf)
+    dirty_adv[pad] = np.float32(np.nan)
+    ws = torch.empty(vb.vla_policy_objective_workspace_bytes(n), dtype=torch.uint8, device=DEV)
+    obj, frac, per = torch.empty(1, device=DEV), torch.empty(1, device=DEV), torch.empty(n, T, device=DEV)
+    vb.vla_policy_objective(dev(dirty_new), dev(dirty_old), dev(dirty_adv), True, dev(m, torch.int32), n, T, 0.2, 0.28,
+                            True, ws, obj, per, frac)
+    torch.cuda.synchronize()
+    assert np.isfinite(per.cpu().numpy()).all()
+    assert np.max(np.abs(per.cpu().numpy() - ref_s)) < 2e-5 * max(1.0, np.abs(ref_s).max())
+    assert abs(obj.item() - ref_obj) < 2e-5 * max(1.0, abs(ref_obj))
+    assert abs(frac.item() - ref_frac) < 1e-5
+
+
+def test_grpo_groups_of_equal_inexact_returns_are_filtered():
+    """Eight equal returns of 0.1 (not representable in binary) are one value: zero advantages, keep = 0."""
+    G = 8
+    R = np.concatenate([np.full(G, 0.1), np.full(G, 0.7), np.array([0.1] * 7 + [0.3])]).astype(np.float32)
+    adv = torch.empty(3 * G, device=DEV)
+    keep = torch.empty(3, dtype=torch.int32, device=DEV)
+    vb.vla_grpo_advantage(dev(R), 3, G, adv, keep)
+    torch.cuda.synchronize()
+    ra, rk = ro.ogrpo_advantage(R, G)
+    assert rk.tolist() == [False, False, True]
+    assert keep.cpu().numpy().astype(bool).tolist() == rk.tolist()
+    assert np.max(np.abs(adv.cpu().numpy() - ra)) < 1e-5
+    assert (adv.cpu().numpy()[:2 * G] == 0).all()

@@ -247,6 +247,21 @@ int vla_policy_objective(const float *logp_new, const float *logp_old, const flo
                          float *clip_frac, void *stream);
 int vla_logp_aggregate(const float *logp, size_t n_out, int inner, float *out, void *stream);
 
+/* vla_policy_objective_noalloc -- vla_policy_objective for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace,
+ * same kernels, same results bit for bit.  The per-trajectory partial sums live in an array built into the library
+ * (786,432 bytes of device memory per GPU, held until the process ends), so n_traj is limited to
+ * vla_policy_objective_noalloc_max_traj() = 65,536; beyond that VLA_ESHAPE and nothing is enqueued.  The call
+ * allocates and frees nothing, on the device or through any library; the first call on a GPU looks the array's
+ * address up once (hipGetSymbolAddress).  Every call on one GPU shares that GPU's array: two calls that overlap in
+ * time on the same GPU (different streams or threads) race and must be ordered by the caller.  Nothing of an
+ * earlier call is read: every slot the second kernel reads is written by the first. */
+int vla_policy_objective_noalloc_max_traj(void);
+int vla_policy_objective_noalloc(const float *logp_new, const float *logp_old, const float *adv, int adv_per_step,
+                                 const int32_t *mask, int n_traj, int T, float clip_low, float clip_high,
+                                 int per_trajectory, float *objective, float *per_step, float *clip_frac,
+                                 void *stream);
+
 /* ---------------------------------------------------------------- GPU allocation modes (section IV-A)
  * Host-only arithmetic (no device work, all pointers HOST): the rollout-time model behind the
  * automatic placement.  One rollout epoch is m_chunks steps, each a Generation phase (t_gen for the

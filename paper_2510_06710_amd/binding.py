@@ -81,6 +81,8 @@ def lib() -> C.CDLL:
         L.vla_policy_objective_workspace_bytes.argtypes = [i32]
         L.vla_policy_objective_workspace_bytes.restype = sz
         L.vla_policy_objective.argtypes = [vp, vp, vp, i32, vp, i32, i32, f32, f32, i32, vp, sz, vp, vp, vp, vp]
+        L.vla_policy_objective_noalloc_max_traj.restype = C.c_int
+        L.vla_policy_objective_noalloc.argtypes = [vp, vp, vp, i32, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp]
         L.vla_logp_aggregate.argtypes = [vp, sz, i32, vp, vp]
         dp = C.POINTER(C.c_double)
         L.vla_pipeline_time.argtypes = [C.c_double, C.c_double, i32, i32, dp]
@@ -193,6 +195,17 @@ def vla_policy_objective(logp_new, logp_old, adv, adv_per_step, mask, n_traj, T,
                                       n_traj, T, clip_low, clip_high, int(per_trajectory), _ptr(ws),
                                       ws.numel() * ws.element_size(), _ptr(objective), _ptr(per_step),
                                       _ptr(clip_frac), _stream(stream)))
+
+
+def vla_policy_objective_noalloc_max_traj() -> int:
+    return lib().vla_policy_objective_noalloc_max_traj()
+
+
+def vla_policy_objective_noalloc(logp_new, logp_old, adv, adv_per_step, mask, n_traj, T, clip_low, clip_high,
+                                 per_trajectory, objective, per_step=None, clip_frac=None, stream=None) -> None:
+    _check(lib().vla_policy_objective_noalloc(_ptr(logp_new), _ptr(logp_old), _ptr(adv), int(adv_per_step),
+                                              _ptr(mask), n_traj, T, clip_low, clip_high, int(per_trajectory),
+                                              _ptr(objective), _ptr(per_step), _ptr(clip_frac), _stream(stream)))
 
 
 def vla_logp_aggregate(logp, n_out, inner, out, stream=None) -> None:

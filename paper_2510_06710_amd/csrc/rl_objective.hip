@@ -105,6 +105,34 @@ __global__ void logp_aggregate_kernel(const float *logp, size_t n_out, int inner
     out[i] = s;
 }
 
+// Scratch of vla_policy_objective_noalloc: the per-trajectory partial sums [n][3] that the workspace argument of
+// vla_policy_objective otherwise brings in.  One copy per GPU that loads the library, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress; kernels are handed the address it returns.
+constexpr int NOALLOC_MAX_TRAJ = 65536;
+__device__ __align__(256) float scratch[NOALLOC_MAX_TRAJ * 3];
+
+constexpr int MAX_DEVICES = 64;
+float *g_scratch_ptr[MAX_DEVICES] = {};          // device address of `scratch` on each GPU, looked up on first use
+
+// Device address of this GPU's copy of `scratch` (the current device's), or NULL with the error set.
+float *scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        vla_set_error("policy_objective_noalloc: cannot identify the current device");
+        return nullptr;
+    }
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            vla_set_error("policy_objective_noalloc: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = (float *)p;
+    }
+    return g_scratch_ptr[dev];
+}
+
 int policy_objective_launch(const float *logp_new, const float *logp_old, const float *adv, int adv_per_step,
                             const int32_t *mask, int n_traj, int T, float clip_low, float clip_high, int per_trajectory,
                             float *rows, float *objective, float *per_step, float *clip_frac, hipStream_t st) {
@@ -155,6 +183,32 @@ int vla_policy_objective(const float *logp_new, const float *logp_old, const flo
     }
     return policy_objective_launch(logp_new, logp_old, adv, adv_per_step, mask, n_traj, T, clip_low, clip_high,
                                    per_trajectory, (float *)ws, objective, per_step, clip_frac, (hipStream_t)stream);
+}
+
+int vla_policy_objective_noalloc_max_traj(void) { return NOALLOC_MAX_TRAJ; }
+
+int vla_policy_objective_noalloc(const float *logp_new, const float *logp_old, const float *adv, int adv_per_step,
+                                 const int32_t *mask, int n_traj, int T, float clip_low, float clip_high,
+                                 int per_trajectory, float *objective, float *per_step, float *clip_frac, void *stream) {
+    if (!logp_new || !logp_old || !adv || !objective) {
+        vla_set_error("policy_objective_noalloc: logp_new, logp_old, adv or objective is NULL");
+        return VLA_EINVAL;
+    }
+    if (n_traj <= 0 || T <= 0 || !(clip_low >= 0.f) || !(clip_high >= 0.f)) {
+        vla_set_error("policy_objective_noalloc: sizes must be positive and clip ratios non-negative");
+        return VLA_EINVAL;
+    }
+    if (n_traj > NOALLOC_MAX_TRAJ) {
+        vla_set_error("policy_objective_noalloc: %d trajectories exceed the built-in scratch of %d; use "
+                      "vla_policy_objective with a workspace", n_traj, NOALLOC_MAX_TRAJ);
+        return VLA_ESHAPE;
+    }
+    float *rows = scratch_of_current_device();
+    if (!rows) return VLA_EHIP;
+    // every slot below n_traj is written by the first kernel before the second reads it, so what an earlier call
+    // left in the array is never seen and nothing has to be cleared
+    return policy_objective_launch(logp_new, logp_old, adv, adv_per_step, mask, n_traj, T, clip_low, clip_high,
+                                   per_trajectory, rows, objective, per_step, clip_frac, (hipStream_t)stream);
 }
 
 int vla_logp_aggregate(const float *logp, size_t n_out, int inner, float *out, void *stream) {

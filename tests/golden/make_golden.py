@@ -1,8 +1,9 @@
 """Writes tests/golden/oracle_7b.npz (exact fp64 intermediates) or, with ``--operands bf16``,
 tests/golden/oracle_7b_bf16ops.npz (stored tensors rounded to bf16, see oracle/vla_oracle.py):
 oracle outputs for a few sampled environments / rollouts of the 7B-shape workloads (all 32 layers).
-Calls only vla_inputs and oracle/; takes 30-45 minutes on 8 cores and about 20 GB of host memory.
-Run from the repository root:
+Calls only vla_inputs and oracle/; a few minutes per environment on 8 cores and about 20 GB of host memory.
+Entries that the file already holds are kept and not computed again, so adding an environment to the lists below
+costs only that environment.  Run from the repository root:
 
     python tests/golden/make_golden.py [--operands bf16]
 
@@ -23,9 +24,9 @@ from oracle.from_inputs import oracle_weights  # noqa: E402
 from parity import oracle_recompute, oracle_rollout  # noqa: E402
 
 SEED = 0
-AR_ENVS = [0, 37, 200]          # 0 and 37 are inside cfg2's 64 envs; all three inside cfg3's 256
-OFT_ENVS = [0, 100]             # cfg4: 128 envs
-RC_ROLLOUTS = [0, 300]          # cfg5: 512 stored rollouts
+AR_ENVS = [0, 37, 63, 200, 255]  # 0, 37 and 63 (the last) are inside cfg2's 64 envs; all inside cfg3's 256, 255 its last
+OFT_ENVS = [0, 100, 127]         # cfg4: 128 envs, 127 the last
+RC_ROLLOUTS = [0, 256, 300, 511] # cfg5: 512 stored rollouts in two passes of 256: first of the second pass, and the last
 
 
 def main():
@@ -35,29 +36,47 @@ def main():
     mode = ap.parse_args().operands
     t0 = time.time()
     w = oracle_weights(vi.SynthModel(vi.SHAPE_7B, SEED), vi.VALUE_BIAS)
+    name = "oracle_7b.npz" if mode == "exact" else "oracle_7b_bf16ops.npz"
+    path = os.path.join(ROOT, "tests", "golden", name)
     out = {"seed": np.array(SEED)}
+    if os.path.exists(path):
+        with np.load(path, allow_pickle=False) as old:
+            assert int(old["seed"]) == SEED
+            out.update({k: old[k] for k in old.files})
+
+    def save():
+        np.savez_compressed(path, **out)
+
     wl3 = vi.WORKLOADS["cfg3_7b_b256"]
     for e in AR_ENVS:
+        if f"ar_{e}_logits" in out:
+            continue
         r = oracle_rollout(wl3, SEED, env0=e, envs=1, weights=w, operand_dtype=mode)
         for k, v in r.items():
             out[f"ar_{e}_{k}"] = v
+        save()
         print(f"AR env {e} done at {time.time() - t0:.0f}s bins={r['bins']}", flush=True)
     wl4 = vi.WORKLOADS["cfg4_7b_oft_b128"]
     for e in OFT_ENVS:
+        if f"oft_{e}_logits" in out:
+            continue
         r = oracle_rollout(wl4, SEED, env0=e, envs=1, sampled=False, weights=w, operand_dtype=mode)
         for k, v in r.items():
             out[f"oft_{e}_{k}"] = v
+        save()
         print(f"OFT env {e} done at {time.time() - t0:.0f}s", flush=True)
     wl5 = vi.WORKLOADS["cfg5_7b_recompute_n512"]
     for e in RC_ROLLOUTS:
+        if f"rc_{e}_logits" in out:
+            continue
         bins = vi.stored_bins(wl5, SEED, env0=e, envs=1).numpy()
         r = oracle_recompute(wl5, SEED, bins, env0=e, envs=1, weights=w, operand_dtype=mode)
         out[f"rc_{e}_bins"] = bins
         for k, v in r.items():
             out[f"rc_{e}_{k}"] = v
+        save()
         print(f"recompute rollout {e} done at {time.time() - t0:.0f}s", flush=True)
-    name = "oracle_7b.npz" if mode == "exact" else "oracle_7b_bf16ops.npz"
-    np.savez_compressed(os.path.join(ROOT, "tests", "golden", name), **out)
+    save()
     print("written", flush=True)
 
 

@@ -13,23 +13,27 @@ from oracle.from_inputs import oracle_config, oracle_weights, to_f64
 # "f32", "bf16": the stated parity bar -- logits 1e-4 (fp32 storage) / 2e-2 (bf16 storage), chosen-bin
 #   log-prob 1e-2, sampled bins identical unless the oracle's top-2 gap of y + g is below 1e-2.
 #   It is met by the fp32 workload and by bf16 models that are shallow (tiny shapes; one layer at
-#   7B width).
-# "bf16_deep": bf16 storage through many layers at width 4096.  Rounding the eight stored tensors of
-#   a layer to bf16 (2^-9 relative each) perturbs the final hidden state by about 0.9 % per layer, and
-#   the random-weight decoder (per-projection gain 0.02 * sqrt(4096) = 1.28, softmax over 288 keys)
-#   carries perturbations forward undamped, so the error adds in quadrature over layers: measured
-#   0.016 RMS on the logits after 2 layers, predicted 0.016 * sqrt(16) = 0.064 after 32, against a
-#   logit sigma of 1.28.  A CPU emulation that rounds the fp64 oracle at the same eight points gives
-#   the same numbers as the kernels, i.e. the deviation is operand rounding, not the kernels.  Any two
-#   bf16 implementations that differ in fp32 summation order drift apart the same way (a flipped
-#   rounding is a full-ulp perturbation that the following layers amplify), so this bound is also used
-#   against the oracle that rounds the stored tensors itself.  Bounds: logits RMS 0.10 (1.5x the
-#   prediction), max-abs 0.40 (6 sigma over <= 14k compared logits), log-prob 0.30, entropy 0.08,
-#   value 0.15; a sampled bin may differ only where the oracle's top-2 gap is below 0.37 (4 sigma of
-#   the difference of two logit errors).
+#   7B width, also at the full batch sizes of the benchmarked workloads).
+# deep_tol(depth, against, ...): bf16 storage through `depth` layers at width 4096, where the stated bar
+#   cannot hold for any implementation with bf16 operands.  The bound is per depth and per oracle mode, 1.5
+#   times what tests/bf16_drift.py measures on the CPU between correct evaluations of the same rows (table
+#   tests/golden/bf16_drift_7b.json, reproduced for depths 1, 2 and 4 by tests/test_bf16_drift.py), for the RMS
+#   and, scaled by the expected largest of n normal draws, for the maximum.
 TOL = {"f32": dict(logits=1e-4, logp=1e-4, ent=1e-4, value=1e-4, near_tie=1e-2),
-       "bf16": dict(logits=2e-2, logp=1e-2, ent=1e-2, value=2e-2, near_tie=1e-2),
-       "bf16_deep": dict(logits=0.40, logp=0.30, ent=0.08, value=0.15, logits_rms=0.10, near_tie=0.37)}
+       "bf16": dict(logits=2e-2, logp=1e-2, ent=1e-2, value=2e-2, near_tie=1e-2)}
+
+
+def deep_tol(depth: int, against: str, n_logits: int, n_tokens: int) -> dict:
+    """`against`: "ops" (oracle that rounds the stored tensors), "exact" (plain fp64 oracle), "impl" (another
+    bf16 evaluation of the same rows by the library itself)."""
+    import bf16_drift
+    return bf16_drift.tolerance(depth, against, n_logits, n_tokens)
+
+
+def _tol(t):
+    return TOL[t] if isinstance(t, str) else t
+
+
 NEAR_TIE = 1e-2
 
 
@@ -103,44 +107,71 @@ def _rms(a, b):
     return float(np.sqrt(np.mean((np.asarray(a, dtype=np.float64) - b) ** 2)))
 
 
-def compare_rollout(gpu, ref, dtype: str, autoregressive: bool):
-    """Element-by-element comparison.  A sampled bin may differ only where the oracle's top-2 gap of
-    y + g is below NEAR_TIE; such cases are counted, and in autoregressive mode the later tokens of
-    that environment (which now follow a different prefix) are left out."""
-    tol = TOL[dtype]
+def compare_rollout(gpu, ref, dtype, autoregressive: bool, pooled_rms=None):
+    """Element-by-element comparison.  `dtype` names an entry of TOL or is a tolerance dict (deep_tol).
+    A sampled bin may differ only where the oracle's top-2 gap of y + g is below the near-tie bound;
+    such cases are counted, and in autoregressive mode the later tokens of that environment (which now
+    follow a different prefix) are left out.  With "logits_rms" / "logp_rms" in the tolerance the RMS over
+    everything compared is bounded as well as the maximum."""
+    tol = _tol(dtype)
     B, A = ref["bins"].shape
     stats = dict(max_logit_err=0.0, max_logp_err=0.0, max_ent_err=0.0, near_ties=0, compared=0,
                  rms_logit_err_token0=_rms(gpu["logits"][:, 0], ref["logits"][:, 0]))
+    sq_logit, n_logit, sq_logp, n_logp = 0.0, 0, 0.0, 0
     if "value" in gpu and gpu["value"] is not None and ref.get("value") is not None:
         stats["max_value_err"] = float(np.max(np.abs(gpu["value"] - ref["value"])))
-        assert stats["max_value_err"] <= tol["value"], stats
+        assert stats["max_value_err"] <= tol["value"], (stats, tol)
     for b in range(B):
         for j in range(A):
             stats["compared"] += 1
-            stats["max_logit_err"] = max(stats["max_logit_err"], float(np.max(np.abs(gpu["logits"][b, j] - ref["logits"][b, j]))))
+            dz = np.asarray(gpu["logits"][b, j], dtype=np.float64) - ref["logits"][b, j]
+            sq_logit += float(np.sum(dz * dz)); n_logit += dz.size
+            stats["max_logit_err"] = max(stats["max_logit_err"], float(np.max(np.abs(dz))))
             stats["max_ent_err"] = max(stats["max_ent_err"], float(abs(gpu["ent"][b, j] - ref["ent"][b, j])))
             if gpu["bins"][b, j] == ref["bins"][b, j]:
-                stats["max_logp_err"] = max(stats["max_logp_err"], float(abs(gpu["logp"][b, j] - ref["logp"][b, j])))
+                dl = float(gpu["logp"][b, j]) - float(ref["logp"][b, j])
+                sq_logp += dl * dl; n_logp += 1
+                stats["max_logp_err"] = max(stats["max_logp_err"], abs(dl))
                 continue
             assert ref["gap"][b, j] < tol["near_tie"], (b, j, gpu["bins"][b, j], ref["bins"][b, j], ref["gap"][b, j])
             stats["near_ties"] += 1
             if autoregressive:
                 break
-    assert stats["max_logit_err"] <= tol["logits"], stats
-    assert stats["max_logp_err"] <= tol["logp"], stats
-    assert stats["max_ent_err"] <= tol["ent"], stats
-    assert stats["rms_logit_err_token0"] <= tol.get("logits_rms", tol["logits"]), stats
+    stats["rms_logit_err"] = float(np.sqrt(sq_logit / max(n_logit, 1)))
+    stats["rms_logp_err"] = float(np.sqrt(sq_logp / max(n_logp, 1)))
+    stats["n_logits"], stats["n_logp"] = n_logit, n_logp
+    assert stats["max_logit_err"] <= tol["logits"], (stats, tol)
+    assert stats["max_logp_err"] <= tol["logp"], (stats, tol)
+    assert stats["max_ent_err"] <= tol["ent"], (stats, tol)
+    if pooled_rms is None:
+        assert_rms(stats["rms_logit_err"], n_logit, stats["rms_logp_err"], n_logp, tol, stats)
+    else:                      # the caller pools several calls (one environment each) before bounding the RMS
+        pooled_rms["sq_logit"] = pooled_rms.get("sq_logit", 0.0) + sq_logit
+        pooled_rms["n_logit"] = pooled_rms.get("n_logit", 0) + n_logit
+        pooled_rms["sq_logp"] = pooled_rms.get("sq_logp", 0.0) + sq_logp
+        pooled_rms["n_logp"] = pooled_rms.get("n_logp", 0) + n_logp
     return stats
 
 
-def compare_recompute(gpu, ref, dtype: str):
-    tol = TOL[dtype]
+def rms_allowance(n: int) -> float:
+    """An RMS over n draws of spread sigma is itself random: sigma * sqrt(chi2_n / n), whose square has standard
+    deviation sigma^2 sqrt(2 / n).  Bounds on a measured RMS allow two of those (1.02 at 5000 values, 1.3 at 14)."""
+    return float(np.sqrt(1.0 + 2.0 * np.sqrt(2.0 / max(n, 1))))
+
+
+def assert_rms(rms_logit, n_logit, rms_logp, n_logp, tol, context=None):
+    assert rms_logit <= tol.get("logits_rms", tol["logits"]) * rms_allowance(n_logit), (rms_logit, n_logit, tol, context)
+    assert rms_logp <= tol.get("logp_rms", tol["logp"]) * rms_allowance(n_logp), (rms_logp, n_logp, tol, context)
+
+
+def compare_recompute(gpu, ref, dtype):
+    tol = _tol(dtype)
     stats = dict(max_logit_err=float(np.max(np.abs(gpu["logits"] - ref["logits"]))),
                  max_logp_err=float(np.max(np.abs(gpu["logp"] - ref["logp"]))),
                  max_ent_err=float(np.max(np.abs(gpu["ent"] - ref["ent"]))),
                  max_value_err=float(np.max(np.abs(gpu["value"] - ref["value"]))),
-                 rms_logit_err=_rms(gpu["logits"], ref["logits"]))
-    assert stats["rms_logit_err"] <= tol.get("logits_rms", tol["logits"]), stats
+                 rms_logit_err=_rms(gpu["logits"], ref["logits"]), rms_logp_err=_rms(gpu["logp"], ref["logp"]))
+    assert_rms(stats["rms_logit_err"], gpu["logits"].size, stats["rms_logp_err"], gpu["logp"].size, tol, stats)
     assert stats["max_logit_err"] <= tol["logits"], stats
     assert stats["max_logp_err"] <= tol["logp"], stats
     assert stats["max_ent_err"] <= tol["ent"], stats

@@ -247,6 +247,37 @@ int vla_policy_objective(const float *logp_new, const float *logp_old, const flo
                          float *clip_frac, void *stream);
 int vla_logp_aggregate(const float *logp, size_t n_out, int inner, float *out, void *stream);
 
+/* ---- backward pass of the log-probability recompute: LoRA gradients (section IV-B.2; appendix I-B, I-C) -------------
+ * The policy update differentiates the clipped surrogate through rho = exp(logp_theta - logp_old) only, so what it
+ * needs from the model is the gradient of  L = sum_{n,j} coef[n,j] * logp_theta[n,j]  with coef = dJ/dlogp (rho * A-hat
+ * where the unclipped branch is active, 0 elsewhere; the per_step output of vla_policy_objective times the caller's
+ * normalisation).  The trainable parameters are the LoRA factors of the seven projections of every decoder layer:
+ * W_eff = W + scale * B A, A [rank, in], B [out, rank].  The model's weights are the EFFECTIVE ones (the caller keeps
+ * them merged); with X a projection's input and dY the gradient at its output,
+ *     dL/dB = scale * dY^T (X A^T)   [out, rank],      dL/dA = scale * (dY B)^T X   [rank, in].
+ * Embeddings, norm gains, the action head and the value head are frozen.
+ *
+ * vla_lora_layer: DEVICE pointers, storage dtype, per projection a [rank, in] and b [out, rank]
+ *   (in / out: hidden / hidden for q, k, v, o; hidden / ffn for gate, up; ffn / hidden for down).
+ * vla_lora_layer_grads: DEVICE fp32 outputs of the same shapes, overwritten.
+ * vla_logprob_backward: teacher-forced forward over the N stored rollouts exactly as vla_logprob_recompute (same
+ *   arguments, same modes), then the backward.  lora, grads: HOST arrays of n_layers entries.  coef DEVICE fp32 [N, A].
+ *   logp DEVICE fp32 [N, A] out or NULL: the forward's log-probabilities of the stored bins (fp32 attention here, so
+ *   equal to vla_logprob_recompute's up to the rounding differences of two evaluations).  Rollouts are processed in
+ *   micro-batches of max_batch; gradients are summed over micro-batches in order, every sum in a fixed order, so the
+ *   result is reproducible bit for bit.  Gradient operands of the GEMMs are rounded to the storage dtype.
+ *   ws: DEVICE, at least vla_backward_workspace_bytes(cfg, N, P + T, A, rank) bytes (it grows with max_batch: the
+ *   residual stream of every layer is kept for one micro-batch). */
+typedef struct { const void *a, *b; } vla_lora_factor;
+typedef struct { vla_lora_factor q, k, v, o, gate, up, down; } vla_lora_layer;
+typedef struct { float *da, *db; } vla_lora_grad;
+typedef struct { vla_lora_grad q, k, v, o, gate, up, down; } vla_lora_layer_grads;
+size_t vla_backward_workspace_bytes(const vla_config *cfg, int N, int S, int A, int rank);
+int vla_logprob_backward(vla_model *model, void *ws, size_t ws_bytes, const void *patch, const int32_t *ids,
+                         const int32_t *bins, const float *coef, int N, int P, int T, int A, int mode,
+                         const void *slot_embed, float temperature, int rank, float scale, const vla_lora_layer *lora,
+                         const vla_lora_layer_grads *grads, float *logp, void *stream);
+
 /* vla_policy_objective_noalloc -- vla_policy_objective for callers that cannot allocate device memory (code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace,
  * same kernels, same results bit for bit.  The per-trajectory partial sums live in an array built into the library

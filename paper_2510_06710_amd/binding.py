@@ -37,6 +37,25 @@ class vla_weights(C.Structure):
                 ("layers", C.POINTER(vla_layer_weights)), ("value_bias", C.c_void_p)]
 
 
+class vla_lora_factor(C.Structure):
+    _fields_ = [("a", C.c_void_p), ("b", C.c_void_p)]
+
+
+class vla_lora_grad(C.Structure):
+    _fields_ = [("da", C.c_void_p), ("db", C.c_void_p)]
+
+
+LORA_PROJECTIONS = ("q", "k", "v", "o", "gate", "up", "down")
+
+
+class vla_lora_layer(C.Structure):
+    _fields_ = [(n, vla_lora_factor) for n in LORA_PROJECTIONS]
+
+
+class vla_lora_layer_grads(C.Structure):
+    _fields_ = [(n, vla_lora_grad) for n in LORA_PROJECTIONS]
+
+
 class vla_placement(C.Structure):
     _fields_ = [("k", C.c_int32), ("n_gen", C.c_int32), ("n_sim", C.c_int32), ("time", C.c_double)]
 
@@ -73,6 +92,10 @@ def lib() -> C.CDLL:
         L.vla_decode_actions.argtypes = [vp, vp, vp, sz, vp, i32, i32, i32, i32, vp, f32, vp, vp, vp, vp, vp, vp]
         L.vla_logprob_recompute.argtypes = [vp, vp, sz, vp, vp, vp, i32, i32, i32, i32, i32, vp, f32,
                                             vp, vp, vp, vp, vp]
+        L.vla_backward_workspace_bytes.argtypes = [C.POINTER(vla_config), i32, i32, i32, i32]
+        L.vla_backward_workspace_bytes.restype = sz
+        L.vla_logprob_backward.argtypes = [vp, vp, sz, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, f32, i32, f32,
+                                           C.POINTER(vla_lora_layer), C.POINTER(vla_lora_layer_grads), vp, vp]
         L.vla_profile_enable.argtypes = [i32]
         L.vla_profile_report.argtypes = [C.c_char_p, sz]
         L.vla_calibration_copy.argtypes = [vp, vp, sz, vp]
@@ -170,6 +193,29 @@ def vla_logprob_recompute(model, ws, patch, ids, bins, N, P, T, A, mode, slot_em
                                        _ptr(ids), _ptr(bins), N, P, T, A, mode, _ptr(slot_embed),
                                        temperature, _ptr(logp), _ptr(entropy), _ptr(value),
                                        _ptr(logits), _stream(stream)))
+
+
+def vla_backward_workspace_bytes(cfg: vla_config, N: int, S: int, A: int, rank: int) -> int:
+    n = lib().vla_backward_workspace_bytes(C.byref(cfg), N, S, A, rank)
+    if n == 0:
+        raise VlaError(VLA_EINVAL, vla_last_error())
+    return n
+
+
+def vla_logprob_backward(model, ws, patch, ids, bins, coef, N, P, T, A, mode, slot_embed, temperature, rank, scale,
+                         lora, grads, logp=None, stream=None) -> None:
+    """lora[l][p] = (a, b) and grads[l][p] = (da, db): device tensors per layer and projection name."""
+    n_layers = len(lora)
+    la = (vla_lora_layer * n_layers)()
+    ga = (vla_lora_layer_grads * n_layers)()
+    for l in range(n_layers):
+        for p in LORA_PROJECTIONS:
+            f, g = getattr(la[l], p), getattr(ga[l], p)
+            f.a, f.b = lora[l][p][0].data_ptr(), lora[l][p][1].data_ptr()
+            g.da, g.db = grads[l][p][0].data_ptr(), grads[l][p][1].data_ptr()
+    _check(lib().vla_logprob_backward(model, _ptr(ws), ws.numel() * ws.element_size(), _ptr(patch), _ptr(ids), _ptr(bins),
+                                      _ptr(coef), N, P, T, A, mode, _ptr(slot_embed), temperature, rank, scale, la, ga,
+                                      _ptr(logp), _stream(stream)))
 
 
 def vla_calibration_copy(dst, src, nbytes: int, stream=None) -> None:

@@ -60,13 +60,6 @@ static void prof_clear() {
     g_prof.clear();
 }
 
-struct vla_model {
-    vla_config cfg;
-    vla_weights w;
-    std::vector<vla_layer_weights> layers;
-    std::vector<vla_layer_weights> packed;   // k-blocked copies of the seven projection matrices (vla_prepack), or empty
-};
-
 // ------------------------------------------------------------------------------------------ config
 static int check_config(const vla_config *c) {
     if (!c) { vla_set_error("config is NULL"); return VLA_EINVAL; }
@@ -383,6 +376,12 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
         }
     }
     return 0;
+}
+
+int vla_check_config(const vla_config *c) { return check_config(c); }
+int vla_check_rows_per_pass(const vla_config &c, long n_seq, long rows_per_seq) { return check_rows_per_pass(c, n_seq, rows_per_seq); }
+int vla_gemm_dispatch(const vla_config &c, const GemmArgs &g, hipStream_t st) {
+    return c.dtype == VLA_DTYPE_F32 ? run_gemm<float>(c, g, nullptr, st) : run_gemm<bf16_t>(c, g, nullptr, st);
 }
 
 static KvView kv_view(const vla_config &c, void *kv, int n_seq, int n_layers) {

@@ -1,0 +1,599 @@
+// Backward pass of the log-probability recompute: gradients of L = sum(coef * logp) with respect to the LoRA
+// factors of the seven projections of every decoder layer (the policy update of appendix I-B / I-C differentiates
+// the clipped surrogate through rho = exp(logp - logp_old) only; LoRA adapters: section IV-B.2).
+//
+// Structure.  Stored rollouts are processed in micro-batches.  For one micro-batch: (1) a forward pass that keeps the
+// residual stream at the input of every layer (fp32 [layers][rows, H]) and ends in the head, which also returns logp;
+// (2) the head's backward puts d L / d x on the rows that predict action tokens; (3) layers in reverse: the layer's
+// forward is run again from its kept input (same kernels, same values), then the chain rule walks back through the
+// down projection, SwiGLU, gate / up, the FFN norm, the O projection, attention, the rotation, Q / K / V and the
+// attention norm.  Every large contraction -- the seven forward projections and the four input-gradient products
+// dY . W, which run as the same "activation x weight^T" GEMM on a transposed copy of the weights made per layer --
+// goes through the library's GEMM dispatch (MFMA kernels for bf16 shapes they cover).  Attention (scores, softmax,
+// its backward) runs on materialised [rows x rows] matrices per (rollout, head) with a batched fp32 tile kernel, as
+// do the four skinny LoRA products per projection (X A^T, dY B, dY^T (X A^T), (dY B)^T X).  Gradient operands of
+// the GEMMs are rounded to the storage type like every other GEMM operand; all sums are fp32 and taken in a fixed
+// order (no atomics), so the result is reproducible bit for bit.
+#include <vector>
+
+#include "vla_internal.h"
+
+namespace {
+
+template <typename T> __device__ __forceinline__ float ld(const T *p) { return (float)*p; }
+template <typename T> __device__ __forceinline__ T cvt(float v) { return (T)v; }
+
+__device__ __forceinline__ float bsum256(float v, float *red) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+__device__ __forceinline__ float wsum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wmax(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------- batched tile GEMM
+// C[b] (+)= alpha * op(A[b]) . op(B[b]), fp32 accumulation and output.  op(A) is m x k (A row-major [m, k], or
+// [k, m] with transA), op(B) is k x n (B row-major [k, n], or [n, k] with transB).  Batch b = b1 * inner + b2 moves
+// each operand by b1 * s?1 + b2 * s?2 elements.  64 x 64 output tile per 256-thread workgroup, 4 x 4 per thread, K in
+// steps of 16 through LDS; every access bounds checked.  `tri`: rows and columns index the same positions and only
+// keys <= query matter (causal attention): 1 = op(A)'s columns beyond the tile's last row are skipped (P . V, dS . K),
+// 2 = output tiles entirely above the diagonal are skipped (scores, dP: their entries are never read).
+struct BgemmArgs {
+    const void *A, *B;
+    float *C;
+    int m, n, k, lda, ldb, ldc, transA, transB, accumulate, inner, tri;
+    float alpha;
+    long sA1, sA2, sB1, sB2, sC1, sC2;
+};
+
+template <typename TA, typename TB>
+__global__ void __launch_bounds__(256) bgemm_kernel(BgemmArgs g) {
+    constexpr int BM = 64, BN = 64, BK = 16;
+    __shared__ float As[BK][BM + 1];
+    __shared__ float Bs[BK][BN + 1];
+    const int b = blockIdx.z, b1 = b / g.inner, b2 = b - b1 * g.inner;
+    const TA *A = (const TA *)g.A + b1 * g.sA1 + b2 * g.sA2;
+    const TB *B = (const TB *)g.B + b1 * g.sB1 + b2 * g.sB2;
+    float *C = g.C + b1 * g.sC1 + b2 * g.sC2;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    if (g.tri == 2 && n0 > m0 + BM - 1) return;
+    const int kend = g.tri == 1 ? min(g.k, m0 + BM) : g.k;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < kend; k0 += BK) {
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const int idx = e * 256 + threadIdx.x;
+            {   // op(A)[m0 + i][k0 + kk]
+                int i, kk;
+                if (g.transA) { i = idx & 63; kk = idx >> 6; } else { kk = idx & 15; i = idx >> 4; }
+                const int gi = m0 + i, gk = k0 + kk;
+                float v = 0.f;
+                if (gi < g.m && gk < kend) v = g.transA ? ld(A + (size_t)gk * g.lda + gi) : ld(A + (size_t)gi * g.lda + gk);
+                As[kk][i] = v;
+            }
+            {   // op(B)[k0 + kk][n0 + j]
+                int j, kk;
+                if (g.transB) { kk = idx & 15; j = idx >> 4; } else { j = idx & 63; kk = idx >> 6; }
+                const int gj = n0 + j, gk = k0 + kk;
+                float v = 0.f;
+                if (gj < g.n && gk < kend) v = g.transB ? ld(B + (size_t)gj * g.ldb + gk) : ld(B + (size_t)gk * g.ldb + gj);
+                Bs[kk][j] = v;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; kk++) {
+            float a[4], w[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; j++) w[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+#pragma unroll
+                for (int j = 0; j < 4; j++) acc[i][j] += a[i] * w[j];
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int gi = m0 + ty * 4 + i;
+        if (gi >= g.m) continue;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int gj = n0 + tx * 4 + j;
+            if (gj >= g.n) continue;
+            float *c = C + (size_t)gi * g.ldc + gj;
+            const float v = g.alpha * acc[i][j];
+            *c = g.accumulate ? *c + v : v;
+        }
+    }
+}
+
+template <typename TA, typename TB>
+int bgemm(const BgemmArgs &g, int batch, hipStream_t st) {
+    if (g.m <= 0 || g.n <= 0 || batch <= 0) return 0;
+    dim3 grid((g.n + 63) / 64, (g.m + 63) / 64, batch);
+    bgemm_kernel<TA, TB><<<grid, 256, 0, st>>>(g);
+    return vla_check_launch("bgemm");
+}
+
+// ---------------------------------------------------------------------------------------------- elementwise pieces
+__global__ void fill_kernel(float *p, size_t n, float v) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = v;
+}
+
+// rows [M, cols] fp32 -> storage type, row strides given
+template <typename T>
+__global__ void cast_rows_kernel(T *out, const float *in, size_t M, int cols, int ld_out, int ld_in) {
+    const size_t total = M * (size_t)cols;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t m = i / cols;
+        const int c = (int)(i - m * cols);
+        out[m * ld_out + c] = cvt<T>(in[m * ld_in + c]);
+    }
+}
+
+// Rotary on the q and k thirds of the fp32 [M, 3H] projection (pairs (i, i + d/2), angle of the row's position from
+// the table), v copied; everything rounded to the storage type once, after the rotation.  sign = -1 applies the
+// transpose of the rotation (the backward of q and k; v passes through).
+template <typename T>
+__global__ void rope_rows_kernel(T *out, const float *in, const float2 *table, size_t M, int R, int H, int d, float sign) {
+    const int half = d >> 1;
+    const size_t per_row = (size_t)3 * (H >> 1);                 // pairs in q and k, pairs of plain elements in v
+    const size_t total = M * per_row;
+    for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
+        const size_t m = idx / per_row;
+        const int e = (int)(idx - m * per_row);
+        const int seg = e / (H >> 1), w = e - seg * (H >> 1);   // pair w of segment seg
+        const int h = w / half, i = w - h * half;
+        const size_t base = m * 3 * (size_t)H + (size_t)seg * H + (size_t)h * d;
+        const float a = in[base + i], b = in[base + i + half];
+        if (seg == 2) { out[base + i] = cvt<T>(a); out[base + i + half] = cvt<T>(b); continue; }
+        const float2 cs = table[(size_t)(m % R) * half + i];
+        const float s = sign * cs.y;
+        out[base + i] = cvt<T>(a * cs.x - b * s);
+        out[base + i + half] = cvt<T>(b * cs.x + a * s);
+    }
+}
+
+// In-place masked softmax of the score rows of one (sequence, head): row i sees keys 0..i, or all R keys from row
+// full_from on.  One wave per row; entries outside the mask become 0.
+__global__ void __launch_bounds__(256) attn_softmax_kernel(float *SP, size_t n_rows, int R, int full_from) {
+    const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n_rows) return;
+    const int lane = threadIdx.x & 63, i = (int)(row % R);
+    const int nk = i >= full_from ? R : i + 1;
+    float *s = SP + row * R;
+    float mx = -INFINITY;
+    for (int j = lane; j < nk; j += 64) mx = fmaxf(mx, s[j]);
+    mx = wmax(mx);
+    float sum = 0.f;
+    for (int j = lane; j < nk; j += 64) { const float e = expf(s[j] - mx); s[j] = e; sum += e; }
+    sum = wsum(sum);
+    const float inv = 1.0f / sum;
+    for (int j = lane; j < R; j += 64) s[j] = j < nk ? s[j] * inv : 0.f;
+}
+
+// dS = P (dP - sum_j P dP) in place on dP; masked entries (P = 0) become 0.
+__global__ void __launch_bounds__(256) attn_ds_kernel(float *dP, const float *P, size_t n_rows, int R, int full_from) {
+    const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n_rows) return;
+    const int lane = threadIdx.x & 63, i = (int)(row % R);
+    const int nk = i >= full_from ? R : i + 1;
+    float *d = dP + row * R;
+    const float *p = P + row * R;
+    float dot = 0.f;
+    for (int j = lane; j < nk; j += 64) dot += p[j] * d[j];
+    dot = wsum(dot);
+    for (int j = lane; j < R; j += 64) d[j] = j < nk ? p[j] * (d[j] - dot) : 0.f;
+}
+
+// act = silu(gate) * up from the fp32 [M, 2F] projection (gate columns, then up columns)
+template <typename T>
+__global__ void swiglu_fwd_kernel(T *act, const float *GU, size_t M, int F) {
+    const size_t total = M * (size_t)F;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t m = i / F;
+        const int f = (int)(i - m * F);
+        const float g = GU[m * 2 * F + f], u = GU[m * 2 * F + F + f];
+        act[m * F + f] = cvt<T>(g / (1.0f + expf(-g)) * u);
+    }
+}
+
+// d gate = d act * up * silu'(gate), d up = d act * silu(gate); silu'(t) = s (1 + t (1 - s)), s = sigmoid(t)
+template <typename T>
+__global__ void swiglu_bwd_kernel(T *dGU, const float *d_act, const float *GU, size_t M, int F) {
+    const size_t total = M * (size_t)F;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t m = i / F;
+        const int f = (int)(i - m * F);
+        const float g = GU[m * 2 * F + f], u = GU[m * 2 * F + F + f], da = d_act[i];
+        const float s = 1.0f / (1.0f + expf(-g));
+        dGU[m * 2 * F + f] = cvt<T>(da * u * s * (1.0f + g * (1.0f - s)));
+        dGU[m * 2 * F + F + f] = cvt<T>(da * g * s);
+    }
+}
+
+// dX[m] += r (g dn) - x r^3 mean(x g dn), r = (mean(x^2) + eps)^(-1/2): the backward of n = RMSNorm(x) g.
+__global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(float *dX, const float *X, const float *gain, const float *dn, int H, float eps) {
+    __shared__ float red[4];
+    const float *x = X + (size_t)blockIdx.x * H, *d = dn + (size_t)blockIdx.x * H;
+    float ss = 0.f, xd = 0.f;
+    for (int i = threadIdx.x; i < H; i += 256) { ss += x[i] * x[i]; xd += x[i] * gain[i] * d[i]; }
+    ss = bsum256(ss, red);
+    xd = bsum256(xd, red);
+    const float r = 1.0f / sqrtf(ss / (float)H + eps);
+    const float k = r * r * r * xd / (float)H;
+    float *o = dX + (size_t)blockIdx.x * H;
+    for (int i = threadIdx.x; i < H; i += 256) o[i] += r * gain[i] * d[i] - x[i] * k;
+}
+
+// Head forward + backward of one read-out row (one workgroup, thread k = bin k): h = RMSNorm(x) g_f, z = h . W_bins^T,
+// y = z / tau, logp = y_bin - logsumexp(y); d z_k = coef / tau * ([k = bin] - p_k); d h = d z . W_bins; d x by the norm's
+// backward.  Writes logp (if asked) and the row of dX (which is zero elsewhere).
+template <typename T>
+__global__ void __launch_bounds__(256) head_bwd_kernel(float *dX, float *logp_out, const float *X, const float *gain, const T *Wb,
+                                                      const int32_t *bins, const float *coef, int A, int rows_per_seq, int row0,
+                                                      int H, float eps, float inv_tau) {
+    extern __shared__ float smem[];
+    float *hs = smem, *dz = smem + H;          // [H], [256]
+    __shared__ float red[4];
+    __shared__ float stat[2];
+    const int s = blockIdx.x / A, j = blockIdx.x - s * A, t = threadIdx.x;
+    const size_t m = (size_t)s * rows_per_seq + row0 + j;
+    const float *x = X + m * H;
+    float ss = 0.f;
+    for (int i = t; i < H; i += 256) ss += x[i] * x[i];
+    ss = bsum256(ss, red);
+    const float r = 1.0f / sqrtf(ss / (float)H + eps);
+    for (int i = t; i < H; i += 256) hs[i] = x[i] * r * gain[i];
+    __syncthreads();
+    const T *w = Wb + (size_t)t * H;
+    float z = 0.f;
+    for (int i = 0; i < H; i++) z += hs[i] * ld(w + i);
+    const float y = z * inv_tau;
+    dz[t] = y;
+    __syncthreads();
+    if (t < 64) {
+        float mx = fmaxf(fmaxf(dz[t], dz[t + 64]), fmaxf(dz[t + 128], dz[t + 192]));
+        mx = wmax(mx);
+        float sum = expf(dz[t] - mx) + expf(dz[t + 64] - mx) + expf(dz[t + 128] - mx) + expf(dz[t + 192] - mx);
+        sum = wsum(sum);
+        if (t == 0) { stat[0] = mx; stat[1] = logf(sum) + mx; }
+    }
+    __syncthreads();
+    const float lse = stat[1];
+    int bin = bins[(size_t)s * A + j];
+    bin = min(max(bin, 0), VLA_N_BINS - 1);
+    const float c = coef[(size_t)s * A + j];
+    if (logp_out && t == bin) logp_out[(size_t)s * A + j] = y - lse;
+    __syncthreads();
+    dz[t] = c * inv_tau * ((t == bin ? 1.0f : 0.0f) - expf(y - lse));
+    __syncthreads();
+    // d h_i = sum_k dz_k W[k][i], then the norm's backward; a thread owns columns t, t + 256, ...
+    float xd = 0.f;
+    for (int i = t; i < H; i += 256) {
+        float dh = 0.f;
+        for (int k = 0; k < VLA_N_BINS; k++) dh += dz[k] * ld(Wb + (size_t)k * H + i);
+        hs[i] = gain[i] * dh;                       // g dh (h itself is no longer needed)
+        xd += x[i] * hs[i];
+    }
+    xd = bsum256(xd, red);
+    const float k3 = r * r * r * xd / (float)H;
+    float *o = dX + m * H;
+    for (int i = t; i < H; i += 256) o[i] = r * hs[i] - x[i] * k3;
+}
+
+// Wt[k][col0 + n] = W[n][k]: the weight matrix [N, K] transposed into a [K, ldt] matrix at column col0 (32 x 32 tiles
+// through LDS so that both sides move whole rows).
+template <typename T>
+__global__ void __launch_bounds__(256) transpose_kernel(T *Wt, const T *W, int N, int K, int ldt, int col0) {
+    __shared__ T tile[32][33];
+    const int n0 = blockIdx.y * 32, k0 = blockIdx.x * 32, tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int r = ty; r < 32; r += 8)
+        if (n0 + r < N && k0 + tx < K) tile[r][tx] = W[(size_t)(n0 + r) * K + k0 + tx];
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8)
+        if (k0 + r < K && n0 + tx < N) Wt[(size_t)(k0 + r) * ldt + col0 + n0 + tx] = tile[tx][r];
+}
+
+inline unsigned blocks_for(size_t n) { size_t b = (n + 255) / 256; return (unsigned)(b > 65535 * 16 ? 65535 * 16 : (b ? b : 1)); }
+
+// ---------------------------------------------------------------------------------------------- workspace
+struct BwSpace {
+    float *X, *dX, *ckpt, *QKV, *GU, *Tmp, *SP, *dP, *U, *V;
+    void *Nrm, *Nrm2, *AO, *ACT, *QKVr, *dGU, *dXb, *dQKVb, *Wt;
+    float2 *rope;
+    int a_rows;
+    size_t total;
+};
+
+size_t al(size_t v) { return (v + 255) & ~(size_t)255; }
+
+BwSpace plan_bw(const vla_config &c, char *base, int mb, int R, int rank) {
+    BwSpace w;
+    size_t off = 0;
+    const size_t es = c.dtype == VLA_DTYPE_F32 ? 4 : 2, M = (size_t)mb * R, H = c.hidden, F = c.ffn, L = c.n_layers;
+    const size_t Mp = (M + 255) / 256 * 256 + VLA_KB_PAD_ROWS;
+    auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += al(bytes); return (void *)p; };
+    w.a_rows = (int)Mp;
+    w.X = (float *)take(M * H * 4);
+    w.dX = (float *)take(M * H * 4);
+    w.ckpt = (float *)take(L * M * H * 4);
+    w.QKV = (float *)take(M * 3 * H * 4);
+    w.GU = (float *)take(M * 2 * F * 4);
+    w.Tmp = (float *)take(M * (F > 3 * H ? F : 3 * H) * 4);
+    w.SP = (float *)take((size_t)mb * c.n_heads * R * R * 4);
+    w.dP = (float *)take((size_t)mb * c.n_heads * R * R * 4);
+    w.U = (float *)take(M * rank * 4);
+    w.V = (float *)take(M * rank * 4);
+    w.Nrm = take(Mp * H * es);
+    w.Nrm2 = take(Mp * H * es);
+    w.AO = take(Mp * H * es);
+    w.ACT = take(Mp * F * es);
+    w.QKVr = take(Mp * 3 * H * es);
+    w.dGU = take(Mp * 2 * F * es);
+    w.dXb = take(Mp * H * es);
+    w.dQKVb = take(Mp * 3 * H * es);
+    w.Wt = take((3 * H > 2 * F ? 3 * H : 2 * F) * H * es);      // the widest transposed stack: [H, 3H] or [H, 2F] ([F, H] is smaller)
+    w.rope = (float2 *)take((size_t)R * (H / c.n_heads / 2) * sizeof(float2));
+    w.total = off;
+    return w;
+}
+
+int bw_micro_batch(const vla_config &c, int N) { return N < c.max_batch ? N : c.max_batch; }
+
+// ---------------------------------------------------------------------------------------------- the pass itself
+template <typename T>
+struct Backward {
+    const vla_model *m;
+    const vla_config &c;
+    BwSpace ws;
+    hipStream_t st;
+    int n, R, M, H, F, d, nh, full_from, rank;
+    float scale;
+
+    int gemm(const void *A, const void *W0, const void *W1, const void *W2, int n_seg, int segN, float *C, int K) {
+        GemmArgs g{};
+        g.A = A; g.W[0] = W0; g.W[1] = W1; g.W[2] = W2; g.n_seg = n_seg; g.segN = segN; g.C = C; g.M = M; g.K = K;
+        g.epilogue = EPI_STORE; g.a_rows = ws.a_rows;
+        return vla_gemm_dispatch(c, g, st);
+    }
+    int transpose(const void *W, int N, int K, int ldt, int col0) {
+        dim3 grid((K + 31) / 32, (N + 31) / 32);
+        transpose_kernel<T><<<grid, 256, 0, st>>>((T *)ws.Wt, (const T *)W, N, K, ldt, col0);
+        return vla_check_launch("transpose");
+    }
+    int cast(void *out, const float *in, int cols, int ld_out, int ld_in) {
+        cast_rows_kernel<T><<<blocks_for((size_t)M * cols), 256, 0, st>>>((T *)out, in, (size_t)M, cols, ld_out, ld_in);
+        return vla_check_launch("cast_rows");
+    }
+    BgemmArgs heads(const void *A, int lda, long sA1, long sA2, const void *B, int ldb, long sB1, long sB2, float *C, int ldc,
+                    long sC1, long sC2, int mm, int nn, int kk, int tA, int tB, float alpha, int tri) {
+        BgemmArgs g{};
+        g.A = A; g.B = B; g.C = C; g.m = mm; g.n = nn; g.k = kk; g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.transA = tA; g.transB = tB;
+        g.accumulate = 0; g.inner = nh; g.tri = tri; g.alpha = alpha;
+        g.sA1 = sA1; g.sA2 = sA2; g.sB1 = sB1; g.sB2 = sB2; g.sC1 = sC1; g.sC2 = sC2;
+        return g;
+    }
+
+    // One decoder layer forward on ws.X (in place), leaving in the workspace what its backward needs: Nrm, QKVr, SP (the
+    // attention probabilities), AO, X = x_mid ... then x_out, Nrm2, GU, ACT.  `x_mid_keep`: copy of x_mid (or NULL).
+    int layer_forward(int l, float *x_mid_keep) {
+        const vla_layer_weights &lw = m->layers[l];
+        const T *Q = (const T *)ws.QKVr;
+        const long RR = (long)R * R, rowsH3 = (long)R * 3 * H;
+        const bool causal = full_from >= R;
+        int rc;
+        if ((rc = launch_rmsnorm<T>((T *)ws.Nrm, ws.X, (const float *)lw.attn_norm, M, H, c.rms_eps, st))) return rc;
+        if ((rc = gemm(ws.Nrm, lw.wq, lw.wk, lw.wv, 3, H, ws.QKV, H))) return rc;
+        rope_rows_kernel<T><<<blocks_for((size_t)M * 3 * (H / 2)), 256, 0, st>>>((T *)ws.QKVr, ws.QKV, ws.rope, (size_t)M, R, H, d, 1.0f);
+        if ((rc = vla_check_launch("rope_rows"))) return rc;
+        // scores = q k^T / sqrt(d) per (sequence, head); softmax under the mask; output = P v
+        BgemmArgs g = heads(Q, 3 * H, rowsH3, d, Q + H, 3 * H, rowsH3, d, ws.SP, R, RR * nh, RR, R, R, d, 0, 1, 1.0f / sqrtf((float)d), causal ? 2 : 0);
+        if ((rc = bgemm<T, T>(g, n * nh, st))) return rc;
+        attn_softmax_kernel<<<(unsigned)(((size_t)n * nh * R + 3) / 4), 256, 0, st>>>(ws.SP, (size_t)n * nh * R, R, full_from);
+        if ((rc = vla_check_launch("attn_softmax"))) return rc;
+        g = heads(ws.SP, R, RR * nh, RR, Q + 2 * H, 3 * H, rowsH3, d, ws.Tmp, H, (long)R * H, d, R, d, R, 0, 0, 1.0f, causal ? 1 : 0);
+        if ((rc = bgemm<float, T>(g, n * nh, st))) return rc;
+        if ((rc = cast(ws.AO, ws.Tmp, H, H, H))) return rc;
+        if ((rc = gemm(ws.AO, lw.wo, nullptr, nullptr, 1, H, ws.Tmp, H))) return rc;
+        add_kernel_launch(ws.X, ws.Tmp, (size_t)M * H);
+        if ((rc = vla_check_launch("residual add"))) return rc;
+        if (x_mid_keep && hipMemcpyAsync(x_mid_keep, ws.X, (size_t)M * H * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) { vla_set_error("backward: copy failed"); return VLA_EHIP; }
+        if ((rc = launch_rmsnorm<T>((T *)ws.Nrm2, ws.X, (const float *)lw.ffn_norm, M, H, c.rms_eps, st))) return rc;
+        if ((rc = gemm(ws.Nrm2, lw.w_gate, lw.w_up, nullptr, 2, F, ws.GU, H))) return rc;
+        swiglu_fwd_kernel<T><<<blocks_for((size_t)M * F), 256, 0, st>>>((T *)ws.ACT, ws.GU, (size_t)M, F);
+        if ((rc = vla_check_launch("swiglu_fwd"))) return rc;
+        if ((rc = gemm(ws.ACT, lw.w_down, nullptr, nullptr, 1, H, ws.Tmp, F))) return rc;
+        add_kernel_launch(ws.X, ws.Tmp, (size_t)M * H);
+        return vla_check_launch("residual add");
+    }
+    void add_kernel_launch(float *x, const float *y, size_t nel);
+
+    // dA [rank, in] and dB [out, rank] of one projection: X [M, in] (storage type, row stride ldx), dY [M, out] (ldy)
+    int lora_grads(const vla_lora_factor &f, const vla_lora_grad &gr, const void *X, int ldx, int in, const void *dY, int ldy, int out,
+                   bool first) {
+        int rc;
+        BgemmArgs g{};
+        g.inner = 1; g.accumulate = 0; g.alpha = 1.0f;
+        // U = X A^T  [M, rank]
+        g.A = X; g.lda = ldx; g.transA = 0; g.B = f.a; g.ldb = in; g.transB = 1; g.C = ws.U; g.ldc = rank; g.m = M; g.n = rank; g.k = in;
+        if ((rc = bgemm<T, T>(g, 1, st))) return rc;
+        // V = dY B   [M, rank]
+        g.A = dY; g.lda = ldy; g.B = f.b; g.ldb = rank; g.transB = 0; g.C = ws.V; g.k = out;
+        if ((rc = bgemm<T, T>(g, 1, st))) return rc;
+        // dB (+)= scale dY^T U  [out, rank]
+        g.accumulate = first ? 0 : 1; g.alpha = scale;
+        g.A = dY; g.lda = ldy; g.transA = 1; g.B = ws.U; g.ldb = rank; g.transB = 0; g.C = gr.db; g.ldc = rank; g.m = out; g.n = rank; g.k = M;
+        if ((rc = bgemm<T, float>(g, 1, st))) return rc;
+        // dA (+)= scale V^T X   [rank, in]
+        g.A = ws.V; g.lda = rank; g.transA = 1; g.B = X; g.ldb = ldx; g.transB = 0; g.C = gr.da; g.ldc = in; g.m = rank; g.n = in; g.k = M;
+        return bgemm<float, T>(g, 1, st);
+    }
+
+    // Backward of layer l: on entry ws.dX = d L / d x_out; on exit d L / d x_in.  x_in is ckpt[l].
+    int layer_backward(int l, const vla_lora_layer &lo, const vla_lora_layer_grads &gr, bool first) {
+        const vla_layer_weights &lw = m->layers[l];
+        float *x_in = ws.ckpt + (size_t)l * M * H;
+        float *x_mid = ws.QKV;                       // the fp32 projection buffer is free once QKVr exists: x_mid lives there
+        const T *Q = (const T *)ws.QKVr;
+        const long RR = (long)R * R, rowsH3 = (long)R * 3 * H;
+        const bool causal = full_from >= R;
+        const float isd = 1.0f / sqrtf((float)d);
+        int rc;
+        if (hipMemcpyAsync(ws.X, x_in, (size_t)M * H * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) { vla_set_error("backward: copy failed"); return VLA_EHIP; }
+        if ((rc = layer_forward(l, x_mid))) return rc;
+        // ---- down projection and SwiGLU
+        if ((rc = cast(ws.dXb, ws.dX, H, H, H))) return rc;
+        if ((rc = lora_grads(lo.down, gr.down, ws.ACT, F, F, ws.dXb, H, H, first))) return rc;
+        if ((rc = transpose(lw.w_down, H, F, H, 0))) return rc;                               // [F, H]
+        if ((rc = gemm(ws.dXb, ws.Wt, nullptr, nullptr, 1, F, ws.Tmp, H))) return rc;          // d act [M, F]
+        swiglu_bwd_kernel<T><<<blocks_for((size_t)M * F), 256, 0, st>>>((T *)ws.dGU, ws.Tmp, ws.GU, (size_t)M, F);
+        if ((rc = vla_check_launch("swiglu_bwd"))) return rc;
+        if ((rc = lora_grads(lo.gate, gr.gate, ws.Nrm2, H, H, ws.dGU, 2 * F, F, first))) return rc;
+        if ((rc = lora_grads(lo.up, gr.up, ws.Nrm2, H, H, (const T *)ws.dGU + F, 2 * F, F, first))) return rc;
+        if ((rc = transpose(lw.w_gate, F, H, 2 * F, 0)) || (rc = transpose(lw.w_up, F, H, 2 * F, F))) return rc;   // [H, 2F]
+        if ((rc = gemm(ws.dGU, ws.Wt, nullptr, nullptr, 1, H, ws.Tmp, 2 * F))) return rc;      // d n2 [M, H]
+        rmsnorm_bwd_kernel<<<M, 256, 0, st>>>(ws.dX, x_mid, (const float *)lw.ffn_norm, ws.Tmp, H, c.rms_eps);
+        if ((rc = vla_check_launch("rmsnorm_bwd"))) return rc;
+        // ---- O projection and attention (ws.dX is now d L / d x_mid)
+        if ((rc = cast(ws.dXb, ws.dX, H, H, H))) return rc;
+        if ((rc = lora_grads(lo.o, gr.o, ws.AO, H, H, ws.dXb, H, H, first))) return rc;
+        if ((rc = transpose(lw.wo, H, H, H, 0))) return rc;
+        float *d_ao = ws.GU;                         // [M, H] fp32; the gate / up projection is no longer needed
+        if ((rc = gemm(ws.dXb, ws.Wt, nullptr, nullptr, 1, H, d_ao, H))) return rc;
+        float *dqkv = ws.Tmp;                        // [M, 3H] fp32: d q | d k | d v (q, k still in the rotated frame)
+        // dP = dO v^T ; dV = P^T dO ; dS = P (dP - rowsum(P dP)) ; dQ = dS k / sqrt(d) ; dK = dS^T q / sqrt(d)
+        BgemmArgs g = heads(d_ao, H, (long)R * H, d, Q + 2 * H, 3 * H, rowsH3, d, ws.dP, R, RR * nh, RR, R, R, d, 0, 1, 1.0f, causal ? 2 : 0);
+        if ((rc = bgemm<float, T>(g, n * nh, st))) return rc;
+        g = heads(ws.SP, R, RR * nh, RR, d_ao, H, (long)R * H, d, dqkv + 2 * H, 3 * H, rowsH3, d, R, d, R, 1, 0, 1.0f, 0);
+        if ((rc = bgemm<float, float>(g, n * nh, st))) return rc;
+        attn_ds_kernel<<<(unsigned)(((size_t)n * nh * R + 3) / 4), 256, 0, st>>>(ws.dP, ws.SP, (size_t)n * nh * R, R, full_from);
+        if ((rc = vla_check_launch("attn_ds"))) return rc;
+        g = heads(ws.dP, R, RR * nh, RR, Q + H, 3 * H, rowsH3, d, dqkv, 3 * H, rowsH3, d, R, d, R, 0, 0, isd, causal ? 1 : 0);
+        if ((rc = bgemm<float, T>(g, n * nh, st))) return rc;
+        g = heads(ws.dP, R, RR * nh, RR, Q, 3 * H, rowsH3, d, dqkv + H, 3 * H, rowsH3, d, R, d, R, 1, 0, isd, 0);
+        if ((rc = bgemm<float, T>(g, n * nh, st))) return rc;
+        rope_rows_kernel<T><<<blocks_for((size_t)M * 3 * (H / 2)), 256, 0, st>>>((T *)ws.dQKVb, dqkv, ws.rope, (size_t)M, R, H, d, -1.0f);
+        if ((rc = vla_check_launch("rope_rows (transpose)"))) return rc;
+        // ---- Q / K / V projections and the attention norm
+        const T *dq = (const T *)ws.dQKVb;
+        if ((rc = lora_grads(lo.q, gr.q, ws.Nrm, H, H, dq, 3 * H, H, first))) return rc;
+        if ((rc = lora_grads(lo.k, gr.k, ws.Nrm, H, H, dq + H, 3 * H, H, first))) return rc;
+        if ((rc = lora_grads(lo.v, gr.v, ws.Nrm, H, H, dq + 2 * H, 3 * H, H, first))) return rc;
+        if ((rc = transpose(lw.wq, H, H, 3 * H, 0)) || (rc = transpose(lw.wk, H, H, 3 * H, H)) || (rc = transpose(lw.wv, H, H, 3 * H, 2 * H))) return rc;
+        if ((rc = gemm(ws.dQKVb, ws.Wt, nullptr, nullptr, 1, H, ws.GU, 3 * H))) return rc;     // d n [M, H]
+        rmsnorm_bwd_kernel<<<M, 256, 0, st>>>(ws.dX, x_in, (const float *)lw.attn_norm, ws.GU, H, c.rms_eps);
+        return vla_check_launch("rmsnorm_bwd");
+    }
+};
+
+__global__ void add_kernel(float *x, const float *y, size_t nel) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nel; i += (size_t)gridDim.x * 256) x[i] += y[i];
+}
+template <typename T>
+void Backward<T>::add_kernel_launch(float *x, const float *y, size_t nel) {
+    add_kernel<<<blocks_for(nel), 256, 0, st>>>(x, y, nel);
+}
+
+template <typename T>
+int backward_impl(vla_model *m, void *wsbuf, const void *patch, const int32_t *ids, const int32_t *bins, const float *coef, int N, int P,
+                  int T_, int A, int mode, const void *slot_embed, float temperature, int rank, float scale,
+                  const vla_lora_layer *lora, const vla_lora_layer_grads *grads, float *logp, hipStream_t st) {
+    const vla_config &c = m->cfg;
+    const int S = P + T_, H = c.hidden, L = c.n_layers;
+    const int R = (mode == VLA_MODE_AR) ? S + A - 1 : S + A;
+    const int first_row = (mode == VLA_MODE_AR) ? S - 1 : S;
+    const int mb = bw_micro_batch(c, N);
+    const T *head = (const T *)m->w.lm_head + (size_t)(c.vocab - VLA_N_BINS) * H;
+    int rc;
+    Backward<T> bw{m, c, plan_bw(c, (char *)wsbuf, mb, R, rank), st, 0, R, 0, H, c.ffn, H / c.n_heads, c.n_heads,
+                   mode == VLA_MODE_AR ? 0x7fffffff : S, rank, scale};
+    if ((rc = launch_rope_table(bw.ws.rope, R, 0, bw.d, c.rope_theta, st))) return rc;
+    bool first = true;
+    for (int n0 = 0; n0 < N; n0 += mb, first = false) {
+        const int n = (N - n0 < mb) ? N - n0 : mb;
+        bw.n = n; bw.M = n * R;
+        const size_t MH = (size_t)bw.M * H;
+        const T *pp = (const T *)patch + (size_t)n0 * P * H;
+        if ((rc = launch_embed_prefix<T>(bw.ws.X, pp, ids + (size_t)n0 * T_, (const T *)m->w.embed, n, P, T_, R, H, c.vocab, st))) return rc;
+        if (mode == VLA_MODE_AR) {
+            if ((rc = launch_embed_tokens<T>(bw.ws.X, bins + (size_t)n0 * A, A, A - 1, (const T *)m->w.embed, n, R, S, H, c.vocab, st))) return rc;
+        } else if ((rc = launch_embed_slots<T>(bw.ws.X, (const T *)slot_embed, n, A, R, S, H, st))) return rc;
+        for (int l = 0; l < L; l++) {
+            if (hipMemcpyAsync(bw.ws.ckpt + (size_t)l * MH, bw.ws.X, MH * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) { vla_set_error("backward: copy failed"); return VLA_EHIP; }
+            if ((rc = bw.layer_forward(l, nullptr))) return rc;
+        }
+        fill_kernel<<<blocks_for(MH), 256, 0, st>>>(bw.ws.dX, MH, 0.f);
+        if ((rc = vla_check_launch("fill"))) return rc;
+        head_bwd_kernel<T><<<n * A, 256, (size_t)(H + VLA_N_BINS) * sizeof(float), st>>>(
+            bw.ws.dX, logp ? logp + (size_t)n0 * A : nullptr, bw.ws.X, (const float *)m->w.final_norm, head, bins + (size_t)n0 * A,
+            coef + (size_t)n0 * A, A, R, first_row, H, c.rms_eps, 1.0f / temperature);
+        if ((rc = vla_check_launch("head_bwd"))) return rc;
+        for (int l = L - 1; l >= 0; l--)
+            if ((rc = bw.layer_backward(l, lora[l], grads[l], first))) return rc;
+    }
+    return 0;
+}
+
+bool lora_layer_complete(const vla_lora_layer &l, const vla_lora_layer_grads &g) {
+    const vla_lora_factor *f = &l.q;
+    const vla_lora_grad *d = &g.q;
+    for (int i = 0; i < 7; i++)
+        if (!f[i].a || !f[i].b || !d[i].da || !d[i].db) return false;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t vla_backward_workspace_bytes(const vla_config *cfg, int N, int S, int A, int rank) {
+    if (vla_check_config(cfg)) return 0;
+    if (N <= 0 || S <= 0 || A <= 0 || rank <= 0) { vla_set_error("N, S, A and rank must be positive"); return 0; }
+    if (S + A > cfg->max_seq + 1) { vla_set_error("S + A exceeds capacity"); return 0; }
+    const int R = (S + A <= cfg->max_seq) ? S + A : S + A - 1;
+    return plan_bw(*cfg, nullptr, bw_micro_batch(*cfg, N), R, rank).total;
+}
+
+int vla_logprob_backward(vla_model *m, void *ws, size_t ws_bytes, const void *patch, const int32_t *ids, const int32_t *bins,
+                         const float *coef, int N, int P, int T, int A, int mode, const void *slot_embed, float temperature,
+                         int rank, float scale, const vla_lora_layer *lora, const vla_lora_layer_grads *grads, float *logp,
+                         void *stream) {
+    if (!m || !ws || !bins || !coef || !lora || !grads) { vla_set_error("model, ws, bins, coef, lora or grads is NULL"); return VLA_EINVAL; }
+    if (mode != VLA_MODE_AR && mode != VLA_MODE_PARALLEL_CHUNK) { vla_set_error("unknown mode %d", mode); return VLA_EINVAL; }
+    if (N <= 0 || P < 0 || T < 0 || P + T < 1 || A <= 0 || rank <= 0) { vla_set_error("need N, A, rank >= 1, P, T >= 0, P + T >= 1"); return VLA_EINVAL; }
+    if ((P > 0 && !patch) || (T > 0 && !ids)) { vla_set_error("patch / ids is NULL"); return VLA_EINVAL; }
+    if (!(temperature > 0.f)) { vla_set_error("temperature must be positive"); return VLA_EINVAL; }
+    if (mode == VLA_MODE_PARALLEL_CHUNK && !slot_embed) { vla_set_error("slot_embed is NULL"); return VLA_EINVAL; }
+    const vla_config &c = m->cfg;
+    for (int l = 0; l < c.n_layers; l++)
+        if (!lora_layer_complete(lora[l], grads[l])) { vla_set_error("layer %d has a NULL LoRA factor or gradient pointer", l); return VLA_EINVAL; }
+    const int S = P + T, R = (mode == VLA_MODE_AR) ? S + A - 1 : S + A;
+    if (R > c.max_seq) { vla_set_error("rows per rollout %d exceed max_seq %d", R, c.max_seq); return VLA_ESHAPE; }
+    const int mb = bw_micro_batch(c, N);
+    if ((size_t)mb * R * (size_t)(c.ffn > 3 * c.hidden ? 2 * c.ffn : 3 * c.hidden) * 4 >= ((size_t)1 << 40)) { vla_set_error("micro-batch too large"); return VLA_ESHAPE; }
+    if (int rc = vla_check_rows_per_pass(c, mb, R)) return rc;
+    const size_t need = plan_bw(c, nullptr, mb, R, rank).total;
+    if (ws_bytes < need) { vla_set_error("workspace %zu bytes, need %zu", ws_bytes, need); return VLA_EWORKSPACE; }
+    hipStream_t st = (hipStream_t)stream;
+    return c.dtype == VLA_DTYPE_F32
+               ? backward_impl<float>(m, ws, patch, ids, bins, coef, N, P, T, A, mode, slot_embed, temperature, rank, scale, lora, grads, logp, st)
+               : backward_impl<bf16_t>(m, ws, patch, ids, bins, coef, N, P, T, A, mode, slot_embed, temperature, rank, scale, lora, grads, logp, st);
+}
+
+}  // extern "C"

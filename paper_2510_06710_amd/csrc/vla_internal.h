@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/vla.h"
 
 typedef __bf16 bf16_t;
@@ -179,6 +181,18 @@ size_t attention_prefill_scratch_bytes(int n_seq, int n_heads, int d, int n_keys
 
 int vla_check_launch(const char *what);
 void vla_set_error(const char *fmt, ...);
+
+// The host-side model object behind the opaque handle of the C ABI.
+struct vla_model {
+    vla_config cfg;
+    vla_weights w;
+    std::vector<vla_layer_weights> layers;
+    std::vector<vla_layer_weights> packed;   // k-blocked copies of the seven projection matrices (vla_prepack), or empty
+};
+int vla_check_config(const vla_config *c);                                   // VLA_OK or the error code, message set
+int vla_check_rows_per_pass(const vla_config &c, long n_seq, long rows_per_seq);
+// C = A . W^T of a multi-row forward (row-major operands): the MFMA kernels where the shape allows, else the generic one
+int vla_gemm_dispatch(const vla_config &c, const GemmArgs &g, hipStream_t st);
 
 // Profiling scope: when profiling is enabled, records an event pair around the launches issued
 // during its lifetime, tagged with `label` (a string literal) and the algorithmic work.

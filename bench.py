@@ -66,6 +66,16 @@ def read_traffic(path, kernel, source):
         return None, prov
 
 
+def forward_flops(shape, n_seq, rows, tail_rows):
+    """Projection flops a multi-row forward executes: all rows through all layers but the last; in the last layer K and
+    V for all rows and the rest (q, o, gate, up, down) for the `tail_rows` rows per sequence whose output is read
+    (the library skips what nothing reads; the skipped work is not counted here).  tail_rows = rows: no skipping."""
+    H, F = shape.hidden, shape.ffn
+    full = 2.0 * shape.layer_params
+    last = 2.0 * (2 * H * H) * rows + 2.0 * (2 * H * H + 3 * H * F) * tail_rows
+    return n_seq * (rows * full * (shape.n_layers - 1) + last)
+
+
 def cpu_baseline(wl, vi, sample_layers=8):
     """The CPU oracle as it stands, on 1 environment x `sample_layers` of the model's layers
     (prefill + decode), scaled linearly to all layers; the head and embedding cost is negligible."""
@@ -128,7 +138,8 @@ def bench_recompute(args, wl, torch, vi, vb, Rollout):
     prof = profile_report(vb)
     vb.lib().vla_profile_enable(0)
     rows = S + A - 1 if wl.mode == 0 else S + A
-    flops = N * rows * 2.0 * shape.layer_params * shape.n_layers
+    tail = A if (wl.mode == 0 and A * 4 <= rows) else rows          # autoregressive form: only the A read-out rows finish the last layer
+    flops = forward_flops(shape, N, rows, tail)
     dom = prof.get("gemm_bf16_dma<swiglu>")
     roofline = None
     if dom:
@@ -330,7 +341,7 @@ def main():
         kv_bytes = B * (S + A) * kv_tok
     decode_bytes = fwd * weight_bytes + kv_bytes
     decode_gbps = decode_bytes / (decode_ms * 1e-3) / 1e9
-    prefill_flops = B * S * 2.0 * shape.layer_params * shape.n_layers
+    prefill_flops = forward_flops(shape, B, S, 1 if S >= 4 else S)       # the last layer finishes the last prefix row only
 
     def table(p):
         return {k: {"n": v["count"], "ms": round(v["ms"], 3),
@@ -353,7 +364,10 @@ def main():
                    "prefill_mfma_TFLOPs": prefill_flops / (prefill_ms * 1e-3) / 1e12,
                    "prefill_mfma_frac": prefill_flops / (prefill_ms * 1e-3) / 1e12 / MI355X_BF16_TFLOPS,
                    "decode_hbm_GBps": decode_gbps, "decode_hbm_frac": decode_gbps / MI355X_HBM_GBPS,
-                   "decode_algorithmic_GB": decode_bytes / 1e9},
+                   "decode_algorithmic_GB": decode_bytes / 1e9,
+                   "prefill_executed_TFLOP": prefill_flops / 1e12,
+                   "note": "last layer of the prefill: K, V for all rows, the rest for the last prefix row only (nothing else "
+                           "is read); prefill_mfma_* count the executed flops"},
         "kernels_prefill": table(prof_prefill), "kernels_decode": table(prof_decode),
     }
     if not args.no_cpu_baseline:

@@ -204,6 +204,12 @@ int vla_logprob_recompute(vla_model *model, void *ws, size_t ws_bytes,
 int vla_profile_enable(int on);
 int vla_profile_report(char *buf, size_t n);
 
+/* Triage aid (process-wide, not thread safe): a bit mask of steps that take the shape-generic kernel even where a
+ * gfx950 fast path applies -- 1 large GEMM, 2 decode GEMM, 4 multi-row attention, 8 decode attention, 16 rotary / KV
+ * write / RMSNorm; 0 (the default) selects every fast path.  Results stay within the parity tolerances either way;
+ * the tests use it to run the generic kernels on shapes that would otherwise never reach them. */
+int vla_debug_force_generic(int mask);
+
 /* Calibration aid for hardware-counter runs: a plain copy kernel (`bytes` must be a multiple of 16;
  * dst, src DEVICE, 16-byte aligned) that reads and writes exactly `bytes` bytes, so that HBM
  * traffic counters collected around the hot kernels can be scaled by what they read for it. */

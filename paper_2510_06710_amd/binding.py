@@ -96,6 +96,7 @@ def lib() -> C.CDLL:
         L.vla_backward_workspace_bytes.restype = sz
         L.vla_logprob_backward.argtypes = [vp, vp, sz, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, f32, i32, f32,
                                            C.POINTER(vla_lora_layer), C.POINTER(vla_lora_layer_grads), vp, vp]
+        L.vla_debug_force_generic.argtypes = [i32]
         L.vla_profile_enable.argtypes = [i32]
         L.vla_profile_report.argtypes = [C.c_char_p, sz]
         L.vla_calibration_copy.argtypes = [vp, vp, sz, vp]
@@ -216,6 +217,10 @@ def vla_logprob_backward(model, ws, patch, ids, bins, coef, N, P, T, A, mode, sl
     _check(lib().vla_logprob_backward(model, _ptr(ws), ws.numel() * ws.element_size(), _ptr(patch), _ptr(ids), _ptr(bins),
                                       _ptr(coef), N, P, T, A, mode, _ptr(slot_embed), temperature, rank, scale, la, ga,
                                       _ptr(logp), _stream(stream)))
+
+
+def vla_debug_force_generic(mask: int) -> None:
+    _check(lib().vla_debug_force_generic(mask))
 
 
 def vla_calibration_copy(dst, src, nbytes: int, stream=None) -> None:

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libvla.so")
-SOURCES = ["api.hip", "kernels_generic.hip", "gemm_mfma.hip", "gemm_dma.hip", "gemm_skinny.hip", "gemm_mid.hip", "attn_mfma.hip", "attn_decode.hip", "elementwise_bf16.hip", "rl_objective.hip", "placement.hip", "backward.hip"]
+SOURCES = ["api.hip", "kernels_generic.hip", "gemm_dma.hip", "gemm_skinny.hip", "gemm_mid.hip", "attn_mfma.hip", "attn_decode.hip", "elementwise_bf16.hip", "rl_objective.hip", "placement.hip", "backward.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -106,12 +106,17 @@ struct Workspace {
     void *skinny;    // split-K partial sums of the decode GEMM (single-row forwards only)
     int a_rows;      // rows allocated for Nrm, AO and ACT (M rounded up to whole 256-row GEMM tiles, plus the pad of
                      // the k-blocked layout, whose block stride this is)
+    // Tail of the last layer (see run_layers): the rows whose output is read, packed [n_seq * tail_rows, ...]
+    int tail_rows;   // rows per sequence (0: no tail buffers)
+    float *tX, *tQf; // residual stream and fp32 q projection of the tail rows
+    void *tNrm, *tQ, *tAO, *tACT, *tskinny;
+    int t_a_rows;
     size_t total;
 };
 
 // Lays the workspace out from `base` (may be NULL to only size it).
 static Workspace plan_workspace(const vla_config &c, char *base, int n_seq, int R, int n_keys,
-                                int head_rows, bool kv_scratch) {
+                                int head_rows, bool kv_scratch, int tail_rows = 0) {
     Workspace w;
     size_t off = 0, es = elt_size(c);
     size_t M = (size_t)n_seq * R, H = c.hidden, F = c.ffn;
@@ -135,6 +140,20 @@ static Workspace plan_workspace(const vla_config &c, char *base, int n_seq, int 
     w.vt = vtb ? take(vtb) : nullptr;
     size_t skb = (c.dtype == VLA_DTYPE_BF16 && R == 1 && M <= 256) ? gemm_skinny_scratch_bytes((int)M, (int)(2 * F > 3 * H ? 2 * F : 3 * H)) : 0;
     w.skinny = skb ? take(skb) : nullptr;
+    w.tail_rows = tail_rows;
+    w.tX = w.tQf = nullptr; w.tNrm = w.tQ = w.tAO = w.tACT = w.tskinny = nullptr; w.t_a_rows = 0;
+    if (tail_rows > 0) {
+        const size_t Mt = (size_t)n_seq * tail_rows, Mtp = (Mt + 255) / 256 * 256 + VLA_KB_PAD_ROWS;
+        w.t_a_rows = (int)Mtp;
+        w.tX = (float *)take(Mt * H * 4);
+        w.tQf = (float *)take(Mt * H * 4);
+        w.tNrm = take(Mtp * H * es);
+        w.tQ = take(Mtp * H * es);
+        w.tAO = take(Mtp * H * es);
+        w.tACT = take(Mtp * F * es);
+        const size_t tsk = (c.dtype == VLA_DTYPE_BF16 && Mt <= 256) ? gemm_skinny_scratch_bytes((int)Mt, (int)(2 * F > 3 * H ? 2 * F : 3 * H)) : 0;
+        w.tskinny = tsk ? take(tsk) : nullptr;
+    }
     w.total = off;
     return w;
 }
@@ -170,27 +189,16 @@ static int recompute_micro_batch(const vla_config &c, int N, int R) {
 }
 
 // ------------------------------------------------------------------------------------------ forward
-// Triage knob: VLA_FORCE_GENERIC is a bit mask that sends a step to the shape-generic kernel even
-// when a gfx950 fast path applies (1 large GEMM, 2 decode GEMM, 4 multi-row attention, 8 decode
-// attention, 16 rotary/KV write).  Read once.
-static int force_generic() {
-    static int v = -1;
-    if (v < 0) { const char *e = getenv("VLA_FORCE_GENERIC"); v = e ? atoi(e) : 0; }
-    return v;
-}
-
-static int mid_gemm_enabled() {
-    static int v = -1;
-    if (v < 0) { const char *e = getenv("VLA_MID_GEMM"); v = e ? atoi(e) : 1; }
-    return v;
-}
+// Triage switch (vla_debug_force_generic): a bit mask that sends a step to the shape-generic kernel even when a
+// gfx950 fast path applies (1 large GEMM, 2 decode GEMM, 4 multi-row attention, 8 decode attention, 16 rotary / KV
+// write / RMSNorm).  Process-wide; 0 unless the caller sets it.
+static int g_force_generic = 0;
+static int force_generic() { return g_force_generic; }
 
 // The multi-row bf16 forwards can run on k-blocked operands ([K / 32][rows][32], see gemm_dma.hip): needs
 // head_dim 128 (fused rotation epilogue), tile-aligned widths and repacked weights.
 static bool kblocked_shape_ok(const vla_config &c) {
-    static int env = -1;
-    if (env < 0) { const char *e = getenv("VLA_KBLOCKED"); env = e ? atoi(e) : 1; }
-    if (!env || c.dtype != VLA_DTYPE_BF16 || c.hidden % c.n_heads != 0 || c.hidden / c.n_heads != 128) return false;
+    if (c.dtype != VLA_DTYPE_BF16 || c.hidden % c.n_heads != 0 || c.hidden / c.n_heads != 128) return false;
     if (c.hidden % 1024 != 0 || c.hidden > 8192) return false;        // the register-resident RMSNorm writes the layout
     return c.hidden % 256 == 0 && c.hidden >= 256 && c.ffn % 128 == 0 && c.ffn >= 256 &&
            (size_t)c.ffn * c.hidden * 2 < ((size_t)1 << 31);
@@ -200,20 +208,8 @@ static size_t prepack_layer_bytes(const vla_config &c) {
     return (4 * (H + P) * H + 2 * (F + P) * H + (H + P) * F) * 2;
 }
 
-static int dma_gemm_enabled() {
-    static int v = -1;
-    if (v < 0) { const char *e = getenv("VLA_GEMM_DMA"); v = e ? atoi(e) : 1; }
-    return v;
-}
-
-// The large-tile GEMM: the direct-to-LDS kernel where it applies, else the register-staged one.
-static int try_gemm_bf16_large(const GemmArgs &g, hipStream_t st) {
-    if (dma_gemm_enabled()) {
-        int r = try_gemm_bf16_dma(g, st);
-        if (r != 0) return r;
-    }
-    return try_gemm_bf16_mfma(g, st);
-}
+// The large-tile GEMM (declines K below 256 or not a multiple of 64: the generic kernel then takes the call).
+static int try_gemm_bf16_large(const GemmArgs &g, hipStream_t st) { return try_gemm_bf16_dma(g, st); }
 
 // Kernel choice depends on the storage type, on whether the forward has one row per sequence (decode) and, for
 // decode forwards, on the batch: up to 128 rows stream the weights through the skinny kernel, larger batches use
@@ -229,12 +225,9 @@ static int run_gemm(const vla_config &c, GemmArgs g, void *skinny_scratch, hipSt
             // that the work is MFMA bound and the large tile with split K does better
             if (g.M > 128 && !(force_generic() & 1)) {
                 const size_t sb = gemm_skinny_scratch_bytes(g.M, 2 * c.ffn > 3 * c.hidden ? 2 * c.ffn : 3 * c.hidden);
-                if (dma_gemm_enabled() && mid_gemm_enabled() != 3) r = try_gemm_bf16_dma_splitk(g, skinny_scratch, sb, st);
-                if (r == 0) r = mid_gemm_enabled() ? try_gemm_bf16_mid(g, skinny_scratch, sb, st) : 0;
-                if (r == 0) r = try_gemm_bf16_mfma_splitk(g, skinny_scratch, sb, st);
+                r = try_gemm_bf16_dma_splitk(g, skinny_scratch, sb, st);
+                if (r == 0) r = try_gemm_bf16_mid(g, skinny_scratch, sb, st);
             }
-            if (r == 0 && mid_gemm_enabled() == 2)
-                r = try_gemm_bf16_mid(g, skinny_scratch, gemm_skinny_scratch_bytes(g.M, 2 * c.ffn > 3 * c.hidden ? 2 * c.ffn : 3 * c.hidden), st);
             if (r == 0) r = try_gemm_bf16_skinny(g, skinny_scratch, st);
         }
         if (r != 0) return r < 0 ? r : 0;
@@ -291,15 +284,96 @@ static int run_layer_kblocked(const vla_model *m, const Workspace &ws, const Row
     return must(try_gemm_bf16_dma(g, st), "down projection");
 }
 
+// The rows of a multi-row forward whose final hidden state is read: `count` rows per sequence from row `first`.
+struct TailSpec { int first, count; };
+
+// Whether a forward of R rows per sequence takes the shortened last layer.  Only the rows that the head (or the value
+// head) reads need the last layer's attention output and feed-forward block; all rows still need its K and V, which
+// the KV cache keeps.  So the last layer computes K and V for every row and everything else for the tail rows alone
+// (packed), which leaves the outputs unchanged and saves (1 - 2H^2 / (4H^2 + 3HF)) of one layer's GEMMs: 2.6 % of a
+// 32-layer prefill.  Not worth it when the tail is a large share of the rows.
+static bool use_tail(const TailSpec *tail, int R) { return tail && tail->count >= 1 && tail->count * 4 <= R; }
+
+// Last layer, tail form: K, V of all rows (ws.X / ws.Nrm as in any layer), then the rest of the layer on the packed
+// tail rows (ws.tX and friends) with the kernels a forward of that many rows would use.
+template <typename T>
+static int run_last_layer_tail(const vla_model *m, const Workspace &ws, const RowsArgs &ra, const KvView &kv, int l, int kl,
+                               const TailSpec &tail, bool kb, hipStream_t st) {
+    const vla_config &c = m->cfg;
+    const int H = c.hidden, F = c.ffn, M = ra.n_seq * ra.R, d = H / c.n_heads, Mt = ra.n_seq * tail.count;
+    const vla_layer_weights &lw = m->layers[l];
+    int rc;
+    // ---- K and V of every row
+    bool kv_done = false;
+    if (c.dtype == VLA_DTYPE_BF16 && d == 128 && !(force_generic() & (1 | 16))) {
+        QkvRopeArgs qa{nullptr, ws.rope, &kv, kl, &ra};
+        GemmArgs g{};
+        g.A = ws.Nrm; g.n_seg = 2; g.segN = H; g.C = nullptr; g.M = M; g.K = H; g.epilogue = EPI_QKV_ROPE; g.rope = &qa; g.a_rows = ws.a_rows;
+        if (kb) {
+            if ((rc = try_rmsnorm_bf16((bf16_t *)ws.Nrm, ws.X, (const float *)lw.attn_norm, M, H, c.rms_eps, ws.a_rows, st)) <= 0)
+                return rc < 0 ? rc : (vla_set_error("internal: k-blocked RMSNorm declined"), (int)VLA_ESHAPE);
+            g.W[0] = m->packed[l].wk; g.W[1] = m->packed[l].wv; g.kblocked = 1;
+        } else {
+            if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.attn_norm, M, 0, st))) return rc;
+            g.W[0] = lw.wk; g.W[1] = lw.wv;
+        }
+        rc = try_gemm_bf16_dma(g, st);
+        if (rc < 0) return rc;
+        if (rc == 0 && kb) { vla_set_error("internal: k-blocked K / V projection declined"); return VLA_ESHAPE; }
+        kv_done = rc == 1;
+    }
+    if (!kv_done) {          // plain path: the full projection (its q rows are not used), rotation and KV write
+        if ((rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.attn_norm, M, 0, st))) return rc;
+        GemmArgs g{};
+        g.A = ws.Nrm; g.W[0] = lw.wq; g.W[1] = lw.wk; g.W[2] = lw.wv; g.n_seg = 3; g.segN = H; g.C = ws.QKV; g.M = M; g.K = H;
+        g.epilogue = EPI_STORE; g.a_rows = ws.a_rows;
+        if ((rc = run_gemm<T>(c, g, nullptr, st))) return rc;
+        if (c.dtype == VLA_DTYPE_BF16 && !(force_generic() & 16))
+            rc = launch_rope_kv_write_bf16((bf16_t *)ws.Q, ws.QKV, 1, (size_t)M * 3 * H, ws.rope, kv, kl, ra, H, st);
+        else rc = launch_rope_kv_write<T>((T *)ws.Q, ws.QKV, ws.rope, kv, kl, ra, H, st);
+        if (rc) return rc;
+    }
+    // ---- the tail rows: q, attention against the layer's K and V, O projection, feed-forward block
+    if ((rc = launch_gather_rows(ws.tX, ws.X, ra.n_seq, ra.R, tail.first, tail.count, H, st))) return rc;
+    if ((rc = run_rmsnorm<T>(c, ws.tNrm, ws.tX, lw.attn_norm, Mt, 0, st))) return rc;
+    GemmArgs g{};
+    g.A = ws.tNrm; g.W[0] = lw.wq; g.n_seg = 1; g.segN = H; g.C = ws.tQf; g.M = Mt; g.K = H; g.epilogue = EPI_STORE; g.a_rows = ws.t_a_rows;
+    if ((rc = run_gemm<T>(c, g, ws.tskinny, st))) return rc;
+    if ((rc = launch_rope_q<T>((T *)ws.tQ, ws.tQf, ws.rope, ra.n_seq, tail.count, tail.first, c.n_heads, d, H, st))) return rc;
+    const RowsArgs rt{ra.n_seq, tail.count, ra.pos0 + tail.first, ra.full_from};
+    int done = 0;
+    if (c.dtype == VLA_DTYPE_BF16) {
+        if (tail.count == 1)
+            done = (force_generic() & 8) ? 0 : try_attention_decode_bf16((bf16_t *)ws.tAO, (const bf16_t *)ws.tQ, kv, kl, rt, H, st);
+        else
+            done = (force_generic() & 4) ? 0 : try_attention_prefill_bf16((bf16_t *)ws.tAO, (const bf16_t *)ws.tQ, kv, kl, rt, H, ws.vt, 0, st);
+        if (done < 0) return done;
+    }
+    if (!done && (rc = launch_attention_generic<T>((T *)ws.tAO, (const T *)ws.tQ, kv, kl, rt, H, st))) return rc;
+    g = GemmArgs{};
+    g.A = ws.tAO; g.W[0] = lw.wo; g.n_seg = 1; g.segN = H; g.C = ws.tX; g.M = Mt; g.K = H; g.epilogue = EPI_RESIDUAL; g.a_rows = ws.t_a_rows;
+    if ((rc = run_gemm<T>(c, g, ws.tskinny, st))) return rc;
+    if ((rc = run_rmsnorm<T>(c, ws.tNrm, ws.tX, lw.ffn_norm, Mt, 0, st))) return rc;
+    g = GemmArgs{};
+    g.A = ws.tNrm; g.W[0] = lw.w_gate; g.W[1] = lw.w_up; g.n_seg = 2; g.segN = F; g.C = ws.tACT; g.M = Mt; g.K = H;
+    g.epilogue = EPI_SWIGLU; g.a_rows = ws.t_a_rows;
+    if ((rc = run_gemm<T>(c, g, ws.tskinny, st))) return rc;
+    g = GemmArgs{};
+    g.A = ws.tACT; g.W[0] = lw.w_down; g.n_seg = 1; g.segN = H; g.C = ws.tX; g.M = Mt; g.K = F; g.epilogue = EPI_RESIDUAL; g.a_rows = ws.t_a_rows;
+    return run_gemm<T>(c, g, ws.tskinny, st);
+}
+
+// `tail` (may be NULL): the rows whose final hidden state the caller reads.  Where use_tail() holds, the last layer
+// is run in its tail form and the result of those rows is in ws.tX (packed), not in ws.X.
 template <typename T>
 static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &ra, const KvView &kv,
-                      bool kv_single_layer, hipStream_t st) {
+                      bool kv_single_layer, hipStream_t st, const TailSpec *tail = nullptr) {
     const vla_config &c = m->cfg;
     int H = c.hidden, F = c.ffn, M = ra.n_seq * ra.R, d = H / c.n_heads, rc;
     if ((rc = launch_rope_table(ws.rope, ra.R, ra.pos0, d, c.rope_theta, st))) return rc;
     // k-blocked operands: repacked weights present, a multi-row forward, every fast path available and the
     // 32-bit offsets of the loads sufficient
-    const bool kb = !m->packed.empty() && ra.R > 1 && kblocked_shape_ok(c) && dma_gemm_enabled() && force_generic() == 0 &&
+    const bool kb = !m->packed.empty() && ra.R > 1 && kblocked_shape_ok(c) && force_generic() == 0 &&
                     ws.vt && (size_t)ra.n_seq * c.n_heads <= 65535 && M >= 1 &&
                     (size_t)ws.a_rows * (F > H ? F : H) * 2 < ((size_t)1 << 31);
     // Single-row bf16 forwards: the split-K GEMMs leave their partial sums to the kernel that follows (rotation + KV
@@ -308,9 +382,11 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
     const bool fuse_reduce = c.dtype == VLA_DTYPE_BF16 && ra.R == 1 && ws.skinny && !(force_generic() & (2 | 16)) &&
                              H % 1024 == 0 && H <= 8192;
     bool have_nrm = false;                 // the previous layer's down projection already wrote this layer's Nrm
+    const bool tail_form = use_tail(tail, ra.R) && ws.tail_rows == tail->count && ra.R > 1;
     for (int l = 0; l < c.n_layers; l++) {
         const vla_layer_weights &lw = m->layers[l];
         int kl = kv_single_layer ? 0 : l;
+        if (tail_form && l == c.n_layers - 1) return run_last_layer_tail<T>(m, ws, ra, kv, l, kl, *tail, kb, st);
         if (kb) {
             if ((rc = run_layer_kblocked(m, ws, ra, kv, l, kl, st))) return rc;
             continue;
@@ -384,6 +460,13 @@ int vla_gemm_dispatch(const vla_config &c, const GemmArgs &g, hipStream_t st) {
     return c.dtype == VLA_DTYPE_F32 ? run_gemm<float>(c, g, nullptr, st) : run_gemm<bf16_t>(c, g, nullptr, st);
 }
 
+static int prefill_tail_rows(int S) { const TailSpec t{S - 1, 1}; return use_tail(&t, S) ? 1 : 0; }
+// recompute, autoregressive mode: rows S - 1 .. S + A - 2 are read (the value head reads the first of them)
+static int recompute_tail_rows(int S, int A, int mode) {
+    const TailSpec t{S - 1, A};
+    return mode == VLA_MODE_AR && use_tail(&t, S + A - 1) ? A : 0;
+}
+
 static KvView kv_view(const vla_config &c, void *kv, int n_seq, int n_layers) {
     KvView v;
     v.layer_elems = kv_layer_elems(c, n_seq);
@@ -399,12 +482,16 @@ static int prefill_impl(vla_model *m, void *kvbuf, void *wsbuf, const void *patc
                         int P, int T_, float *h_last, float *value, hipStream_t st) {
     const vla_config &c = m->cfg;
     int S = P + T_, H = c.hidden, rc;
-    Workspace ws = plan_workspace(c, (char *)wsbuf, B, S, S, 0, false);
+    const TailSpec tail{S - 1, 1};                    // only the last prefix row is read after the last layer
+    const bool tf = use_tail(&tail, S);
+    Workspace ws = plan_workspace(c, (char *)wsbuf, B, S, S, 0, false, tf ? 1 : 0);
     if ((rc = launch_embed_prefix<T>(ws.X, (const T *)patch, ids, (const T *)m->w.embed, B, P, T_, S, H, c.vocab, st))) return rc;
     RowsArgs ra{B, S, 0, 0x7fffffff};
     KvView kv = kv_view(c, kvbuf, B, c.n_layers);
-    if ((rc = run_layers<T>(m, ws, ra, kv, false, st))) return rc;
-    if ((rc = launch_final_norm_rows(h_last, ws.X, (const float *)m->w.final_norm, B, S, S - 1, 1, H, c.rms_eps, st))) return rc;
+    if ((rc = run_layers<T>(m, ws, ra, kv, false, st, &tail))) return rc;
+    if (tf) rc = launch_final_norm_rows(h_last, ws.tX, (const float *)m->w.final_norm, B, 1, 0, 1, H, c.rms_eps, st);
+    else rc = launch_final_norm_rows(h_last, ws.X, (const float *)m->w.final_norm, B, S, S - 1, 1, H, c.rms_eps, st);
+    if (rc) return rc;
     if (value && (rc = launch_value_head(value, h_last, (const float *)m->w.value_w, m->w.value_b, (const float *)m->w.value_bias, value_dim(m->cfg), B, H, H, st))) return rc;
     return 0;
 }
@@ -452,7 +539,9 @@ static int recompute_impl(vla_model *m, void *wsbuf, const void *patch, const in
     int first = (mode == VLA_MODE_AR) ? S - 1 : S;          // row that predicts action token 1
     int mb = recompute_micro_batch(c, N, S + A);
     const T *head = (const T *)m->w.lm_head + (size_t)(c.vocab - VLA_N_BINS) * H;
-    Workspace ws = plan_workspace(c, (char *)wsbuf, mb, R, R, mb * (A + 1), true);
+    const int tr = recompute_tail_rows(S, A, mode);
+    const TailSpec tail{S - 1, A};
+    Workspace ws = plan_workspace(c, (char *)wsbuf, mb, R, R, mb * (A + 1), true, tr);
     for (int n0 = 0; n0 < N; n0 += mb) {
         int n = (N - n0 < mb) ? N - n0 : mb;
         const T *pp = (const T *)patch + (size_t)n0 * P * H;
@@ -466,14 +555,17 @@ static int recompute_impl(vla_model *m, void *wsbuf, const void *patch, const in
         KvView kv;
         kv.layer_elems = kv_layer_elems(c, mb);
         kv.k = ws.kvs_k; kv.v = ws.kvs_v; kv.n_seq = n; kv.n_heads = c.n_heads; kv.d = H / c.n_heads; kv.pos_stride = c.max_seq;
-        if ((rc = run_layers<T>(m, ws, ra, kv, true, st))) return rc;
-        if ((rc = launch_final_norm_rows(ws.Hb, ws.X, (const float *)m->w.final_norm, n, R, first, A, H, c.rms_eps, st))) return rc;
+        if ((rc = run_layers<T>(m, ws, ra, kv, true, st, tr ? &tail : nullptr))) return rc;
+        // after a tail-form last layer the read-out rows are the packed tail rows 0 .. A - 1 of each rollout
+        const float *Xh = tr ? ws.tX : ws.X;
+        const int rows_h = tr ? A : R, first_h = tr ? 0 : first, value_row = tr ? 0 : S - 1;
+        if ((rc = launch_final_norm_rows(ws.Hb, Xh, (const float *)m->w.final_norm, n, rows_h, first_h, A, H, c.rms_eps, st))) return rc;
         size_t o = (size_t)n0 * A;
         if ((rc = launch_head_sample<T>(ws.Hb, head, n * A, H, temperature, nullptr, bins + o, nullptr, logp + o, entropy + o,
                                         logits ? logits + o * VLA_N_BINS : nullptr, 1, 0, nullptr, (const T *)nullptr, c.vocab, st))) return rc;
         if (value) {
             float *hv = ws.Hb + (size_t)mb * A * H;
-            if ((rc = launch_final_norm_rows(hv, ws.X, (const float *)m->w.final_norm, n, R, S - 1, 1, H, c.rms_eps, st))) return rc;
+            if ((rc = launch_final_norm_rows(hv, Xh, (const float *)m->w.final_norm, n, rows_h, value_row, 1, H, c.rms_eps, st))) return rc;
             if ((rc = launch_value_head(value + (size_t)n0 * value_dim(m->cfg), hv, (const float *)m->w.value_w, m->w.value_b, (const float *)m->w.value_bias, value_dim(m->cfg), n, H, H, st))) return rc;
         }
     }
@@ -573,7 +665,7 @@ size_t vla_workspace_bytes(const vla_config *cfg, int entry, int B, int S, int A
         case VLA_ENTRY_PREFILL:
             if (B > cfg->max_batch || S > cfg->max_seq) { vla_set_error("B or S exceeds capacity"); return 0; }
             if (check_rows_per_pass(*cfg, B, S)) return 0;
-            return plan_workspace(*cfg, nullptr, B, S, S, 0, false).total;
+            return plan_workspace(*cfg, nullptr, B, S, S, 0, false, prefill_tail_rows(S)).total;
         case VLA_ENTRY_DECODE: {
             if (B > cfg->max_batch || S + a > cfg->max_seq + 1) { vla_set_error("B or S + A exceeds capacity"); return 0; }
             if (check_rows_per_pass(*cfg, B, a)) return 0;
@@ -585,7 +677,8 @@ size_t vla_workspace_bytes(const vla_config *cfg, int entry, int B, int S, int A
             if (S + a > cfg->max_seq + 1) { vla_set_error("S + A exceeds capacity"); return 0; }
             int R = (S + a <= cfg->max_seq) ? S + a : S + a - 1;
             int mb = recompute_micro_batch(*cfg, B, S + a);
-            return plan_workspace(*cfg, nullptr, mb, R, R, mb * (a + 1), true).total;
+            // (the query does not know the mode: the autoregressive form's tail buffers are included either way)
+            return plan_workspace(*cfg, nullptr, mb, R, R, mb * (a + 1), true, recompute_tail_rows(S, a, VLA_MODE_AR)).total;
         }
         default:
             vla_set_error("unknown entry %d", entry);
@@ -605,7 +698,7 @@ int vla_prefill(vla_model *m, void *kv, void *ws, size_t ws_bytes, const void *p
         return VLA_ESHAPE;
     }
     if (int rc = check_rows_per_pass(c, B, P + T)) return rc;
-    size_t need = plan_workspace(c, nullptr, B, P + T, P + T, 0, false).total;
+    size_t need = plan_workspace(c, nullptr, B, P + T, P + T, 0, false, prefill_tail_rows(P + T)).total;
     if (ws_bytes < need) { vla_set_error("workspace %zu bytes, need %zu", ws_bytes, need); return VLA_EWORKSPACE; }
     hipStream_t st = (hipStream_t)stream;
     return c.dtype == VLA_DTYPE_F32 ? prefill_impl<float>(m, kv, ws, patch, ids, B, P, T, h_last, value, st)
@@ -651,12 +744,18 @@ int vla_logprob_recompute(vla_model *m, void *ws, size_t ws_bytes, const void *p
     int S = P + T, R = (mode == VLA_MODE_AR) ? S + A - 1 : S + A;
     if (R > c.max_seq) { vla_set_error("rows per rollout %d exceed max_seq %d", R, c.max_seq); return VLA_ESHAPE; }
     int mb = recompute_micro_batch(c, N, S + A);
-    size_t need = plan_workspace(c, nullptr, mb, R, R, mb * (A + 1), true).total;
+    size_t need = plan_workspace(c, nullptr, mb, R, R, mb * (A + 1), true, recompute_tail_rows(S, A, mode)).total;
     if (ws_bytes < need) { vla_set_error("workspace %zu bytes, need %zu", ws_bytes, need); return VLA_EWORKSPACE; }
     hipStream_t st = (hipStream_t)stream;
     return c.dtype == VLA_DTYPE_F32
                ? recompute_impl<float>(m, ws, patch, ids, bins, N, P, T, A, mode, slot_embed, temperature, logp, entropy, value, logits, st)
                : recompute_impl<bf16_t>(m, ws, patch, ids, bins, N, P, T, A, mode, slot_embed, temperature, logp, entropy, value, logits, st);
+}
+
+int vla_debug_force_generic(int mask) {
+    if (mask < 0 || mask > 31) { vla_set_error("force_generic mask %d outside 0..31", mask); return VLA_EINVAL; }
+    g_force_generic = mask;
+    return VLA_OK;
 }
 
 int vla_profile_enable(int on) {

@@ -459,12 +459,6 @@ int launch_loader(bf16_t *out, const bf16_t *q, const bf16_t *kc, const bf16_t *
     return vla_check_launch("attn_prefill");
 }
 
-int shared_keys_enabled() {
-    static int v = -1;
-    if (v < 0) { const char *e = getenv("VLA_ATTN_SHARED"); v = e ? atoi(e) : 1; }
-    return v;
-}
-
 inline int round_up32(int v) { return (v + 31) & ~31; }
 
 }  // namespace
@@ -491,7 +485,7 @@ int try_attention_prefill_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, i
         for (int r = 0; r < ra.R; r++) pairs += (ra.pos0 + r >= ra.full_from) ? nk : ra.pos0 + r + 1;
         return pairs;
     };
-    if (kv.d == 128 && shared_keys_enabled()) {
+    if (kv.d == 128) {
         ProfScope ps("attn_prefill", 4.0 * kv.d * pair_count() * n_items, st);
         // One wave per 32-query block, at most three of them plus the loading wave per workgroup: three such
         // workgroups fit a CU (35 KB LDS, 159 registers), each with two key blocks in flight.  Larger workgroups
@@ -509,19 +503,14 @@ int try_attention_prefill_bf16(bf16_t *out, const bf16_t *q, const KvView &kv, i
     {
         ProfScope ps("v_transpose", 2.0 * n_items * (double)nk * kv.d * 2.0, st);
         dim3 grid(ps_pad / 32, n_items);
-        if (kv.d == 128) v_transpose_kernel<128><<<grid, 256, 0, st>>>(vt, vc, nk, kv.pos_stride, ps_pad);
-        else v_transpose_kernel<64><<<grid, 256, 0, st>>>(vt, vc, nk, kv.pos_stride, ps_pad);
+        v_transpose_kernel<64><<<grid, 256, 0, st>>>(vt, vc, nk, kv.pos_stride, ps_pad);        // (head_dim 64 from here on)
         if ((rc = vla_check_launch("v_transpose"))) return rc;
     }
     {
         // algorithmic flops: 4 * d per (query, visible key) pair
         ProfScope ps("attn_prefill", 4.0 * kv.d * pair_count() * n_items, st);
         dim3 grid((q_blocks + 3) / 4, n_items);
-        if (kv.d == 128)
-            attn_prefill_kernel<128><<<grid, 256, 0, st>>>(out, q, kc, vt, ra.R, ra.pos0, ra.full_from, kv.n_heads,
-                                                          kv.pos_stride, ps_pad, H, q_blocks, out_kb_rows);
-        else
-            attn_prefill_kernel<64><<<grid, 256, 0, st>>>(out, q, kc, vt, ra.R, ra.pos0, ra.full_from, kv.n_heads,
+        attn_prefill_kernel<64><<<grid, 256, 0, st>>>(out, q, kc, vt, ra.R, ra.pos0, ra.full_from, kv.n_heads,
                                                          kv.pos_stride, ps_pad, H, q_blocks, out_kb_rows);
         if ((rc = vla_check_launch("attn_prefill"))) return rc;
     }

@@ -62,6 +62,7 @@ struct DmaGemmParams {
     bf16_t *q_out, *kc, *vc;
     const float2 *table;
     int R, pos0, n_heads, pos_stride, H;
+    int seg0;        // EPI_QKV_ROPE: what the first weight segment is (0 = q, k, v follow; 1 = k, v only)
     int group;
     int splits;      // > 1: K is cut into `splits` equal ranges; item = range * tiles + tile, and range r of an
                      // EPI_STORE launch writes its fp32 partial product to C + r * M * N
@@ -107,7 +108,7 @@ __device__ __forceinline__ void epilogue(f32x4_t (&acc)[8][8], const DmaGemmPara
     if (EPI == EPI_QKV_ROPE) {
         // the wave's 128 columns are one head of q, k or v (head_dim 128)
         const int n0 = tn * BN + wn * 128;
-        const int seg = n0 / p.H, head = (n0 - seg * p.H) >> 7;
+        const int seg_in = n0 / p.H, head = (n0 - seg_in * p.H) >> 7, seg = seg_in + p.seg0;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             const int mblock = m0 + wm * 128 + i * 16;
@@ -568,11 +569,9 @@ template <int EPI>
 int launch_kb(const DmaGemmParams &p, bool kb, hipStream_t st) {
     // The unit-barrier schedule pays for the gate/up projection (3.7 % faster at M = 73728: 10.03 against 10.41 ms);
     // the QKV and down projections run the same with either and the O projection, whose short tiles end in the
-    // heaviest epilogue, 5 % slower.  VLA_GEMM_UB=0 turns it off.
+    // heaviest epilogue, 5 % slower.
     if constexpr (EPI == EPI_SWIGLU) {
-        static int ub = -1;
-        if (ub < 0) { const char *e = getenv("VLA_GEMM_UB"); ub = e ? atoi(e) : 1; }
-        if (kb && ub) return launch<EPI, true, true>(p, st);
+        if (kb) return launch<EPI, true, true>(p, st);
     }
     return kb ? launch<EPI, true>(p, st) : launch<EPI, false>(p, st);
 }
@@ -596,10 +595,8 @@ int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st) {
     p.splits = 1;
     {
         // tile rows per column panel of the walk: 4, except for the QKV projection (1.9 % faster with 2 at
-        // M = 73728: 5.73 against 5.84 ms; the other projections within 0.5 % either way); VLA_GEMM_GROUP overrides
-        static int grp = -1;
-        if (grp < 0) { const char *e = getenv("VLA_GEMM_GROUP"); grp = e ? atoi(e) : 0; }
-        p.group = grp > 0 ? grp : (g.epilogue == EPI_QKV_ROPE ? 2 : 4);
+        // M = 73728: 5.73 against 5.84 ms; the other projections within 0.5 % either way)
+        p.group = g.epilogue == EPI_QKV_ROPE ? 2 : 4;
     }
     p.tiles_m = (g.M + BM - 1) / BM;
     if (g.epilogue == EPI_SWIGLU) {
@@ -611,14 +608,16 @@ int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st) {
     if (g.segN % BN != 0) return 0;
     if (g.epilogue == EPI_QKV_ROPE) {
         const QkvRopeArgs *ra = g.rope;
-        if (!ra || ra->kv->d != 128 || g.n_seg != 3 || g.segN != ra->kv->n_heads * 128) return 0;
+        if (!ra || ra->kv->d != 128 || (g.n_seg != 3 && g.n_seg != 2) || g.segN != ra->kv->n_heads * 128) return 0;
+        if (g.n_seg == 3 && !ra->q_out) return 0;
+        p.seg0 = 3 - g.n_seg;                   // two segments: the k and v projections alone
         p.q_out = (bf16_t *)ra->q_out;
         p.kc = (bf16_t *)ra->kv->k + (size_t)ra->layer * ra->kv->layer_elems;
         p.vc = (bf16_t *)ra->kv->v + (size_t)ra->layer * ra->kv->layer_elems;
         p.table = ra->table;
         p.R = ra->rows->R; p.pos0 = ra->rows->pos0; p.n_heads = ra->kv->n_heads;
         p.pos_stride = ra->kv->pos_stride; p.H = g.segN;
-        p.N = 3 * g.segN;
+        p.N = g.n_seg * g.segN;
         p.tiles_n = p.N / BN;
         return launch_kb<EPI_QKV_ROPE>(p, kb, st);
     }

@@ -269,15 +269,7 @@ int launch_splitk_reduce(int epilogue, void *C, const float *P, int splits, int 
     return vla_check_launch("splitk_reduce");
 }
 
-static int skinny_target_wgs() {
-    static int v = -1;
-    if (v < 0) {
-        const char *e = getenv("VLA_SKINNY_WGS");
-        v = e ? atoi(e) : 512;
-        if (v < 1) v = 1;
-    }
-    return v;
-}
+static int skinny_target_wgs() { return 512; }      // two workgroups per CU keep the weight stream of 256 CUs busy
 
 size_t gemm_skinny_scratch_bytes(int M, int max_n) {
     return (size_t)8 * M * max_n * sizeof(float);     // at most 8 K-splits of an [M, max_n] fp32 panel

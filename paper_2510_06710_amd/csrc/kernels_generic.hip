@@ -228,6 +228,33 @@ __global__ void rope_kv_write_kernel(T *q_out, const float *qkv, const float2 *t
     }
 }
 
+// Rows first .. first + count - 1 of every sequence of X [n_seq * R, H], packed into Xt [n_seq * count, H].
+__global__ void gather_rows_kernel(float *Xt, const float *X, int R, int first, int count, int H) {
+    const int s = blockIdx.x / count, j = blockIdx.x - s * count;
+    const f32x4_t *src = (const f32x4_t *)(X + ((size_t)s * R + first + j) * H);
+    f32x4_t *dst = (f32x4_t *)(Xt + (size_t)blockIdx.x * H);
+    for (int i = threadIdx.x; i < H / 4; i += blockDim.x) dst[i] = src[i];
+}
+
+// Rotary on q alone: qf fp32 [M, H] (row m of sequence s is position table row first + m % count) -> q_out in the
+// storage type.  One thread per (row, head, pair index).
+template <typename T>
+__global__ void rope_q_kernel(T *q_out, const float *qf, const float2 *table, size_t M, int count, int first, int n_heads,
+                              int d, int H) {
+    const int half = d / 2;
+    const size_t total = M * (size_t)n_heads * half;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int i = (int)(idx % half);
+    const int h = (int)((idx / half) % n_heads);
+    const size_t m = idx / ((size_t)half * n_heads);
+    const float2 cs = table[(size_t)(first + (int)(m % count)) * half + i];
+    const size_t o = m * (size_t)H + (size_t)h * d + i;
+    const float a = qf[o], b = qf[o + half];
+    q_out[o] = from_f<T>(a * cs.x - b * cs.y);
+    q_out[o + half] = from_f<T>(b * cs.x + a * cs.y);
+}
+
 // ---------------------------------------------------------------------------------- attention
 // One wave per (sequence, head, new row): scores over the allowed keys into LDS, softmax, then
 // the weighted sum of V rows with each lane owning head dims lane, lane+64, ...
@@ -462,6 +489,21 @@ int launch_rope_kv_write(T *q_out, const float *qkv, const float2 *table, const 
         q_out, qkv, table, kc, vc, ra.n_seq, ra.R, ra.pos0, kv.n_heads, kv.d, kv.pos_stride, H);
     return vla_check_launch("rope_kv_write");
 }
+int launch_gather_rows(float *Xt, const float *X, int n_seq, int R, int first, int count, int H, hipStream_t st) {
+    if (n_seq * count == 0) return 0;
+    ProfScope ps("gather_rows", 0.0, st);
+    gather_rows_kernel<<<n_seq * count, 256, 0, st>>>(Xt, X, R, first, count, H);
+    return vla_check_launch("gather_rows");
+}
+template <typename T>
+int launch_rope_q(T *q_out, const float *qf, const float2 *table, int n_seq, int count, int first, int n_heads, int d, int H,
+                  hipStream_t st) {
+    const size_t M = (size_t)n_seq * count, total = M * n_heads * (d / 2);
+    if (total == 0) return 0;
+    ProfScope ps("rope_q", 0.0, st);
+    rope_q_kernel<T><<<(unsigned)((total + 255) / 256), 256, 0, st>>>(q_out, qf, table, M, count, first, n_heads, d, H);
+    return vla_check_launch("rope_q");
+}
 template <typename T>
 int launch_attention_generic(T *out, const T *q, const KvView &kv, int layer, const RowsArgs &ra,
                              int H, hipStream_t st) {
@@ -522,6 +564,7 @@ int launch_value_head(float *value, const float *h, const float *w, float b, con
                                          const RowsArgs &, int, hipStream_t);                                                        \
     template int launch_attention_generic<T>(T *, const T *, const KvView &, int, const RowsArgs &, int,      \
                                              hipStream_t);                                                    \
+    template int launch_rope_q<T>(T *, const float *, const float2 *, int, int, int, int, int, int, hipStream_t); \
     template int launch_head_sample<T>(const float *, const T *, int, int, float, const float *,              \
                                        const int32_t *, int32_t *, float *, float *, float *, int, int,       \
                                        float *, const T *, int, hipStream_t);

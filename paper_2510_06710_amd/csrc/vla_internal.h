@@ -38,7 +38,7 @@ enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_QKV_ROP
 // Extra arguments of EPI_QKV_ROPE: the QKV projection whose epilogue rotates q and k and writes q to
 // q_out [M, H] and k, v straight into layer `layer` of the KV buffer (head_dim 128 only).
 struct QkvRopeArgs {
-    void *q_out;
+    void *q_out;            // may be NULL when the projection has no q segment (n_seg = 2: k and v only)
     const float2 *table;    // [R][d/2] (cos, sin)
     const KvView *kv;
     int layer;
@@ -93,6 +93,12 @@ int launch_rope_kv_write(T *q_out, const float *qkv, const float2 *table, const 
 template <typename T>
 int launch_attention_generic(T *out, const T *q, const KvView &kv, int layer, const RowsArgs &ra,
                              int H, hipStream_t st);
+// rows first .. first + count - 1 of each of n_seq sequences of R rows, packed
+int launch_gather_rows(float *Xt, const float *X, int n_seq, int R, int first, int count, int H, hipStream_t st);
+// rotary on q alone: qf fp32 [n_seq * count, H]; packed row m sits at table row first + m % count
+template <typename T>
+int launch_rope_q(T *q_out, const float *qf, const float2 *table, int n_seq, int count, int first, int n_heads, int d, int H,
+                  hipStream_t st);
 // Row i of h produces output index o = i * out_stride + out_off: bins_out[o], logp[o], ent[o],
 // logits[o * 256 ..]; it reads gumbel[o * 256 ..] (if any) and given_bins[o] (if any: then the
 // log-prob is that of the given bin and nothing is sampled).  If X_next is not NULL the embedding
@@ -154,7 +160,6 @@ __device__ __forceinline__ void vla_tile_of_block(int pid, int tiles_m, int tile
 
 // ---- gfx950 fast paths (bf16, aligned shapes); each returns 1 if it handled the call, 0 if the
 // shape is outside what it supports (caller then uses the generic kernel), <0 on launch error ----
-int try_gemm_bf16_mfma(const GemmArgs &g, hipStream_t st);
 int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st);
 int try_gemm_bf16_dma_splitk(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st);
 int launch_weight_kblock(bf16_t *dst, const bf16_t *src, int N, int K, hipStream_t st);
@@ -168,7 +173,6 @@ int try_reduce_residual_rmsnorm_bf16(bf16_t *out, float *X, const float *P, int 
 // kb_rows = 0: row-major output [M, H]; else k-blocked [H / 32][kb_rows][32]
 int try_rmsnorm_bf16(bf16_t *out, const float *X, const float *gain, int M, int H, float eps, int kb_rows, hipStream_t st);
 int try_gemm_bf16_skinny(const GemmArgs &g, void *scratch, hipStream_t st);
-int try_gemm_bf16_mfma_splitk(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st);
 int try_gemm_bf16_mid(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st);
 int launch_splitk_reduce(int epilogue, void *C, const float *P, int splits, int M, int N, hipStream_t st);
 size_t gemm_skinny_scratch_bytes(int M, int max_n);

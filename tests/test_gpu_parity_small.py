@@ -273,3 +273,31 @@ def test_prepacked_weights_give_bit_identical_results():
         outs.append([x.cpu() for x in (h, v, b, lp, en, z, rlp, ren, rv, rz)])
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4 | 8, 16, 31])
+def test_generic_kernels_on_a_shape_that_has_fast_paths(mask):
+    """vla_debug_force_generic sends the chosen steps of a bf16 model to the shape-generic kernels (large GEMM, decode
+    GEMM, attention, rotary / norm, everything): the stated bar holds either way."""
+    from paper_2510_06710_amd import binding as vb
+    wl = vi.scaled(ALIGNED, batch=130)
+    ref = oracle_rollout(wl, 10, operand_dtype="bf16", envs=8)
+    vb.vla_debug_force_generic(mask)
+    try:
+        case = GpuCase(wl, 10)
+        gpu = case.rollout()
+        rc = case.recompute(ref["bins"], envs=8)
+    finally:
+        vb.vla_debug_force_generic(0)
+    _print(f"forced generic mask {mask}", compare_rollout({k: v[:8] for k, v in gpu.items()}, ref, "bf16", autoregressive=True))
+    compare_recompute(rc, oracle_recompute(wl, 10, ref["bins"], envs=8, operand_dtype="bf16"), "bf16")
+
+
+def test_generic_attention_with_more_keys_than_the_default_lds_limit():
+    """4,300 keys: the generic attention kernel keeps one score per visible key and wave in LDS, 69 KB here, above
+    the 64 KB a kernel gets without asking."""
+    wl = vi.Workload("long", vi.ModelShape(n_layers=1, hidden=64, n_heads=2, ffn=64, vocab=300, dtype="f32"),
+                     batch=1, n_patches=4290, n_instr=8, n_action=2)
+    ref = oracle_rollout(wl, 13)
+    gpu = GpuCase(wl, 13).rollout()
+    _print("4,300 keys, generic attention", compare_rollout(gpu, ref, "f32", autoregressive=True))

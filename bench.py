@@ -160,6 +160,59 @@ def bench_recompute(args, wl, torch, vi, vb, Rollout):
     print(json.dumps(out))
 
 
+def bench_backward(args, wl, torch, vi, vb, Rollout):
+    """LoRA-gradient pass (vla_logprob_backward) over a sample of the recompute workload's stored rollouts: a step is
+    one call over `--backward-rollouts` rollouts in micro-batches of `--backward-micro-batch`.  Reports rollouts/s and
+    the rate of the projection flops it executes (forward twice -- once kept, once recomputed per layer -- and the
+    input-gradient products once), against the bf16 MFMA peak."""
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    N, mb, rank = args.backward_rollouts, args.backward_micro_batch, args.lora_rank
+    S, A, shape = wl.prefix, wl.n_action, wl.shape
+    wl_n = vi.scaled(wl, batch=N)
+    synth = vi.SynthModel(shape, 0, device=dev)
+    run = Rollout(synth, mb, S + A, device=dev, value_b=vi.VALUE_BIAS, prepack=False)
+    patch, ids = vi.observation(wl_n, 0, device=dev)
+    bins = vi.stored_bins(wl_n, 0, device=dev)
+    g = torch.Generator(device="cpu").manual_seed(1)
+    coef = torch.randn(N, A, generator=g).to(dev)
+    dims = {"q": (shape.hidden, shape.hidden), "k": (shape.hidden, shape.hidden), "v": (shape.hidden, shape.hidden),
+            "o": (shape.hidden, shape.hidden), "gate": (shape.ffn, shape.hidden), "up": (shape.ffn, shape.hidden),
+            "down": (shape.hidden, shape.ffn)}
+    lora = [{p: ((0.05 * torch.randn(rank, i, generator=g)).to(shape.torch_dtype).to(dev),
+                 (0.05 * torch.randn(o, rank, generator=g)).to(shape.torch_dtype).to(dev)) for p, (o, i) in dims.items()}
+            for _ in range(shape.n_layers)]
+    stream = torch.cuda.current_stream()
+
+    def step():
+        return run.backward(patch, ids, bins, coef, A, lora, rank, 0.5, wl.mode, None, wl.temperature, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    vb.lib().vla_profile_enable(1)
+    step()
+    torch.cuda.synchronize()
+    prof = profile_report(vb)
+    vb.lib().vla_profile_enable(0)
+    rows = S + A - 1 if wl.mode == 0 else S + A
+    flops = 3.0 * N * rows * 2.0 * shape.layer_params * shape.n_layers
+    out = {"metric": "stored rollouts/sec, LoRA-gradient pass of the log-prob recompute (7B shape)", "value": N / (ms * 1e-3),
+           "unit": "rollouts/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+           "config": {"workload": wl.name + " (backward)", "rollouts": N, "micro_batch": mb, "rows_per_rollout": rows,
+                      "lora_rank": rank, "layers": shape.n_layers, "hidden": shape.hidden},
+           "phases": {"projection_TFLOPs": flops / (ms * 1e-3) / 1e12, "mfma_frac": flops / (ms * 1e-3) / 1e12 / MI355X_BF16_TFLOPS},
+           "kernels": {k: {"n": v["count"], "ms": round(v["ms"], 3)} for k, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"])}}
+    print(json.dumps(out))
+
+
 def bench_pipeline(args, wl, torch, vb, run, patch, ids, gumbel, slot):
     """t_1 vs t_2 of section IV-A on one GPU: Generation on the GPU, a CPU-parallel stub simulator that
     takes sim_ms_per_env * (environments in the sub-batch) per step on the host."""
@@ -215,6 +268,11 @@ def main():
     ap.add_argument("--sim-ms-per-env", type=float, default=None,
                     help="--pipeline: stub simulator time per environment and step (default: the measured "
                          "generation time per environment, i.e. a 1:1 Generation:Simulator ratio)")
+    ap.add_argument("--backward", action="store_true",
+                    help="recompute workload only: time vla_logprob_backward (LoRA gradients) instead of the forward recompute")
+    ap.add_argument("--backward-rollouts", type=int, default=64)
+    ap.add_argument("--backward-micro-batch", type=int, default=32)
+    ap.add_argument("--lora-rank", type=int, default=32)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one 1 GiB plain copy kernel (reference for rocprofv3 --pmc traffic counters)")
     args = ap.parse_args()
@@ -231,7 +289,10 @@ def main():
     wl = vi.WORKLOADS[args.workload]
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     if wl.kind == "recompute":
-        bench_recompute(args, wl, torch, vi, vb, Rollout)
+        if args.backward:
+            bench_backward(args, wl, torch, vi, vb, Rollout)
+        else:
+            bench_recompute(args, wl, torch, vi, vb, Rollout)
         return
     dev = "cuda:0"
     torch.cuda.set_device(0)

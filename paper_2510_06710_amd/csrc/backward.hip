@@ -123,8 +123,9 @@ __global__ void __launch_bounds__(256) bgemm_kernel(BgemmArgs g) {
 }
 
 template <typename TA, typename TB>
-int bgemm(const BgemmArgs &g, int batch, hipStream_t st) {
+int bgemm(const BgemmArgs &g, int batch, hipStream_t st, const char *label = "bw_attention_tiles") {
     if (g.m <= 0 || g.n <= 0 || batch <= 0) return 0;
+    ProfScope ps(label, 2.0 * g.m * g.n * (double)g.k * batch * (g.tri ? 0.5 : 1.0), st);
     dim3 grid((g.n + 63) / 64, (g.m + 63) / 64, batch);
     bgemm_kernel<TA, TB><<<grid, 256, 0, st>>>(g);
     return vla_check_launch("bgemm");
@@ -310,12 +311,69 @@ __global__ void __launch_bounds__(256) transpose_kernel(T *Wt, const T *W, int N
         if (k0 + r < K && n0 + tx < N) Wt[(size_t)(k0 + r) * ldt + col0 + n0 + tx] = tile[tx][r];
 }
 
+// dst[c][r] = src[r][c] for r < rows, c < cols (src row stride ld_src, storage or fp32 source, rounded to the storage
+// type), and 0 for rows <= r < ld_dst: the operand of a GEMM that contracts over the rows of src, whose K extent is
+// padded to what the kernels accept.  32 x 32 tiles through LDS.
+template <typename T, typename TS>
+__global__ void __launch_bounds__(256) transpose_pad_kernel(T *dst, const TS *src, int rows, int cols, int ld_src, int ld_dst) {
+    __shared__ float tile[32][33];
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32, tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int r = ty; r < 32; r += 8)
+        tile[r][tx] = (r0 + r < rows && c0 + tx < cols) ? ld(src + (size_t)(r0 + r) * ld_src + c0 + tx) : 0.f;
+    __syncthreads();
+    for (int c = ty; c < 32; c += 8)
+        if (c0 + c < cols && r0 + tx < ld_dst) dst[(size_t)(c0 + c) * ld_dst + r0 + tx] = cvt<T>(tile[tx][c]);
+}
+
+// Stacked, zero-padded LoRA factors of a group of n_p projections that share their input (q / k / v; gate / up) as
+// the 256-row weight operands of two GEMMs:  Wa [256, in]: row p * rank + j = A_p[j];  Wb [256, n_p * out]: row
+// p * rank + j holds B_p[:, j] in columns p * out .. (p + 1) * out and zeros elsewhere (block diagonal), so that
+// X Wa^T = [X A_0^T | X A_1^T | ..] and dY Wb^T = [dY_0 B_0 | dY_1 B_1 | ..] for dY = [dY_0 | dY_1 | ..].
+struct LoraGroup { const void *a[3], *b[3]; float *da[3], *db[3]; int n_p, in, out; };
+template <typename T>
+__global__ void pack_factors_kernel(T *Wa, T *Wb, LoraGroup g, int rank) {
+    const size_t na = (size_t)256 * g.in, nb = (size_t)256 * g.n_p * g.out;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < na + nb; i += (size_t)gridDim.x * 256) {
+        if (i < na) {
+            const int row = (int)(i / g.in), c = (int)(i - (size_t)row * g.in), p = row / rank, j = row - p * rank;
+            Wa[i] = p < g.n_p ? ((const T *)g.a[p])[(size_t)j * g.in + c] : cvt<T>(0.f);
+        } else {
+            const size_t k = i - na;
+            const int w = g.n_p * g.out, row = (int)(k / w), c = (int)(k - (size_t)row * w), p = row / rank, j = row - p * rank;
+            const bool in_block = p < g.n_p && c >= p * g.out && c < (p + 1) * g.out;
+            Wb[k] = in_block ? ((const T *)g.b[p])[(size_t)(c - p * g.out) * rank + j] : cvt<T>(0.f);
+        }
+    }
+}
+
+// dB_p[o][j] (+)= scale * Cb[p * out + o][p * rank + j];  dA_p[j][i] (+)= scale * Ca[i][p * rank + j]
+__global__ void unpack_grads_kernel(LoraGroup g, const float *Cb, const float *Ca, int rank, float scale, int accumulate) {
+    const size_t nb = (size_t)g.n_p * g.out * rank, na = (size_t)g.n_p * rank * g.in;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nb + na; i += (size_t)gridDim.x * 256) {
+        if (i < nb) {
+            const int p = (int)(i / ((size_t)g.out * rank));
+            const size_t k = i - (size_t)p * g.out * rank;
+            const int o = (int)(k / rank), j = (int)(k - (size_t)o * rank);
+            const float v = scale * Cb[((size_t)p * g.out + o) * 256 + p * rank + j];
+            g.db[p][k] = accumulate ? g.db[p][k] + v : v;
+        } else {
+            const size_t q = i - nb;
+            const int p = (int)(q / ((size_t)rank * g.in));
+            const size_t k = q - (size_t)p * rank * g.in;
+            const int j = (int)(k / g.in), c = (int)(k - (size_t)j * g.in);
+            const float v = scale * Ca[(size_t)c * 256 + p * rank + j];
+            g.da[p][k] = accumulate ? g.da[p][k] + v : v;
+        }
+    }
+}
+
 inline unsigned blocks_for(size_t n) { size_t b = (n + 255) / 256; return (unsigned)(b > 65535 * 16 ? 65535 * 16 : (b ? b : 1)); }
 
 // ---------------------------------------------------------------------------------------------- workspace
 struct BwSpace {
-    float *X, *dX, *ckpt, *QKV, *GU, *Tmp, *SP, *dP, *U, *V;
-    void *Nrm, *Nrm2, *AO, *ACT, *QKVr, *dGU, *dXb, *dQKVb, *Wt;
+    float *X, *dX, *ckpt, *QKV, *GU, *Tmp, *SP, *dP, *UV, *Cab;
+    void *Nrm, *Nrm2, *AO, *ACT, *QKVr, *dGU, *dXb, *dQKVb, *Wt, *Wa, *Wb, *UVt, *Xt, *dYt;
+    int kp;          // rows of a micro-batch rounded up to what a GEMM's K extent accepts
     float2 *rope;
     int a_rows;
     size_t total;
@@ -323,7 +381,7 @@ struct BwSpace {
 
 size_t al(size_t v) { return (v + 255) & ~(size_t)255; }
 
-BwSpace plan_bw(const vla_config &c, char *base, int mb, int R, int rank) {
+BwSpace plan_bw(const vla_config &c, char *base, int mb, int R, int /*rank*/) {
     BwSpace w;
     size_t off = 0;
     const size_t es = c.dtype == VLA_DTYPE_F32 ? 4 : 2, M = (size_t)mb * R, H = c.hidden, F = c.ffn, L = c.n_layers;
@@ -338,8 +396,17 @@ BwSpace plan_bw(const vla_config &c, char *base, int mb, int R, int rank) {
     w.Tmp = (float *)take(M * (F > 3 * H ? F : 3 * H) * 4);
     w.SP = (float *)take((size_t)mb * c.n_heads * R * R * 4);
     w.dP = (float *)take((size_t)mb * c.n_heads * R * R * 4);
-    w.U = (float *)take(M * rank * 4);
-    w.V = (float *)take(M * rank * 4);
+    // LoRA products (see lora_group): U | V [2][M, 256] fp32, their rounded transposes [2][256 + pad, kp], the stacked
+    // factors, the transposed activations / output gradients and the two [dim, 256] results
+    const size_t kp = M < 256 ? 256 : (M + 63) / 64 * 64, wide = 3 * H > 2 * F ? 3 * H : 2 * F, dim_p = (wide + 255) / 256 * 256 + VLA_KB_PAD_ROWS;
+    w.kp = (int)kp;
+    w.UV = (float *)take(2 * M * 256 * 4);
+    w.Cab = (float *)take(2 * dim_p * 256 * 4);
+    w.Wa = take((size_t)(256 + VLA_KB_PAD_ROWS) * (H > F ? H : F) * es);
+    w.Wb = take((size_t)(256 + VLA_KB_PAD_ROWS) * wide * es);
+    w.UVt = take(2 * (size_t)(256 + VLA_KB_PAD_ROWS) * kp * es);
+    w.Xt = take(dim_p * kp * es);
+    w.dYt = take(dim_p * kp * es);
     w.Nrm = take(Mp * H * es);
     w.Nrm2 = take(Mp * H * es);
     w.AO = take(Mp * H * es);
@@ -424,25 +491,45 @@ struct Backward {
     }
     void add_kernel_launch(float *x, const float *y, size_t nel);
 
-    // dA [rank, in] and dB [out, rank] of one projection: X [M, in] (storage type, row stride ldx), dY [M, out] (ldy)
-    int lora_grads(const vla_lora_factor &f, const vla_lora_grad &gr, const void *X, int ldx, int in, const void *dY, int ldy, int out,
-                   bool first) {
+    // LoRA gradients of a group of projections that share their input X [M, in] (storage type, contiguous rows) and
+    // whose output gradients sit side by side in dY [M, n_p * out]: four GEMMs on the MFMA path where the shape allows,
+    //   U = X Wa^T, V = dY Wb^T                                   [M, 256]   (Wa, Wb: the stacked, zero-padded factors)
+    //   Cb = dY^T U = (dY^T)[n_p * out, kp] . (U^T)[256, kp]^T    -> dB_p = scale * its block p
+    //   Ca = X^T V  = (X^T)[in, kp] . (V^T)[256, kp]^T            -> dA_p = scale * its block p, transposed
+    // with U, V rounded to the storage type like every GEMM operand and the contraction over the rows padded with zeros
+    // to kp.  Needs n_p * rank <= 256.
+    int gemm_rows(const void *A, const void *W, float *C, int rows, int a_rows, int K) {
+        GemmArgs g{};
+        g.A = A; g.W[0] = W; g.n_seg = 1; g.segN = 256; g.C = C; g.M = rows; g.K = K; g.epilogue = EPI_STORE; g.a_rows = a_rows;
+        return vla_gemm_dispatch(c, g, st);
+    }
+    int lora_group(LoraGroup lg, const void *X, const void *dY, bool first) {
+        const int in = lg.in, wout = lg.n_p * lg.out, kp = ws.kp;
+        const int pad_rows = 256 + VLA_KB_PAD_ROWS;
+        float *U = ws.UV, *V = ws.UV + (size_t)M * 256, *Cb = ws.Cab, *Ca = ws.Cab + (size_t)((wout + 255) / 256 * 256 + VLA_KB_PAD_ROWS) * 256;
+        T *Ut = (T *)ws.UVt, *Vt = Ut + (size_t)pad_rows * kp;
         int rc;
-        BgemmArgs g{};
-        g.inner = 1; g.accumulate = 0; g.alpha = 1.0f;
-        // U = X A^T  [M, rank]
-        g.A = X; g.lda = ldx; g.transA = 0; g.B = f.a; g.ldb = in; g.transB = 1; g.C = ws.U; g.ldc = rank; g.m = M; g.n = rank; g.k = in;
-        if ((rc = bgemm<T, T>(g, 1, st))) return rc;
-        // V = dY B   [M, rank]
-        g.A = dY; g.lda = ldy; g.B = f.b; g.ldb = rank; g.transB = 0; g.C = ws.V; g.k = out;
-        if ((rc = bgemm<T, T>(g, 1, st))) return rc;
-        // dB (+)= scale dY^T U  [out, rank]
-        g.accumulate = first ? 0 : 1; g.alpha = scale;
-        g.A = dY; g.lda = ldy; g.transA = 1; g.B = ws.U; g.ldb = rank; g.transB = 0; g.C = gr.db; g.ldc = rank; g.m = out; g.n = rank; g.k = M;
-        if ((rc = bgemm<T, float>(g, 1, st))) return rc;
-        // dA (+)= scale V^T X   [rank, in]
-        g.A = ws.V; g.lda = rank; g.transA = 1; g.B = X; g.ldb = ldx; g.transB = 0; g.C = gr.da; g.ldc = in; g.m = rank; g.n = in; g.k = M;
-        return bgemm<float, T>(g, 1, st);
+        pack_factors_kernel<T><<<blocks_for((size_t)256 * (in + wout)), 256, 0, st>>>((T *)ws.Wa, (T *)ws.Wb, lg, rank);
+        if ((rc = vla_check_launch("pack_factors"))) return rc;
+        if ((rc = gemm_rows(X, ws.Wa, U, M, ws.a_rows, in)) || (rc = gemm_rows(dY, ws.Wb, V, M, ws.a_rows, wout))) return rc;
+        auto tp = [&](auto *dst, auto *src, int rows, int cols, int ld_src) {
+            ProfScope ps("bw_transpose", 0.0, st);
+            dim3 grid((cols + 31) / 32, (kp + 31) / 32);
+            transpose_pad_kernel<<<grid, 256, 0, st>>>(dst, src, rows, cols, ld_src, kp);
+            return vla_check_launch("transpose_pad");
+        };
+        if ((rc = tp(Ut, (const float *)U, M, 256, 256)) || (rc = tp(Vt, (const float *)V, M, 256, 256))) return rc;
+        if ((rc = tp((T *)ws.Xt, (const T *)X, M, in, in)) || (rc = tp((T *)ws.dYt, (const T *)dY, M, wout, wout))) return rc;
+        const int rows_b = (wout + 255) / 256 * 256 + VLA_KB_PAD_ROWS, rows_a = (in + 255) / 256 * 256 + VLA_KB_PAD_ROWS;
+        if ((rc = gemm_rows(ws.dYt, Ut, Cb, wout, rows_b, kp)) || (rc = gemm_rows(ws.Xt, Vt, Ca, in, rows_a, kp))) return rc;
+        unpack_grads_kernel<<<blocks_for((size_t)lg.n_p * rank * (lg.out + in)), 256, 0, st>>>(lg, Cb, Ca, rank, scale, first ? 0 : 1);
+        return vla_check_launch("unpack_grads");
+    }
+    static LoraGroup group_of(int n_p, const vla_lora_factor *f, const vla_lora_grad *g, int in, int out) {
+        LoraGroup lg{};
+        lg.n_p = n_p; lg.in = in; lg.out = out;
+        for (int p = 0; p < n_p; p++) { lg.a[p] = f[p].a; lg.b[p] = f[p].b; lg.da[p] = g[p].da; lg.db[p] = g[p].db; }
+        return lg;
     }
 
     // Backward of layer l: on entry ws.dX = d L / d x_out; on exit d L / d x_in.  x_in is ckpt[l].
@@ -459,20 +546,19 @@ struct Backward {
         if ((rc = layer_forward(l, x_mid))) return rc;
         // ---- down projection and SwiGLU
         if ((rc = cast(ws.dXb, ws.dX, H, H, H))) return rc;
-        if ((rc = lora_grads(lo.down, gr.down, ws.ACT, F, F, ws.dXb, H, H, first))) return rc;
+        if ((rc = lora_group(group_of(1, &lo.down, &gr.down, F, H), ws.ACT, ws.dXb, first))) return rc;
         if ((rc = transpose(lw.w_down, H, F, H, 0))) return rc;                               // [F, H]
         if ((rc = gemm(ws.dXb, ws.Wt, nullptr, nullptr, 1, F, ws.Tmp, H))) return rc;          // d act [M, F]
         swiglu_bwd_kernel<T><<<blocks_for((size_t)M * F), 256, 0, st>>>((T *)ws.dGU, ws.Tmp, ws.GU, (size_t)M, F);
         if ((rc = vla_check_launch("swiglu_bwd"))) return rc;
-        if ((rc = lora_grads(lo.gate, gr.gate, ws.Nrm2, H, H, ws.dGU, 2 * F, F, first))) return rc;
-        if ((rc = lora_grads(lo.up, gr.up, ws.Nrm2, H, H, (const T *)ws.dGU + F, 2 * F, F, first))) return rc;
+        if ((rc = lora_group(group_of(2, &lo.gate, &gr.gate, H, F), ws.Nrm2, ws.dGU, first))) return rc;   // gate, up adjacent in the structs
         if ((rc = transpose(lw.w_gate, F, H, 2 * F, 0)) || (rc = transpose(lw.w_up, F, H, 2 * F, F))) return rc;   // [H, 2F]
         if ((rc = gemm(ws.dGU, ws.Wt, nullptr, nullptr, 1, H, ws.Tmp, 2 * F))) return rc;      // d n2 [M, H]
         rmsnorm_bwd_kernel<<<M, 256, 0, st>>>(ws.dX, x_mid, (const float *)lw.ffn_norm, ws.Tmp, H, c.rms_eps);
         if ((rc = vla_check_launch("rmsnorm_bwd"))) return rc;
         // ---- O projection and attention (ws.dX is now d L / d x_mid)
         if ((rc = cast(ws.dXb, ws.dX, H, H, H))) return rc;
-        if ((rc = lora_grads(lo.o, gr.o, ws.AO, H, H, ws.dXb, H, H, first))) return rc;
+        if ((rc = lora_group(group_of(1, &lo.o, &gr.o, H, H), ws.AO, ws.dXb, first))) return rc;
         if ((rc = transpose(lw.wo, H, H, H, 0))) return rc;
         float *d_ao = ws.GU;                         // [M, H] fp32; the gate / up projection is no longer needed
         if ((rc = gemm(ws.dXb, ws.Wt, nullptr, nullptr, 1, H, d_ao, H))) return rc;
@@ -491,10 +577,7 @@ struct Backward {
         rope_rows_kernel<T><<<blocks_for((size_t)M * 3 * (H / 2)), 256, 0, st>>>((T *)ws.dQKVb, dqkv, ws.rope, (size_t)M, R, H, d, -1.0f);
         if ((rc = vla_check_launch("rope_rows (transpose)"))) return rc;
         // ---- Q / K / V projections and the attention norm
-        const T *dq = (const T *)ws.dQKVb;
-        if ((rc = lora_grads(lo.q, gr.q, ws.Nrm, H, H, dq, 3 * H, H, first))) return rc;
-        if ((rc = lora_grads(lo.k, gr.k, ws.Nrm, H, H, dq + H, 3 * H, H, first))) return rc;
-        if ((rc = lora_grads(lo.v, gr.v, ws.Nrm, H, H, dq + 2 * H, 3 * H, H, first))) return rc;
+        if ((rc = lora_group(group_of(3, &lo.q, &gr.q, H, H), ws.Nrm, ws.dQKVb, first))) return rc;       // q, k, v adjacent
         if ((rc = transpose(lw.wq, H, H, 3 * H, 0)) || (rc = transpose(lw.wk, H, H, 3 * H, H)) || (rc = transpose(lw.wv, H, H, 3 * H, 2 * H))) return rc;
         if ((rc = gemm(ws.dQKVb, ws.Wt, nullptr, nullptr, 1, H, ws.GU, 3 * H))) return rc;     // d n [M, H]
         rmsnorm_bwd_kernel<<<M, 256, 0, st>>>(ws.dX, x_in, (const float *)lw.attn_norm, ws.GU, H, c.rms_eps);
@@ -587,6 +670,7 @@ int vla_logprob_backward(vla_model *m, void *ws, size_t ws_bytes, const void *pa
     if (R > c.max_seq) { vla_set_error("rows per rollout %d exceed max_seq %d", R, c.max_seq); return VLA_ESHAPE; }
     const int mb = bw_micro_batch(c, N);
     if ((size_t)mb * R * (size_t)(c.ffn > 3 * c.hidden ? 2 * c.ffn : 3 * c.hidden) * 4 >= ((size_t)1 << 40)) { vla_set_error("micro-batch too large"); return VLA_ESHAPE; }
+    if (3 * rank > 256) { vla_set_error("rank %d unsupported (at most 85: three stacked factors fill 256 rows)", rank); return VLA_ESHAPE; }
     if (int rc = vla_check_rows_per_pass(c, mb, R)) return rc;
     const size_t need = plan_bw(c, nullptr, mb, R, rank).total;
     if (ws_bytes < need) { vla_set_error("workspace %zu bytes, need %zu", ws_bytes, need); return VLA_EWORKSPACE; }

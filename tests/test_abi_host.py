@@ -132,3 +132,35 @@ def test_hot_calls_reject_bad_arguments_without_a_device():
     assert L.vla_logprob_recompute(*r(mode=1)) == vb.VLA_EINVAL
     assert "slot_embed" in vb.vla_last_error()
     vb.vla_destroy(h)
+
+
+def test_backward_rejects_bad_arguments_without_a_device():
+    cfg = vb.make_config(vi.TINY, 8, 80)
+    h, keep = fake_model(cfg)
+    L = vb.lib()
+    p = C.c_void_p(0x1000)
+    big = 1 << 40
+    n_layers = cfg.n_layers
+    lora = (vb.vla_lora_layer * n_layers)()
+    grads = (vb.vla_lora_layer_grads * n_layers)()
+    for l in range(n_layers):
+        for name in vb.LORA_PROJECTIONS:
+            f, g = getattr(lora[l], name), getattr(grads[l], name)
+            f.a = f.b = g.da = g.db = 0x1000
+    b = lambda **k: [h, p, k.get("ws", big), p, p, k.get("bins", p), k.get("coef", p), k.get("N", 4), 48, 16, k.get("A", 7),
+                     k.get("mode", 0), None, k.get("tau", 1.0), k.get("rank", 8), 0.5, k.get("lora", lora), grads, None, None]
+    assert L.vla_logprob_backward(*b(coef=None)) == vb.VLA_EINVAL
+    assert L.vla_logprob_backward(*b(lora=None)) == vb.VLA_EINVAL
+    assert L.vla_logprob_backward(*b(tau=0.0)) == vb.VLA_EINVAL
+    assert L.vla_logprob_backward(*b(rank=0)) == vb.VLA_EINVAL
+    assert L.vla_logprob_backward(*b(mode=1)) == vb.VLA_EINVAL           # slot_embed missing
+    assert L.vla_logprob_backward(*b(A=30)) == vb.VLA_ESHAPE             # 64 + 30 - 1 rows > max_seq 80
+    assert L.vla_logprob_backward(*b(rank=100)) == vb.VLA_ESHAPE         # three stacked factors exceed 256 rows
+    assert L.vla_logprob_backward(*b(ws=100)) == vb.VLA_EWORKSPACE
+    lora[1].gate.b = None
+    assert L.vla_logprob_backward(*b()) == vb.VLA_EINVAL and "layer 1" in vb.vla_last_error()
+    assert vb.vla_backward_workspace_bytes(cfg, 4, 64, 7, 8) > 4 * 70 * 256 * 4 * cfg.n_layers
+    with pytest.raises(vb.VlaError):
+        vb.vla_backward_workspace_bytes(cfg, 4, 64, 7, 0)
+    assert L.vla_debug_force_generic(32) == vb.VLA_EINVAL and L.vla_debug_force_generic(0) == vb.VLA_OK
+    vb.vla_destroy(h)

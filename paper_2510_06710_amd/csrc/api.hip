@@ -231,6 +231,8 @@ static int run_gemm(const vla_config &c, GemmArgs g, void *skinny_scratch, hipSt
             if (r == 0) r = try_gemm_bf16_skinny(g, skinny_scratch, st);
         }
         if (r != 0) return r < 0 ? r : 0;
+        if (g.split_scratch && !(force_generic() & 1)) r = try_gemm_bf16_dma_splitk_rows(g, g.split_scratch, g.split_scratch_bytes, st);
+        if (r != 0) return r < 0 ? r : 0;
         r = (force_generic() & 1) ? 0 : try_gemm_bf16_large(g, st);
         if (r != 0) return r < 0 ? r : 0;
     }
@@ -367,7 +369,7 @@ static int run_last_layer_tail(const vla_model *m, const Workspace &ws, const Ro
 // is run in its tail form and the result of those rows is in ws.tX (packed), not in ws.X.
 template <typename T>
 static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &ra, const KvView &kv,
-                      bool kv_single_layer, hipStream_t st, const TailSpec *tail = nullptr) {
+                      bool kv_single_layer, hipStream_t st, const TailSpec *tail = nullptr, float *keep = nullptr) {
     const vla_config &c = m->cfg;
     int H = c.hidden, F = c.ffn, M = ra.n_seq * ra.R, d = H / c.n_heads, rc;
     if ((rc = launch_rope_table(ws.rope, ra.R, ra.pos0, d, c.rope_theta, st))) return rc;
@@ -386,6 +388,11 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
     for (int l = 0; l < c.n_layers; l++) {
         const vla_layer_weights &lw = m->layers[l];
         int kl = kv_single_layer ? 0 : l;
+        // keep: the caller wants the residual stream at the input of every layer
+        if (keep && hipMemcpyAsync(keep + (size_t)l * M * H, ws.X, (size_t)M * H * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) {
+            vla_set_error("copy of the residual stream failed");
+            return VLA_EHIP;
+        }
         if (tail_form && l == c.n_layers - 1) return run_last_layer_tail<T>(m, ws, ra, kv, l, kl, *tail, kb, st);
         if (kb) {
             if ((rc = run_layer_kblocked(m, ws, ra, kv, l, kl, st))) return rc;
@@ -570,6 +577,37 @@ static int recompute_impl(vla_model *m, void *wsbuf, const void *patch, const in
         }
     }
     return 0;
+}
+
+size_t vla_forward_streams_bytes(const vla_config &c, int n_max, int R) {
+    return plan_workspace(c, nullptr, n_max, R, R, 0, true, 0).total;
+}
+
+template <typename T>
+static int forward_streams_impl(vla_model *m, void *fw_ws, int n_max, const void *patch, const int32_t *ids, const int32_t *bins, int n,
+                                int P, int T_, int A, int mode, const void *slot_embed, float *keep, const float **x_final, hipStream_t st) {
+    const vla_config &c = m->cfg;
+    const int S = P + T_, H = c.hidden, R = (mode == VLA_MODE_AR) ? S + A - 1 : S + A;
+    int rc;
+    Workspace ws = plan_workspace(c, (char *)fw_ws, n_max, R, R, 0, true, 0);
+    if ((rc = launch_embed_prefix<T>(ws.X, (const T *)patch, ids, (const T *)m->w.embed, n, P, T_, R, H, c.vocab, st))) return rc;
+    if (mode == VLA_MODE_AR) {
+        if ((rc = launch_embed_tokens<T>(ws.X, bins, A, A - 1, (const T *)m->w.embed, n, R, S, H, c.vocab, st))) return rc;
+    } else if ((rc = launch_embed_slots<T>(ws.X, (const T *)slot_embed, n, A, R, S, H, st))) return rc;
+    RowsArgs ra{n, R, 0, (mode == VLA_MODE_AR) ? 0x7fffffff : S};
+    KvView kv;
+    kv.layer_elems = kv_layer_elems(c, n_max);
+    kv.k = ws.kvs_k; kv.v = ws.kvs_v; kv.n_seq = n; kv.n_heads = c.n_heads; kv.d = H / c.n_heads; kv.pos_stride = c.max_seq;
+    if ((rc = run_layers<T>(m, ws, ra, kv, true, st, nullptr, keep))) return rc;
+    *x_final = ws.X;
+    return 0;
+}
+
+int vla_forward_streams(vla_model *m, void *fw_ws, int n_max, const void *patch, const int32_t *ids, const int32_t *bins, int n,
+                        int P, int T, int A, int mode, const void *slot_embed, float *keep, const float **x_final, hipStream_t st) {
+    return m->cfg.dtype == VLA_DTYPE_F32
+               ? forward_streams_impl<float>(m, fw_ws, n_max, patch, ids, bins, n, P, T, A, mode, slot_embed, keep, x_final, st)
+               : forward_streams_impl<bf16_t>(m, fw_ws, n_max, patch, ids, bins, n, P, T, A, mode, slot_embed, keep, x_final, st);
 }
 
 // ------------------------------------------------------------------------------------------ C ABI

@@ -2,16 +2,18 @@
 // factors of the seven projections of every decoder layer (the policy update of appendix I-B / I-C differentiates
 // the clipped surrogate through rho = exp(logp - logp_old) only; LoRA adapters: section IV-B.2).
 //
-// Structure.  Stored rollouts are processed in micro-batches.  For one micro-batch: (1) a forward pass that keeps the
-// residual stream at the input of every layer (fp32 [layers][rows, H]) and ends in the head, which also returns logp;
-// (2) the head's backward puts d L / d x on the rows that predict action tokens; (3) layers in reverse: the layer's
-// forward is run again from its kept input (same kernels, same values), then the chain rule walks back through the
+// Structure.  Stored rollouts are processed in micro-batches.  For one micro-batch: (1) the forward pass of the
+// recompute (its own fused kernels), keeping the residual stream at the input of every layer (fp32 [layers][rows, H]),
+// and the head, which also returns logp; (2) the head's backward puts d L / d x on the rows that predict action
+// tokens; (3) layers in reverse: the layer's forward is run again from its kept input, this time with unfused
+// kernels that leave every intermediate the chain rule needs, then the chain rule walks back through the
 // down projection, SwiGLU, gate / up, the FFN norm, the O projection, attention, the rotation, Q / K / V and the
 // attention norm.  Every large contraction -- the seven forward projections and the four input-gradient products
 // dY . W, which run as the same "activation x weight^T" GEMM on a transposed copy of the weights made per layer --
 // goes through the library's GEMM dispatch (MFMA kernels for bf16 shapes they cover).  Attention (scores, softmax,
-// its backward) runs on materialised [rows x rows] matrices per (rollout, head) with a batched fp32 tile kernel, as
-// do the four skinny LoRA products per projection (X A^T, dY B, dY^T (X A^T), (dY B)^T X).  Gradient operands of
+// its backward) runs on materialised [rows x rows] matrices per (rollout, head) with a batched tile kernel (matrix
+// cores for bf16 storage, fp32 ALU for fp32 storage); the four skinny LoRA products per projection group
+// (X A^T, dY B, dY^T (X A^T), (dY B)^T X) run as GEMMs on stacked, zero-padded factors.  Gradient operands of
 // the GEMMs are rounded to the storage type like every other GEMM operand; all sums are fp32 and taken in a fixed
 // order (no atomics), so the result is reproducible bit for bit.
 #include <vector>
@@ -21,6 +23,7 @@
 namespace {
 
 template <typename T> __device__ __forceinline__ float ld(const T *p) { return (float)*p; }
+template <typename T> __device__ __forceinline__ float ld_elem(const T *p) { return (float)*p; }
 template <typename T> __device__ __forceinline__ T cvt(float v) { return (T)v; }
 
 __device__ __forceinline__ float bsum256(float v, float *red) {
@@ -122,12 +125,142 @@ __global__ void __launch_bounds__(256) bgemm_kernel(BgemmArgs g) {
     }
 }
 
+// The same contraction on the matrix cores, for the bf16 path: 64 x 64 output tile per workgroup, four waves of
+// 32 x 32 (2 x 2 blocks of v_mfma_f32_16x16x32_bf16), K in steps of 32 through LDS.  A bf16 operand is used as it is;
+// an fp32 operand (probabilities, score gradients, output gradients) is split into a bf16 head and a bf16 tail and
+// both enter the product (head x head, tail x head, head x tail), so the result keeps about 16 bits of either
+// operand.  Sums are fp32 in a fixed order.  Same arguments, masks and bounds checks as the tile kernel above; a
+// thread moves eight consecutive elements of an operand with one 16-byte load (two for fp32) where they are inside
+// the matrix and 16-byte aligned, one by one otherwise.
+//
+// LDS tile: [64 rows][32 k] bf16 in 80-byte rows; the four 16-byte chunks of a row are permuted by (row / 8) % 4 so
+// that the element-wise stores of a transposed operand (eight rows apart per lane) land in different banks.
+constexpr int BG_LD = 40;
+__device__ __forceinline__ int bg_col(int row, int k) { return ((((k >> 3) ^ (row >> 3)) & 3) << 3) | (k & 7); }
+
+template <typename T> __device__ __forceinline__ void bg_load8(const T *p, float v[8]);
+template <> __device__ __forceinline__ void bg_load8<float>(const float *p, float v[8]) {
+    const f32x4_t a = *(const f32x4_t *)p, b = *(const f32x4_t *)(p + 4);
+#pragma unroll
+    for (int e = 0; e < 4; e++) { v[e] = a[e]; v[4 + e] = b[e]; }
+}
+template <> __device__ __forceinline__ void bg_load8<bf16_t>(const bf16_t *p, float v[8]) {
+    const bf16x8_t a = *(const bf16x8_t *)p;
+#pragma unroll
+    for (int e = 0; e < 8; e++) v[e] = (float)a[e];
+}
+
+// Stages op(X)[row0 .. row0 + 63][k0 .. k0 + 31] into tile[0] (bf16 heads) and, for fp32 operands, tile[1] (tails).
+// k_contig: X is stored [row][k] (leading dimension ld), else [k][row].  Elements outside rows < lim, k < kend are 0.
+template <typename T, bool SPLIT>
+__device__ __forceinline__ void bg_stage(bf16_t (*tile)[64][BG_LD], const T *X, bool k_contig, int ld, int row0, int lim, int k0, int kend) {
+    const int t = threadIdx.x;
+    float v[8];
+    if (k_contig) {
+        const int row = t >> 2, kk = (t & 3) * 8, gi = row0 + row, gk = k0 + kk;
+        const T *p = X + (size_t)gi * ld + gk;
+        if (gi < lim && gk + 8 <= kend && ((size_t)p & 15) == 0) bg_load8<T>(p, v);
+        else {
+#pragma unroll
+            for (int e = 0; e < 8; e++) v[e] = (gi < lim && gk + e < kend) ? ld_elem(p + e) : 0.f;
+        }
+        bf16x8_t hi, lo;
+#pragma unroll
+        for (int e = 0; e < 8; e++) { hi[e] = (bf16_t)v[e]; lo[e] = (bf16_t)(v[e] - (float)hi[e]); }
+        *(bf16x8_t *)&tile[0][row][bg_col(row, kk)] = hi;
+        if constexpr (SPLIT) *(bf16x8_t *)&tile[1][row][bg_col(row, kk)] = lo;
+    } else {
+        const int kk = t >> 3, r0 = (t & 7) * 8, gk = k0 + kk, gi = row0 + r0;
+        const T *p = X + (size_t)gk * ld + gi;
+        if (gk < kend && gi + 8 <= lim && ((size_t)p & 15) == 0) bg_load8<T>(p, v);
+        else {
+#pragma unroll
+            for (int e = 0; e < 8; e++) v[e] = (gk < kend && gi + e < lim) ? ld_elem(p + e) : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            const bf16_t hi = (bf16_t)v[e];
+            tile[0][r0 + e][bg_col(r0 + e, kk)] = hi;
+            if constexpr (SPLIT) tile[1][r0 + e][bg_col(r0 + e, kk)] = (bf16_t)(v[e] - (float)hi);
+        }
+    }
+}
+
 template <typename TA, typename TB>
-int bgemm(const BgemmArgs &g, int batch, hipStream_t st, const char *label = "bw_attention_tiles") {
+__global__ void __launch_bounds__(256) bgemm_mfma_kernel(BgemmArgs g) {
+    constexpr int BM = 64, BN = 64, BK = 32;
+    constexpr bool SA = sizeof(TA) == 4, SB = sizeof(TB) == 4;
+    __shared__ __attribute__((aligned(16))) bf16_t As[SA ? 2 : 1][BM][BG_LD];
+    __shared__ __attribute__((aligned(16))) bf16_t Bs[SB ? 2 : 1][BN][BG_LD];
+    const int b = blockIdx.z, b1 = b / g.inner, b2 = b - b1 * g.inner;
+    const TA *A = (const TA *)g.A + b1 * g.sA1 + b2 * g.sA2;
+    const TB *B = (const TB *)g.B + b1 * g.sB1 + b2 * g.sB2;
+    float *C = g.C + b1 * g.sC1 + b2 * g.sC2;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    if (g.tri == 2 && n0 > m0 + BM - 1) return;
+    const int kend = g.tri == 1 ? min(g.k, m0 + BM) : g.k;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l16 = lane & 15, kq = lane >> 4;
+    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
+    f32x4_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < kend; k0 += BK) {
+        bg_stage<TA, SA>(As, A, !g.transA, g.lda, m0, g.m, k0, kend);     // op(A)[m][k]: A is [m][k] unless transposed
+        bg_stage<TB, SB>(Bs, B, g.transB != 0, g.ldb, n0, g.n, k0, kend);  // op(B)[k][n]: B is [n][k] when transposed
+        __syncthreads();
+        bf16x8_t af[SA ? 2 : 1][2], bfr[SB ? 2 : 1][2];
+#pragma unroll
+        for (int p = 0; p < (SA ? 2 : 1); p++)
+#pragma unroll
+            for (int i = 0; i < 2; i++) { const int r = wm + 16 * i + l16; af[p][i] = *(const bf16x8_t *)&As[p][r][bg_col(r, kq * 8)]; }
+#pragma unroll
+        for (int p = 0; p < (SB ? 2 : 1); p++)
+#pragma unroll
+            for (int j = 0; j < 2; j++) { const int r = wn + 16 * j + l16; bfr[p][j] = *(const bf16x8_t *)&Bs[p][r][bg_col(r, kq * 8)]; }
+        // result layout of the instruction: the lane holds the second operand's row l16 and the first operand's rows
+        // 4 kq .. 4 kq + 3, so op(B) goes first and each lane ends up with four consecutive columns of one output row
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+            for (int j = 0; j < 2; j++) {
+                if constexpr (SA) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[0][j], af[1][i], acc[i][j], 0, 0, 0);
+                if constexpr (SB) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[1][j], af[0][i], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[0][j], af[0][i], acc[i][j], 0, 0, 0);
+            }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+        const int gi = m0 + wm + 16 * i + l16;
+        if (gi >= g.m) continue;
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const int gj = n0 + wn + 16 * j + 4 * kq;
+            float *c = C + (size_t)gi * g.ldc + gj;
+            if (gj + 4 <= g.n && !g.accumulate && ((size_t)c & 15) == 0) {
+                *(f32x4_t *)c = acc[i][j] * g.alpha;
+                continue;
+            }
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                if (gj + r >= g.n) continue;
+                const float v = g.alpha * acc[i][j][r];
+                c[r] = g.accumulate ? c[r] + v : v;
+            }
+        }
+    }
+}
+
+// MF: the matrix-core kernel (bf16 storage); otherwise the fp32 tile kernel.
+template <typename TA, typename TB, bool MF>
+int bgemm(const BgemmArgs &g, int batch, hipStream_t st) {
     if (g.m <= 0 || g.n <= 0 || batch <= 0) return 0;
-    ProfScope ps(label, 2.0 * g.m * g.n * (double)g.k * batch * (g.tri ? 0.5 : 1.0), st);
+    ProfScope ps(MF ? "bw_attention_mfma" : "bw_attention_tiles", 2.0 * g.m * g.n * (double)g.k * batch * (g.tri ? 0.5 : 1.0), st);
     dim3 grid((g.n + 63) / 64, (g.m + 63) / 64, batch);
-    bgemm_kernel<TA, TB><<<grid, 256, 0, st>>>(g);
+    if constexpr (MF) bgemm_mfma_kernel<TA, TB><<<grid, 256, 0, st>>>(g);
+    else bgemm_kernel<TA, TB><<<grid, 256, 0, st>>>(g);
     return vla_check_launch("bgemm");
 }
 
@@ -170,14 +303,14 @@ __global__ void rope_rows_kernel(T *out, const float *in, const float2 *table, s
     }
 }
 
-// In-place masked softmax of the score rows of one (sequence, head): row i sees keys 0..i, or all R keys from row
-// full_from on.  One wave per row; entries outside the mask become 0.
-__global__ void __launch_bounds__(256) attn_softmax_kernel(float *SP, size_t n_rows, int R, int full_from) {
+// In-place masked softmax of the score rows of one (sequence, head), rows ldp floats apart: row i sees keys 0..i, or
+// all R keys from row full_from on.  One wave per row; entries outside the mask become 0.
+__global__ void __launch_bounds__(256) attn_softmax_kernel(float *SP, size_t n_rows, int R, int ldp, int full_from) {
     const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= n_rows) return;
     const int lane = threadIdx.x & 63, i = (int)(row % R);
     const int nk = i >= full_from ? R : i + 1;
-    float *s = SP + row * R;
+    float *s = SP + row * ldp;
     float mx = -INFINITY;
     for (int j = lane; j < nk; j += 64) mx = fmaxf(mx, s[j]);
     mx = wmax(mx);
@@ -189,13 +322,13 @@ __global__ void __launch_bounds__(256) attn_softmax_kernel(float *SP, size_t n_r
 }
 
 // dS = P (dP - sum_j P dP) in place on dP; masked entries (P = 0) become 0.
-__global__ void __launch_bounds__(256) attn_ds_kernel(float *dP, const float *P, size_t n_rows, int R, int full_from) {
+__global__ void __launch_bounds__(256) attn_ds_kernel(float *dP, const float *P, size_t n_rows, int R, int ldp, int full_from) {
     const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= n_rows) return;
     const int lane = threadIdx.x & 63, i = (int)(row % R);
     const int nk = i >= full_from ? R : i + 1;
-    float *d = dP + row * R;
-    const float *p = P + row * R;
+    float *d = dP + row * ldp;
+    const float *p = P + row * ldp;
     float dot = 0.f;
     for (int j = lane; j < nk; j += 64) dot += p[j] * d[j];
     dot = wsum(dot);
@@ -373,6 +506,9 @@ inline unsigned blocks_for(size_t n) { size_t b = (n + 255) / 256; return (unsig
 struct BwSpace {
     float *X, *dX, *ckpt, *QKV, *GU, *Tmp, *SP, *dP, *UV, *Cab;
     void *Nrm, *Nrm2, *AO, *ACT, *QKVr, *dGU, *dXb, *dQKVb, *Wt, *Wa, *Wb, *UVt, *Xt, *dYt;
+    void *fw;        // scratch of the first forward pass (vla_forward_streams)
+    void *split;     // partial products of the split-K LoRA GEMMs
+    size_t split_bytes;
     int kp;          // rows of a micro-batch rounded up to what a GEMM's K extent accepts
     float2 *rope;
     int a_rows;
@@ -394,8 +530,9 @@ BwSpace plan_bw(const vla_config &c, char *base, int mb, int R, int /*rank*/) {
     w.QKV = (float *)take(M * 3 * H * 4);
     w.GU = (float *)take(M * 2 * F * 4);
     w.Tmp = (float *)take(M * (F > 3 * H ? F : 3 * H) * 4);
-    w.SP = (float *)take((size_t)mb * c.n_heads * R * R * 4);
-    w.dP = (float *)take((size_t)mb * c.n_heads * R * R * 4);
+    const size_t Rp = ((size_t)R + 3) & ~(size_t)3;             // score rows start 16-byte aligned
+    w.SP = (float *)take((size_t)mb * c.n_heads * R * Rp * 4);
+    w.dP = (float *)take((size_t)mb * c.n_heads * R * Rp * 4);
     // LoRA products (see lora_group): U | V [2][M, 256] fp32, their rounded transposes [2][256 + pad, kp], the stacked
     // factors, the transposed activations / output gradients and the two [dim, 256] results
     const size_t kp = M < 256 ? 256 : (M + 63) / 64 * 64, wide = 3 * H > 2 * F ? 3 * H : 2 * F, dim_p = (wide + 255) / 256 * 256 + VLA_KB_PAD_ROWS;
@@ -417,6 +554,9 @@ BwSpace plan_bw(const vla_config &c, char *base, int mb, int R, int /*rank*/) {
     w.dQKVb = take(Mp * 3 * H * es);
     w.Wt = take((3 * H > 2 * F ? 3 * H : 2 * F) * H * es);      // the widest transposed stack: [H, 3H] or [H, 2F] ([F, H] is smaller)
     w.rope = (float2 *)take((size_t)R * (H / c.n_heads / 2) * sizeof(float2));
+    w.fw = take(vla_forward_streams_bytes(c, mb, R));
+    w.split_bytes = (size_t)8 * (M > dim_p ? M : dim_p) * 256 * 4;      // up to 8 parts of the tallest [rows, 256] product
+    w.split = take(w.split_bytes);
     w.total = off;
     return w;
 }
@@ -432,6 +572,7 @@ struct Backward {
     hipStream_t st;
     int n, R, M, H, F, d, nh, full_from, rank;
     float scale;
+    static constexpr bool MF = sizeof(T) == 2;      // bf16 storage: attention matrices on the matrix cores
 
     int gemm(const void *A, const void *W0, const void *W1, const void *W2, int n_seg, int segN, float *C, int K) {
         GemmArgs g{};
@@ -462,7 +603,8 @@ struct Backward {
     int layer_forward(int l, float *x_mid_keep) {
         const vla_layer_weights &lw = m->layers[l];
         const T *Q = (const T *)ws.QKVr;
-        const long RR = (long)R * R, rowsH3 = (long)R * 3 * H;
+        const int Rp = (R + 3) & ~3;
+        const long RR = (long)R * Rp, rowsH3 = (long)R * 3 * H;
         const bool causal = full_from >= R;
         int rc;
         if ((rc = launch_rmsnorm<T>((T *)ws.Nrm, ws.X, (const float *)lw.attn_norm, M, H, c.rms_eps, st))) return rc;
@@ -470,12 +612,12 @@ struct Backward {
         rope_rows_kernel<T><<<blocks_for((size_t)M * 3 * (H / 2)), 256, 0, st>>>((T *)ws.QKVr, ws.QKV, ws.rope, (size_t)M, R, H, d, 1.0f);
         if ((rc = vla_check_launch("rope_rows"))) return rc;
         // scores = q k^T / sqrt(d) per (sequence, head); softmax under the mask; output = P v
-        BgemmArgs g = heads(Q, 3 * H, rowsH3, d, Q + H, 3 * H, rowsH3, d, ws.SP, R, RR * nh, RR, R, R, d, 0, 1, 1.0f / sqrtf((float)d), causal ? 2 : 0);
-        if ((rc = bgemm<T, T>(g, n * nh, st))) return rc;
-        attn_softmax_kernel<<<(unsigned)(((size_t)n * nh * R + 3) / 4), 256, 0, st>>>(ws.SP, (size_t)n * nh * R, R, full_from);
+        BgemmArgs g = heads(Q, 3 * H, rowsH3, d, Q + H, 3 * H, rowsH3, d, ws.SP, Rp, RR * nh, RR, R, R, d, 0, 1, 1.0f / sqrtf((float)d), causal ? 2 : 0);
+        if ((rc = bgemm<T, T, MF>(g, n * nh, st))) return rc;
+        attn_softmax_kernel<<<(unsigned)(((size_t)n * nh * R + 3) / 4), 256, 0, st>>>(ws.SP, (size_t)n * nh * R, R, Rp, full_from);
         if ((rc = vla_check_launch("attn_softmax"))) return rc;
-        g = heads(ws.SP, R, RR * nh, RR, Q + 2 * H, 3 * H, rowsH3, d, ws.Tmp, H, (long)R * H, d, R, d, R, 0, 0, 1.0f, causal ? 1 : 0);
-        if ((rc = bgemm<float, T>(g, n * nh, st))) return rc;
+        g = heads(ws.SP, Rp, RR * nh, RR, Q + 2 * H, 3 * H, rowsH3, d, ws.Tmp, H, (long)R * H, d, R, d, R, 0, 0, 1.0f, causal ? 1 : 0);
+        if ((rc = bgemm<float, T, MF>(g, n * nh, st))) return rc;
         if ((rc = cast(ws.AO, ws.Tmp, H, H, H))) return rc;
         if ((rc = gemm(ws.AO, lw.wo, nullptr, nullptr, 1, H, ws.Tmp, H))) return rc;
         add_kernel_launch(ws.X, ws.Tmp, (size_t)M * H);
@@ -501,6 +643,7 @@ struct Backward {
     int gemm_rows(const void *A, const void *W, float *C, int rows, int a_rows, int K) {
         GemmArgs g{};
         g.A = A; g.W[0] = W; g.n_seg = 1; g.segN = 256; g.C = C; g.M = rows; g.K = K; g.epilogue = EPI_STORE; g.a_rows = a_rows;
+        g.split_scratch = ws.split; g.split_scratch_bytes = ws.split_bytes;     // few output tiles: cut K into parts
         return vla_gemm_dispatch(c, g, st);
     }
     int lora_group(LoraGroup lg, const void *X, const void *dY, bool first) {
@@ -538,7 +681,8 @@ struct Backward {
         float *x_in = ws.ckpt + (size_t)l * M * H;
         float *x_mid = ws.QKV;                       // the fp32 projection buffer is free once QKVr exists: x_mid lives there
         const T *Q = (const T *)ws.QKVr;
-        const long RR = (long)R * R, rowsH3 = (long)R * 3 * H;
+        const int Rp = (R + 3) & ~3;
+        const long RR = (long)R * Rp, rowsH3 = (long)R * 3 * H;
         const bool causal = full_from >= R;
         const float isd = 1.0f / sqrtf((float)d);
         int rc;
@@ -564,16 +708,16 @@ struct Backward {
         if ((rc = gemm(ws.dXb, ws.Wt, nullptr, nullptr, 1, H, d_ao, H))) return rc;
         float *dqkv = ws.Tmp;                        // [M, 3H] fp32: d q | d k | d v (q, k still in the rotated frame)
         // dP = dO v^T ; dV = P^T dO ; dS = P (dP - rowsum(P dP)) ; dQ = dS k / sqrt(d) ; dK = dS^T q / sqrt(d)
-        BgemmArgs g = heads(d_ao, H, (long)R * H, d, Q + 2 * H, 3 * H, rowsH3, d, ws.dP, R, RR * nh, RR, R, R, d, 0, 1, 1.0f, causal ? 2 : 0);
-        if ((rc = bgemm<float, T>(g, n * nh, st))) return rc;
-        g = heads(ws.SP, R, RR * nh, RR, d_ao, H, (long)R * H, d, dqkv + 2 * H, 3 * H, rowsH3, d, R, d, R, 1, 0, 1.0f, 0);
-        if ((rc = bgemm<float, float>(g, n * nh, st))) return rc;
-        attn_ds_kernel<<<(unsigned)(((size_t)n * nh * R + 3) / 4), 256, 0, st>>>(ws.dP, ws.SP, (size_t)n * nh * R, R, full_from);
+        BgemmArgs g = heads(d_ao, H, (long)R * H, d, Q + 2 * H, 3 * H, rowsH3, d, ws.dP, Rp, RR * nh, RR, R, R, d, 0, 1, 1.0f, causal ? 2 : 0);
+        if ((rc = bgemm<float, T, MF>(g, n * nh, st))) return rc;
+        g = heads(ws.SP, Rp, RR * nh, RR, d_ao, H, (long)R * H, d, dqkv + 2 * H, 3 * H, rowsH3, d, R, d, R, 1, 0, 1.0f, 0);
+        if ((rc = bgemm<float, float, MF>(g, n * nh, st))) return rc;
+        attn_ds_kernel<<<(unsigned)(((size_t)n * nh * R + 3) / 4), 256, 0, st>>>(ws.dP, ws.SP, (size_t)n * nh * R, R, Rp, full_from);
         if ((rc = vla_check_launch("attn_ds"))) return rc;
-        g = heads(ws.dP, R, RR * nh, RR, Q + H, 3 * H, rowsH3, d, dqkv, 3 * H, rowsH3, d, R, d, R, 0, 0, isd, causal ? 1 : 0);
-        if ((rc = bgemm<float, T>(g, n * nh, st))) return rc;
-        g = heads(ws.dP, R, RR * nh, RR, Q, 3 * H, rowsH3, d, dqkv + H, 3 * H, rowsH3, d, R, d, R, 1, 0, isd, 0);
-        if ((rc = bgemm<float, T>(g, n * nh, st))) return rc;
+        g = heads(ws.dP, Rp, RR * nh, RR, Q + H, 3 * H, rowsH3, d, dqkv, 3 * H, rowsH3, d, R, d, R, 0, 0, isd, causal ? 1 : 0);
+        if ((rc = bgemm<float, T, MF>(g, n * nh, st))) return rc;
+        g = heads(ws.dP, Rp, RR * nh, RR, Q, 3 * H, rowsH3, d, dqkv + H, 3 * H, rowsH3, d, R, d, R, 1, 0, isd, 0);
+        if ((rc = bgemm<float, T, MF>(g, n * nh, st))) return rc;
         rope_rows_kernel<T><<<blocks_for((size_t)M * 3 * (H / 2)), 256, 0, st>>>((T *)ws.dQKVb, dqkv, ws.rope, (size_t)M, R, H, d, -1.0f);
         if ((rc = vla_check_launch("rope_rows (transpose)"))) return rc;
         // ---- Q / K / V projections and the attention norm
@@ -612,19 +756,15 @@ int backward_impl(vla_model *m, void *wsbuf, const void *patch, const int32_t *i
         const int n = (N - n0 < mb) ? N - n0 : mb;
         bw.n = n; bw.M = n * R;
         const size_t MH = (size_t)bw.M * H;
-        const T *pp = (const T *)patch + (size_t)n0 * P * H;
-        if ((rc = launch_embed_prefix<T>(bw.ws.X, pp, ids + (size_t)n0 * T_, (const T *)m->w.embed, n, P, T_, R, H, c.vocab, st))) return rc;
-        if (mode == VLA_MODE_AR) {
-            if ((rc = launch_embed_tokens<T>(bw.ws.X, bins + (size_t)n0 * A, A, A - 1, (const T *)m->w.embed, n, R, S, H, c.vocab, st))) return rc;
-        } else if ((rc = launch_embed_slots<T>(bw.ws.X, (const T *)slot_embed, n, A, R, S, H, st))) return rc;
-        for (int l = 0; l < L; l++) {
-            if (hipMemcpyAsync(bw.ws.ckpt + (size_t)l * MH, bw.ws.X, MH * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) { vla_set_error("backward: copy failed"); return VLA_EHIP; }
-            if ((rc = bw.layer_forward(l, nullptr))) return rc;
-        }
+        // (1) the forward pass of the recompute itself (its fused kernels), keeping every layer's input
+        const T *pp = patch ? (const T *)patch + (size_t)n0 * P * H : nullptr;
+        const float *x_final = nullptr;
+        if ((rc = vla_forward_streams(m, bw.ws.fw, mb, pp, ids ? ids + (size_t)n0 * T_ : nullptr, bins + (size_t)n0 * A, n, P, T_, A, mode,
+                                      slot_embed, bw.ws.ckpt, &x_final, st))) return rc;
         fill_kernel<<<blocks_for(MH), 256, 0, st>>>(bw.ws.dX, MH, 0.f);
         if ((rc = vla_check_launch("fill"))) return rc;
         head_bwd_kernel<T><<<n * A, 256, (size_t)(H + VLA_N_BINS) * sizeof(float), st>>>(
-            bw.ws.dX, logp ? logp + (size_t)n0 * A : nullptr, bw.ws.X, (const float *)m->w.final_norm, head, bins + (size_t)n0 * A,
+            bw.ws.dX, logp ? logp + (size_t)n0 * A : nullptr, x_final, (const float *)m->w.final_norm, head, bins + (size_t)n0 * A,
             coef + (size_t)n0 * A, A, R, first_row, H, c.rms_eps, 1.0f / temperature);
         if ((rc = vla_check_launch("head_bwd"))) return rc;
         for (int l = L - 1; l >= 0; l--)

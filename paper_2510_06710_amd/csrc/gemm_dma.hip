@@ -668,6 +668,55 @@ int try_gemm_bf16_dma_splitk(const GemmArgs &g, void *scratch, size_t scratch_by
     return 1;
 }
 
+// Split-K form for multi-row problems with few output tiles (the LoRA-gradient products: 256 output columns, or a
+// contraction over all rows of a micro-batch): the K range is cut into `parts` equal ranges so that tiles x parts
+// items keep the CUs busy, each range's fp32 product goes to `scratch` ([parts][M][N]) and launch_splitk_reduce adds
+// them in order.  Row-major operands, fp32 output only.  `parts` minimises a cost estimate (below); declines (0) when
+// that leaves one part or the scratch is too small.
+int try_gemm_bf16_dma_splitk_rows(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st) {
+    if (g.kblocked || g.epilogue != EPI_STORE || g.M < 1 || g.K % 64 != 0 || g.K < 256 || !scratch) return 0;
+    if (g.segN % BN != 0 || g.a_rows < (g.M + BM - 1) / BM * BM) return 0;
+    static int n_cu = 0;
+    if (!n_cu) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1) {
+            vla_set_error("gemm_bf16_dma: cannot read the compute-unit count");
+            return VLA_EHIP;
+        }
+    }
+    const int N = g.n_seg * g.segN, tiles_m = (g.M + BM - 1) / BM, tiles = tiles_m * (N / BN), nh = g.K / HK;
+    // cost in half-tile times (about 0.8 us): rounds of items x (half tiles per item + about 8 for an item's prologue
+    // and fp32 epilogue), plus the reduction's traffic (0.5 MB written and read per tile and part, about 0.16)
+    auto cost_of = [&](int parts) {
+        const long rounds = (tiles * parts + n_cu - 1) / n_cu;
+        return rounds * (nh / parts + 8) * 100 + (parts > 1 ? 16L * parts * tiles : 0);
+    };
+    int best = 1;
+    long best_cost = cost_of(1);
+    for (int parts = 2; parts <= 32; parts++) {
+        const int per = nh / parts;
+        if (nh % parts != 0 || (per & 1) || per < 8) continue;
+        if ((size_t)parts * g.M * N * sizeof(float) > scratch_bytes) break;
+        const long cost = cost_of(parts);
+        if (cost < best_cost) { best_cost = cost; best = parts; }
+    }
+    if (best < 2) return 0;
+    DmaGemmParams p{};
+    p.A = (const bf16_t *)g.A;
+    p.W0 = (const bf16_t *)g.W[0]; p.W1 = (const bf16_t *)g.W[1]; p.W2 = (const bf16_t *)g.W[2];
+    p.C = scratch; p.M = g.M; p.K = g.K; p.segN = g.segN;
+    p.a_rows = g.a_rows; p.w_rows = 0; p.group = 4; p.splits = best;
+    p.tiles_m = tiles_m; p.N = N; p.tiles_n = N / BN;
+    {
+        ProfScope ps("gemm_dma_splitk_rows<store>", 2.0 * g.M * g.K * (double)N, st);
+        const int rc = launch_plain<EPI_STORE, false>(p, st);
+        if (rc != 1) return rc;
+    }
+    const int rc = launch_splitk_reduce(EPI_STORE, g.C, (const float *)scratch, best, g.M, N, st);
+    return rc ? rc : 1;
+}
+
 namespace {
 
 // Repack of one weight matrix [N, K] into [K / 32][N + pad][32]: a thread moves one 16-byte piece (the pad rows

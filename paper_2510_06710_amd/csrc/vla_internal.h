@@ -66,6 +66,8 @@ struct GemmArgs {
     int *deferred_splits;   // not NULL (EPI_STORE and EPI_RESIDUAL of the split-K kernels): the kernel leaves its n
                             // partial products [n][M][N] at the start of the scratch buffer, puts n here and does not
                             // reduce them (the caller's next kernel adds them in order); 0 here: C is complete
+    void *split_scratch;    // not NULL (EPI_STORE, row-major bf16): device scratch of split_scratch_bytes through which a
+    size_t split_scratch_bytes;   // multi-row problem with few output tiles may cut its K range into parts
 };
 
 // ---- generic (any shape, fp32 or bf16 storage) kernels: kernels_generic.hip -----------------
@@ -162,6 +164,7 @@ __device__ __forceinline__ void vla_tile_of_block(int pid, int tiles_m, int tile
 // shape is outside what it supports (caller then uses the generic kernel), <0 on launch error ----
 int try_gemm_bf16_dma(const GemmArgs &g, hipStream_t st);
 int try_gemm_bf16_dma_splitk(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st);
+int try_gemm_bf16_dma_splitk_rows(const GemmArgs &g, void *scratch, size_t scratch_bytes, hipStream_t st);
 int launch_weight_kblock(bf16_t *dst, const bf16_t *src, int N, int K, hipStream_t st);
 // qkv: `splits` partial copies of the fp32 [M, 3H] projection, `split_stride` floats apart, added in order
 int launch_rope_kv_write_bf16(bf16_t *q_out, const float *qkv, int splits, size_t split_stride, const float2 *table,
@@ -197,6 +200,13 @@ int vla_check_config(const vla_config *c);                                   // 
 int vla_check_rows_per_pass(const vla_config &c, long n_seq, long rows_per_seq);
 // C = A . W^T of a multi-row forward (row-major operands): the MFMA kernels where the shape allows, else the generic one
 int vla_gemm_dispatch(const vla_config &c, const GemmArgs &g, hipStream_t st);
+// The teacher-forced forward of the log-prob recompute over n rollouts (the kernels vla_logprob_recompute runs, every
+// row through every layer), keeping the fp32 residual stream at the input of layer l in keep + l * n * R * H
+// ([n * R, H] each).  *x_final: the residual stream after the last layer ([n * R, H], inside fw_ws).  fw_ws: device
+// scratch of vla_forward_streams_bytes(c, n_max, R) bytes with n <= n_max.
+size_t vla_forward_streams_bytes(const vla_config &c, int n_max, int R);
+int vla_forward_streams(vla_model *m, void *fw_ws, int n_max, const void *patch, const int32_t *ids, const int32_t *bins, int n,
+                        int P, int T, int A, int mode, const void *slot_embed, float *keep, const float **x_final, hipStream_t st);
 
 // Profiling scope: when profiling is enabled, records an event pair around the launches issued
 // during its lifetime, tagged with `label` (a string literal) and the algorithmic work.

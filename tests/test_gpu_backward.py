@@ -6,7 +6,12 @@ normal tensors in the storage dtype (the gradient formulas need nothing else).  
 within 2e-4 of its largest entry.  bf16 storage: the GEMM operands of the backward (activations and gradients) are
 rounded to bf16 (2^-9 relative per element, averaged down by the sums over rows), so each gradient tensor is compared
 with the oracle that rounds the forward's stored tensors (straight-through): relative RMS error at most 1e-2 and
-largest deviation at most 2e-2 of the tensor's largest entry (observed: 4e-3 and 5e-3)."""
+largest deviation at most 2e-2 of the tensor's largest entry (observed: 4e-3 and 5e-3).
+
+The log-probs the pass returns come from the recompute's own forward kernels.  Here they are taken at seeded random
+bins, not at sampled ones: such a bin can sit far in the tail (log-prob below -9 where a flat distribution gives
+-ln 256 = -5.5), and a bf16 logit error grows with the distance z_j - logsumexp(z) = logp_j it is measured over, so
+the bf16 bound of 1e-2 is scaled by max(1, |logp| / ln 256) per token."""
 import numpy as np
 import pytest
 import torch
@@ -59,6 +64,11 @@ def _oracle(wl, seed, lora, bins, coef, n, scale, operand_dtype="exact"):
                                     wl.mode, slot, wl.temperature)
 
 
+def _assert_logp_bf16(logp, ref_logp):
+    tol = 1e-2 * np.maximum(1.0, np.abs(ref_logp) / np.log(256.0))
+    assert np.all(np.abs(logp - ref_logp) < tol), float(np.max(np.abs(logp - ref_logp) / tol))
+
+
 def _compare(grads, ref, rel_max, rel_rms=None):
     worst = dict(max=0.0, rms=0.0)
     for l, layer in enumerate(ref):
@@ -103,7 +113,7 @@ def test_aligned_bf16_lora_gradients_mfma_gemms():
                      batch=5, n_patches=40, n_instr=9, n_action=4)
     _, lora, bins, coef, grads, logp = _run(wl, 5, rank=16, scale=0.25)
     ref, ref_logp = _oracle(wl, 5, lora, bins, coef, 5, 0.25, operand_dtype="bf16")
-    assert np.max(np.abs(logp - ref_logp)) < 1e-2
+    _assert_logp_bf16(logp, ref_logp)
     print(f"\n[parity] backward aligned bf16: {_compare(grads, ref, 2e-2, 1e-2)}", flush=True)
 
 
@@ -112,5 +122,5 @@ def test_one_layer_7b_width_lora_gradients():
     print("\n[7b] backward: 1 layer of 7B width, 2 rollouts x 294 rows, rank 32", flush=True)
     _, lora, bins, coef, grads, logp = _run(wl, 6, rank=32, scale=0.5)
     ref, ref_logp = _oracle(wl, 6, lora, bins, coef, 2, 0.5, operand_dtype="bf16")
-    assert np.max(np.abs(logp - ref_logp)) < 1e-2
+    _assert_logp_bf16(logp, ref_logp)
     print(f"[parity] backward 1-layer 7B width: {_compare(grads, ref, 2e-2, 1e-2)}", flush=True)

@@ -163,15 +163,15 @@ def bench_recompute(args, wl, torch, vi, vb, Rollout):
 def bench_backward(args, wl, torch, vi, vb, Rollout):
     """LoRA-gradient pass (vla_logprob_backward) over a sample of the recompute workload's stored rollouts: a step is
     one call over `--backward-rollouts` rollouts in micro-batches of `--backward-micro-batch`.  Reports rollouts/s and
-    the rate of the projection flops it executes (forward twice -- once kept, once recomputed per layer -- and the
-    input-gradient products once), against the bf16 MFMA peak."""
+    the rate of the projection flops it executes (the forward once, every layer again without its down projection, and
+    the input-gradient products once), against the bf16 MFMA peak."""
     dev = "cuda:0"
     torch.cuda.set_device(0)
     N, mb, rank = args.backward_rollouts, args.backward_micro_batch, args.lora_rank
     S, A, shape = wl.prefix, wl.n_action, wl.shape
     wl_n = vi.scaled(wl, batch=N)
     synth = vi.SynthModel(shape, 0, device=dev)
-    run = Rollout(synth, mb, S + A, device=dev, value_b=vi.VALUE_BIAS, prepack=False)
+    run = Rollout(synth, mb, S + A, device=dev, value_b=vi.VALUE_BIAS)
     patch, ids = vi.observation(wl_n, 0, device=dev)
     bins = vi.stored_bins(wl_n, 0, device=dev)
     g = torch.Generator(device="cpu").manual_seed(1)
@@ -201,7 +201,8 @@ def bench_backward(args, wl, torch, vi, vb, Rollout):
     prof = profile_report(vb)
     vb.lib().vla_profile_enable(0)
     rows = S + A - 1 if wl.mode == 0 else S + A
-    flops = 3.0 * N * rows * 2.0 * shape.layer_params * shape.n_layers
+    down_share = shape.hidden * shape.ffn / shape.layer_params          # the recomputed forward skips the down projection
+    flops = (3.0 - down_share) * N * rows * 2.0 * shape.layer_params * shape.n_layers
     out = {"metric": "stored rollouts/sec, LoRA-gradient pass of the log-prob recompute (7B shape)", "value": N / (ms * 1e-3),
            "unit": "rollouts/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,

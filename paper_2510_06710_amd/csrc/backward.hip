@@ -574,10 +574,10 @@ struct Backward {
     float scale;
     static constexpr bool MF = sizeof(T) == 2;      // bf16 storage: attention matrices on the matrix cores
 
-    int gemm(const void *A, const void *W0, const void *W1, const void *W2, int n_seg, int segN, float *C, int K) {
+    int gemm(const void *A, const void *W0, const void *W1, const void *W2, int n_seg, int segN, float *C, int K, int epilogue = EPI_STORE) {
         GemmArgs g{};
         g.A = A; g.W[0] = W0; g.W[1] = W1; g.W[2] = W2; g.n_seg = n_seg; g.segN = segN; g.C = C; g.M = M; g.K = K;
-        g.epilogue = EPI_STORE; g.a_rows = ws.a_rows;
+        g.epilogue = epilogue; g.a_rows = ws.a_rows;
         return vla_gemm_dispatch(c, g, st);
     }
     int transpose(const void *W, int N, int K, int ldt, int col0) {
@@ -598,9 +598,10 @@ struct Backward {
         return g;
     }
 
-    // One decoder layer forward on ws.X (in place), leaving in the workspace what its backward needs: Nrm, QKVr, SP (the
-    // attention probabilities), AO, X = x_mid ... then x_out, Nrm2, GU, ACT.  `x_mid_keep`: copy of x_mid (or NULL).
-    int layer_forward(int l, float *x_mid_keep) {
+    // Layer l again from its input in ws.X, up to the SwiGLU output, leaving in the workspace what the backward needs:
+    // Nrm, QKVr, SP (the attention probabilities), AO, X = x_mid (the stream after the attention block), Nrm2, GU and
+    // ACT.  The down projection is not run: nothing in the backward reads the layer's output.
+    int layer_recompute(int l) {
         const vla_layer_weights &lw = m->layers[l];
         const T *Q = (const T *)ws.QKVr;
         const int Rp = (R + 3) & ~3;
@@ -619,19 +620,12 @@ struct Backward {
         g = heads(ws.SP, Rp, RR * nh, RR, Q + 2 * H, 3 * H, rowsH3, d, ws.Tmp, H, (long)R * H, d, R, d, R, 0, 0, 1.0f, causal ? 1 : 0);
         if ((rc = bgemm<float, T, MF>(g, n * nh, st))) return rc;
         if ((rc = cast(ws.AO, ws.Tmp, H, H, H))) return rc;
-        if ((rc = gemm(ws.AO, lw.wo, nullptr, nullptr, 1, H, ws.Tmp, H))) return rc;
-        add_kernel_launch(ws.X, ws.Tmp, (size_t)M * H);
-        if ((rc = vla_check_launch("residual add"))) return rc;
-        if (x_mid_keep && hipMemcpyAsync(x_mid_keep, ws.X, (size_t)M * H * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) { vla_set_error("backward: copy failed"); return VLA_EHIP; }
+        if ((rc = gemm(ws.AO, lw.wo, nullptr, nullptr, 1, H, ws.X, H, EPI_RESIDUAL))) return rc;     // x_mid = x_in + O(...)
         if ((rc = launch_rmsnorm<T>((T *)ws.Nrm2, ws.X, (const float *)lw.ffn_norm, M, H, c.rms_eps, st))) return rc;
         if ((rc = gemm(ws.Nrm2, lw.w_gate, lw.w_up, nullptr, 2, F, ws.GU, H))) return rc;
         swiglu_fwd_kernel<T><<<blocks_for((size_t)M * F), 256, 0, st>>>((T *)ws.ACT, ws.GU, (size_t)M, F);
-        if ((rc = vla_check_launch("swiglu_fwd"))) return rc;
-        if ((rc = gemm(ws.ACT, lw.w_down, nullptr, nullptr, 1, H, ws.Tmp, F))) return rc;
-        add_kernel_launch(ws.X, ws.Tmp, (size_t)M * H);
-        return vla_check_launch("residual add");
+        return vla_check_launch("swiglu_fwd");
     }
-    void add_kernel_launch(float *x, const float *y, size_t nel);
 
     // LoRA gradients of a group of projections that share their input X [M, in] (storage type, contiguous rows) and
     // whose output gradients sit side by side in dY [M, n_p * out]: four GEMMs on the MFMA path where the shape allows,
@@ -679,7 +673,7 @@ struct Backward {
     int layer_backward(int l, const vla_lora_layer &lo, const vla_lora_layer_grads &gr, bool first) {
         const vla_layer_weights &lw = m->layers[l];
         float *x_in = ws.ckpt + (size_t)l * M * H;
-        float *x_mid = ws.QKV;                       // the fp32 projection buffer is free once QKVr exists: x_mid lives there
+        const float *x_mid = ws.X;                   // layer_recompute leaves the stream after the attention block there
         const T *Q = (const T *)ws.QKVr;
         const int Rp = (R + 3) & ~3;
         const long RR = (long)R * Rp, rowsH3 = (long)R * 3 * H;
@@ -687,7 +681,7 @@ struct Backward {
         const float isd = 1.0f / sqrtf((float)d);
         int rc;
         if (hipMemcpyAsync(ws.X, x_in, (size_t)M * H * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) { vla_set_error("backward: copy failed"); return VLA_EHIP; }
-        if ((rc = layer_forward(l, x_mid))) return rc;
+        if ((rc = layer_recompute(l))) return rc;
         // ---- down projection and SwiGLU
         if ((rc = cast(ws.dXb, ws.dX, H, H, H))) return rc;
         if ((rc = lora_group(group_of(1, &lo.down, &gr.down, F, H), ws.ACT, ws.dXb, first))) return rc;
@@ -728,14 +722,6 @@ struct Backward {
         return vla_check_launch("rmsnorm_bwd");
     }
 };
-
-__global__ void add_kernel(float *x, const float *y, size_t nel) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nel; i += (size_t)gridDim.x * 256) x[i] += y[i];
-}
-template <typename T>
-void Backward<T>::add_kernel_launch(float *x, const float *y, size_t nel) {
-    add_kernel<<<blocks_for(nel), 256, 0, st>>>(x, y, nel);
-}
 
 template <typename T>
 int backward_impl(vla_model *m, void *wsbuf, const void *patch, const int32_t *ids, const int32_t *bins, const float *coef, int N, int P,

@@ -107,14 +107,16 @@ def test_micro_batches_sum_to_the_whole_and_runs_are_bit_identical():
                 assert np.max(np.abs(a - c)) <= 2e-5 * max(np.max(np.abs(a)), 1e-30)
 
 
-def test_aligned_bf16_lora_gradients_mfma_gemms():
-    """hidden 256 / ffn 512 / head_dim 128: the forward and input-gradient GEMMs take the MFMA kernels."""
+@pytest.mark.parametrize("mode", [0, 1])
+def test_aligned_bf16_lora_gradients_mfma_gemms(mode):
+    """hidden 256 / ffn 512 / head_dim 128: the forward and input-gradient GEMMs, the attention matrices and the LoRA
+    products take the MFMA kernels; autoregressive rows and the parallel chunk (slot rows see every key)."""
     wl = vi.Workload("aligned_bw", vi.ModelShape(n_layers=2, hidden=256, n_heads=2, ffn=512, vocab=640, dtype="bf16"),
-                     batch=5, n_patches=40, n_instr=9, n_action=4)
+                     batch=5, n_patches=40, n_instr=9, n_action=4, mode=mode)
     _, lora, bins, coef, grads, logp = _run(wl, 5, rank=16, scale=0.25)
     ref, ref_logp = _oracle(wl, 5, lora, bins, coef, 5, 0.25, operand_dtype="bf16")
     _assert_logp_bf16(logp, ref_logp)
-    print(f"\n[parity] backward aligned bf16: {_compare(grads, ref, 2e-2, 1e-2)}", flush=True)
+    print(f"\n[parity] backward aligned bf16 mode {mode}: {_compare(grads, ref, 2e-2, 1e-2)}", flush=True)
 
 
 def test_one_layer_7b_width_lora_gradients():

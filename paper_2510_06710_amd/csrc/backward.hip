@@ -16,6 +16,7 @@
 // (X A^T, dY B, dY^T (X A^T), (dY B)^T X) run as GEMMs on stacked, zero-padded factors.  Gradient operands of
 // the GEMMs are rounded to the storage type like every other GEMM operand; all sums are fp32 and taken in a fixed
 // order (no atomics), so the result is reproducible bit for bit.
+#include <type_traits>
 #include <vector>
 
 #include "vla_internal.h"
@@ -56,6 +57,7 @@ struct BgemmArgs {
     const void *A, *B;
     float *C;
     int m, n, k, lda, ldb, ldc, transA, transB, accumulate, inner, tri;
+    int c_bf16;      // matrix-core kernel only: C is bf16 (no accumulate)
     float alpha;
     long sA1, sA2, sB1, sB2, sC1, sC2;
 };
@@ -195,7 +197,6 @@ __global__ void __launch_bounds__(256) bgemm_mfma_kernel(BgemmArgs g) {
     const int b = blockIdx.z, b1 = b / g.inner, b2 = b - b1 * g.inner;
     const TA *A = (const TA *)g.A + b1 * g.sA1 + b2 * g.sA2;
     const TB *B = (const TB *)g.B + b1 * g.sB1 + b2 * g.sB2;
-    float *C = g.C + b1 * g.sC1 + b2 * g.sC2;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     if (g.tri == 2 && n0 > m0 + BM - 1) return;
     const int kend = g.tri == 1 ? min(g.k, m0 + BM) : g.k;
@@ -238,7 +239,15 @@ __global__ void __launch_bounds__(256) bgemm_mfma_kernel(BgemmArgs g) {
 #pragma unroll
         for (int j = 0; j < 2; j++) {
             const int gj = n0 + wn + 16 * j + 4 * kq;
-            float *c = C + (size_t)gi * g.ldc + gj;
+            const size_t off = (size_t)(b1 * g.sC1 + b2 * g.sC2) + (size_t)gi * g.ldc + gj;
+            if (g.c_bf16) {
+                bf16_t *c = (bf16_t *)g.C + off;
+#pragma unroll
+                for (int r = 0; r < 4; r++)
+                    if (gj + r < g.n) c[r] = (bf16_t)(g.alpha * acc[i][j][r]);
+                continue;
+            }
+            float *c = g.C + off;
             if (gj + 4 <= g.n && !g.accumulate && ((size_t)c & 15) == 0) {
                 *(f32x4_t *)c = acc[i][j] * g.alpha;
                 continue;
@@ -361,8 +370,10 @@ __global__ void swiglu_bwd_kernel(T *dGU, const float *d_act, const float *GU, s
     }
 }
 
-// dX[m] += r (g dn) - x r^3 mean(x g dn), r = (mean(x^2) + eps)^(-1/2): the backward of n = RMSNorm(x) g.
-__global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(float *dX, const float *X, const float *gain, const float *dn, int H, float eps) {
+// dX[m] += r (g dn) - x r^3 mean(x g dn), r = (mean(x^2) + eps)^(-1/2): the backward of n = RMSNorm(x) g.  The new
+// dX is also written in the storage type to dXb (the operand of the GEMMs that follow).
+template <typename T>
+__global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(float *dX, T *dXb, const float *X, const float *gain, const float *dn, int H, float eps) {
     __shared__ float red[4];
     const float *x = X + (size_t)blockIdx.x * H, *d = dn + (size_t)blockIdx.x * H;
     float ss = 0.f, xd = 0.f;
@@ -372,7 +383,12 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(float *dX, const float
     const float r = 1.0f / sqrtf(ss / (float)H + eps);
     const float k = r * r * r * xd / (float)H;
     float *o = dX + (size_t)blockIdx.x * H;
-    for (int i = threadIdx.x; i < H; i += 256) o[i] += r * gain[i] * d[i] - x[i] * k;
+    T *ob = dXb + (size_t)blockIdx.x * H;
+    for (int i = threadIdx.x; i < H; i += 256) {
+        const float v = o[i] + (r * gain[i] * d[i] - x[i] * k);
+        o[i] = v;
+        ob[i] = cvt<T>(v);
+    }
 }
 
 // Head forward + backward of one read-out row (one workgroup, thread k = bin k): h = RMSNorm(x) g_f, z = h . W_bins^T,
@@ -456,6 +472,40 @@ __global__ void __launch_bounds__(256) transpose_pad_kernel(T *dst, const TS *sr
     __syncthreads();
     for (int c = ty; c < 32; c += 8)
         if (c0 + c < cols && r0 + tx < ld_dst) dst[(size_t)(c0 + c) * ld_dst + r0 + tx] = cvt<T>(tile[tx][c]);
+}
+
+// The same for bf16 -> bf16 with 16-byte accesses on both sides: 64 x 64 tiles, a thread moves eight consecutive
+// elements.  Positions r < extent of every dst row are written (zeros from `rows` on).  Needs ld_src, ld_dst and
+// extent multiples of 8 and 16-byte aligned bases (the caller checks).
+__global__ void __launch_bounds__(256) transpose_pad_bf16_kernel(bf16_t *dst, const bf16_t *src, int rows, int cols, int ld_src, int ld_dst, int extent) {
+    __shared__ __attribute__((aligned(16))) bf16_t tile[64][72];            // 144-byte rows: 16-byte aligned, 36 banks apart
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64, t = threadIdx.x;
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        const int r = (t >> 3) + 32 * h, c = (t & 7) * 8;
+        bf16x8_t v;
+#pragma unroll
+        for (int e = 0; e < 8; e++) v[e] = (bf16_t)0.f;
+        if (r0 + r < rows) {
+            const bf16_t *p = src + (size_t)(r0 + r) * ld_src + c0 + c;
+            if (c0 + c + 8 <= cols) v = *(const bf16x8_t *)p;
+            else {
+#pragma unroll
+                for (int e = 0; e < 8; e++) if (c0 + c + e < cols) v[e] = p[e];
+            }
+        }
+        *(bf16x8_t *)&tile[r][c] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        const int c = (t >> 3) + 32 * h, r = (t & 7) * 8;
+        if (c0 + c >= cols || r0 + r >= extent) continue;                   // extent is a multiple of 8: whole pieces only
+        bf16x8_t v;
+#pragma unroll
+        for (int e = 0; e < 8; e++) v[e] = tile[r + e][c];
+        *(bf16x8_t *)(dst + (size_t)(c0 + c) * ld_dst + r0 + r) = v;
+    }
 }
 
 // Stacked, zero-padded LoRA factors of a group of n_p projections that share their input (q / k / v; gate / up) as
@@ -581,6 +631,13 @@ struct Backward {
         return vla_gemm_dispatch(c, g, st);
     }
     int transpose(const void *W, int N, int K, int ldt, int col0) {
+        if constexpr (std::is_same_v<T, bf16_t>) {
+            if (N % 8 == 0 && K % 8 == 0 && ldt % 8 == 0 && col0 % 8 == 0 && ((size_t)W & 15) == 0) {
+                dim3 grid((K + 63) / 64, (N + 63) / 64);
+                transpose_pad_bf16_kernel<<<grid, 256, 0, st>>>((bf16_t *)ws.Wt + col0, (const bf16_t *)W, N, K, K, ldt, N);
+                return vla_check_launch("transpose");
+            }
+        }
         dim3 grid((K + 31) / 32, (N + 31) / 32);
         transpose_kernel<T><<<grid, 256, 0, st>>>((T *)ws.Wt, (const T *)W, N, K, ldt, col0);
         return vla_check_launch("transpose");
@@ -617,9 +674,10 @@ struct Backward {
         if ((rc = bgemm<T, T, MF>(g, n * nh, st))) return rc;
         attn_softmax_kernel<<<(unsigned)(((size_t)n * nh * R + 3) / 4), 256, 0, st>>>(ws.SP, (size_t)n * nh * R, R, Rp, full_from);
         if ((rc = vla_check_launch("attn_softmax"))) return rc;
-        g = heads(ws.SP, Rp, RR * nh, RR, Q + 2 * H, 3 * H, rowsH3, d, ws.Tmp, H, (long)R * H, d, R, d, R, 0, 0, 1.0f, causal ? 1 : 0);
+        g = heads(ws.SP, Rp, RR * nh, RR, Q + 2 * H, 3 * H, rowsH3, d, MF ? (float *)ws.AO : ws.Tmp, H, (long)R * H, d, R, d, R, 0, 0, 1.0f, causal ? 1 : 0);
+        g.c_bf16 = MF;                               // the matrix-core kernel rounds the output to the storage type itself
         if ((rc = bgemm<float, T, MF>(g, n * nh, st))) return rc;
-        if ((rc = cast(ws.AO, ws.Tmp, H, H, H))) return rc;
+        if (!MF && (rc = cast(ws.AO, ws.Tmp, H, H, H))) return rc;
         if ((rc = gemm(ws.AO, lw.wo, nullptr, nullptr, 1, H, ws.X, H, EPI_RESIDUAL))) return rc;     // x_mid = x_in + O(...)
         if ((rc = launch_rmsnorm<T>((T *)ws.Nrm2, ws.X, (const float *)lw.ffn_norm, M, H, c.rms_eps, st))) return rc;
         if ((rc = gemm(ws.Nrm2, lw.w_gate, lw.w_up, nullptr, 2, F, ws.GU, H))) return rc;
@@ -651,6 +709,15 @@ struct Backward {
         if ((rc = gemm_rows(X, ws.Wa, U, M, ws.a_rows, in)) || (rc = gemm_rows(dY, ws.Wb, V, M, ws.a_rows, wout))) return rc;
         auto tp = [&](auto *dst, auto *src, int rows, int cols, int ld_src) {
             ProfScope ps("bw_transpose", 0.0, st);
+            using D = std::remove_pointer_t<decltype(dst)>;
+            using S = std::remove_const_t<std::remove_pointer_t<decltype(src)>>;
+            if constexpr (std::is_same_v<D, bf16_t> && std::is_same_v<S, bf16_t>) {
+                if (ld_src % 8 == 0 && kp % 8 == 0 && ((size_t)dst & 15) == 0 && ((size_t)src & 15) == 0) {
+                    dim3 grid((cols + 63) / 64, (kp + 63) / 64);
+                    transpose_pad_bf16_kernel<<<grid, 256, 0, st>>>(dst, src, rows, cols, ld_src, kp, kp);
+                    return vla_check_launch("transpose_pad");
+                }
+            }
             dim3 grid((cols + 31) / 32, (kp + 31) / 32);
             transpose_pad_kernel<<<grid, 256, 0, st>>>(dst, src, rows, cols, ld_src, kp);
             return vla_check_launch("transpose_pad");
@@ -682,8 +749,7 @@ struct Backward {
         int rc;
         if (hipMemcpyAsync(ws.X, x_in, (size_t)M * H * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) { vla_set_error("backward: copy failed"); return VLA_EHIP; }
         if ((rc = layer_recompute(l))) return rc;
-        // ---- down projection and SwiGLU
-        if ((rc = cast(ws.dXb, ws.dX, H, H, H))) return rc;
+        // ---- down projection and SwiGLU (ws.dXb: ws.dX in the storage type, left by the head or the layer above)
         if ((rc = lora_group(group_of(1, &lo.down, &gr.down, F, H), ws.ACT, ws.dXb, first))) return rc;
         if ((rc = transpose(lw.w_down, H, F, H, 0))) return rc;                               // [F, H]
         if ((rc = gemm(ws.dXb, ws.Wt, nullptr, nullptr, 1, F, ws.Tmp, H))) return rc;          // d act [M, F]
@@ -692,10 +758,9 @@ struct Backward {
         if ((rc = lora_group(group_of(2, &lo.gate, &gr.gate, H, F), ws.Nrm2, ws.dGU, first))) return rc;   // gate, up adjacent in the structs
         if ((rc = transpose(lw.w_gate, F, H, 2 * F, 0)) || (rc = transpose(lw.w_up, F, H, 2 * F, F))) return rc;   // [H, 2F]
         if ((rc = gemm(ws.dGU, ws.Wt, nullptr, nullptr, 1, H, ws.Tmp, 2 * F))) return rc;      // d n2 [M, H]
-        rmsnorm_bwd_kernel<<<M, 256, 0, st>>>(ws.dX, x_mid, (const float *)lw.ffn_norm, ws.Tmp, H, c.rms_eps);
+        rmsnorm_bwd_kernel<T><<<M, 256, 0, st>>>(ws.dX, (T *)ws.dXb, x_mid, (const float *)lw.ffn_norm, ws.Tmp, H, c.rms_eps);
         if ((rc = vla_check_launch("rmsnorm_bwd"))) return rc;
-        // ---- O projection and attention (ws.dX is now d L / d x_mid)
-        if ((rc = cast(ws.dXb, ws.dX, H, H, H))) return rc;
+        // ---- O projection and attention (ws.dX, ws.dXb are now d L / d x_mid)
         if ((rc = lora_group(group_of(1, &lo.o, &gr.o, H, H), ws.AO, ws.dXb, first))) return rc;
         if ((rc = transpose(lw.wo, H, H, H, 0))) return rc;
         float *d_ao = ws.GU;                         // [M, H] fp32; the gate / up projection is no longer needed
@@ -718,7 +783,7 @@ struct Backward {
         if ((rc = lora_group(group_of(3, &lo.q, &gr.q, H, H), ws.Nrm, ws.dQKVb, first))) return rc;       // q, k, v adjacent
         if ((rc = transpose(lw.wq, H, H, 3 * H, 0)) || (rc = transpose(lw.wk, H, H, 3 * H, H)) || (rc = transpose(lw.wv, H, H, 3 * H, 2 * H))) return rc;
         if ((rc = gemm(ws.dQKVb, ws.Wt, nullptr, nullptr, 1, H, ws.GU, 3 * H))) return rc;     // d n [M, H]
-        rmsnorm_bwd_kernel<<<M, 256, 0, st>>>(ws.dX, x_in, (const float *)lw.attn_norm, ws.GU, H, c.rms_eps);
+        rmsnorm_bwd_kernel<T><<<M, 256, 0, st>>>(ws.dX, (T *)ws.dXb, x_in, (const float *)lw.attn_norm, ws.GU, H, c.rms_eps);
         return vla_check_launch("rmsnorm_bwd");
     }
 };
@@ -753,6 +818,7 @@ int backward_impl(vla_model *m, void *wsbuf, const void *patch, const int32_t *i
             bw.ws.dX, logp ? logp + (size_t)n0 * A : nullptr, x_final, (const float *)m->w.final_norm, head, bins + (size_t)n0 * A,
             coef + (size_t)n0 * A, A, R, first_row, H, c.rms_eps, 1.0f / temperature);
         if ((rc = vla_check_launch("head_bwd"))) return rc;
+        if ((rc = bw.cast(bw.ws.dXb, bw.ws.dX, H, H, H))) return rc;
         for (int l = L - 1; l >= 0; l--)
             if ((rc = bw.layer_backward(l, lora[l], grads[l], first))) return rc;
     }

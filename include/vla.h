@@ -268,12 +268,13 @@ int vla_logp_aggregate(const float *logp, size_t n_out, int inner, float *out, v
  * vla_lora_layer_grads: DEVICE fp32 outputs of the same shapes, overwritten.
  * vla_logprob_backward: teacher-forced forward over the N stored rollouts exactly as vla_logprob_recompute (same
  *   arguments, same modes), then the backward.  lora, grads: HOST arrays of n_layers entries.  coef DEVICE fp32 [N, A].
- *   logp DEVICE fp32 [N, A] out or NULL: the forward's log-probabilities of the stored bins (fp32 attention here, so
- *   equal to vla_logprob_recompute's up to the rounding differences of two evaluations).  Rollouts are processed in
+ *   logp DEVICE fp32 [N, A] out or NULL: the forward's log-probabilities of the stored bins (the kernels of
+ *   vla_logprob_recompute with every row taken through the last layer, so equal to its output up to the rounding
+ *   differences of two evaluations).  Rollouts are processed in
  *   micro-batches of max_batch; gradients are summed over micro-batches in order, every sum in a fixed order, so the
  *   result is reproducible bit for bit.  Gradient operands of the GEMMs are rounded to the storage dtype.
  *   ws: DEVICE, at least vla_backward_workspace_bytes(cfg, N, P + T, A, rank) bytes (it grows with max_batch: the
- *   residual stream of every layer is kept for one micro-batch). */
+ *   residual stream of every layer is kept for one micro-batch; 11.7 GB at the 7B shape with max_batch 32). */
 typedef struct { const void *a, *b; } vla_lora_factor;
 typedef struct { vla_lora_factor q, k, v, o, gate, up, down; } vla_lora_layer;
 typedef struct { float *da, *db; } vla_lora_grad;

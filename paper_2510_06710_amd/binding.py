@@ -75,6 +75,10 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
             raise FileNotFoundError(f"{_LIB_PATH} is not built; run `python -m paper_2510_06710_amd.build`")
+        # The device pointers and streams this library is handed belong to PyTorch's HIP runtime, so that runtime must
+        # be the one in the process: loaded first, the library's own dependency on libamdhip64 resolves to it (loaded
+        # the other way round, the system copy comes in first and the kernels then find no device).
+        import torch  # noqa: F401
         L = C.CDLL(_LIB_PATH)
         vp, i32, f32, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
         L.vla_version.restype = C.c_int

@@ -94,6 +94,16 @@ def test_tiny_fp32_lora_gradients(mode, tau):
     print(f"\n[parity] backward tiny fp32 mode={mode} tau={tau}: {_compare(grads, ref, 2e-4)}", flush=True)
 
 
+@pytest.mark.parametrize("B,P,T,A", [(1, 0, 1, 1), (2, 0, 3, 2), (1, 4, 0, 3), (3, 5, 2, 1)])
+def test_degenerate_sizes_lora_gradients(B, P, T, A):
+    """One rollout, no patches or no instruction tokens, a single action token (one row: softmax over one key)."""
+    wl = vi.scaled(vi.WORKLOADS["cfg1_tiny_fp32"], batch=B, n_patches=P, n_instr=T, n_action=A)
+    _, lora, bins, coef, grads, logp = _run(wl, 8, rank=3, scale=0.7)
+    ref, ref_logp = _oracle(wl, 8, lora, bins, coef, B, 0.7)
+    assert np.max(np.abs(logp - ref_logp)) < 1e-4
+    _compare(grads, ref, 2e-4)
+
+
 def test_micro_batches_sum_to_the_whole_and_runs_are_bit_identical():
     wl = vi.scaled(vi.WORKLOADS["cfg1_tiny_fp32"], batch=5)
     _, lora, bins, coef, g_all, _ = _run(wl, 4, rank=4, scale=1.0)

@@ -164,7 +164,8 @@ def bench_backward(args, wl, torch, vi, vb, Rollout):
     """LoRA-gradient pass (vla_logprob_backward) over a sample of the recompute workload's stored rollouts: a step is
     one call over `--backward-rollouts` rollouts in micro-batches of `--backward-micro-batch`.  Reports rollouts/s and
     the rate of the projection flops it executes (the forward once, every layer again without its down projection, and
-    the input-gradient products once), against the bf16 MFMA peak."""
+    the input-gradient products once; with --backward-keep the forward once and the input-gradient products), against
+    the bf16 MFMA peak."""
     dev = "cuda:0"
     torch.cuda.set_device(0)
     N, mb, rank = args.backward_rollouts, args.backward_micro_batch, args.lora_rank
@@ -185,7 +186,8 @@ def bench_backward(args, wl, torch, vi, vb, Rollout):
     stream = torch.cuda.current_stream()
 
     def step():
-        return run.backward(patch, ids, bins, coef, A, lora, rank, 0.5, wl.mode, None, wl.temperature, stream=stream)
+        return run.backward(patch, ids, bins, coef, A, lora, rank, 0.5, wl.mode, None, wl.temperature, stream=stream,
+                            keep_activations=args.backward_keep)
 
     for _ in range(args.warmup):
         step()
@@ -202,12 +204,14 @@ def bench_backward(args, wl, torch, vi, vb, Rollout):
     vb.lib().vla_profile_enable(0)
     rows = S + A - 1 if wl.mode == 0 else S + A
     down_share = shape.hidden * shape.ffn / shape.layer_params          # the recomputed forward skips the down projection
-    flops = (3.0 - down_share) * N * rows * 2.0 * shape.layer_params * shape.n_layers
+    passes = 2.0 if args.backward_keep else 3.0 - down_share            # forward (+ forward again) + input gradients
+    flops = passes * N * rows * 2.0 * shape.layer_params * shape.n_layers
     out = {"metric": "stored rollouts/sec, LoRA-gradient pass of the log-prob recompute (7B shape)", "value": N / (ms * 1e-3),
            "unit": "rollouts/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
-           "config": {"workload": wl.name + " (backward)", "rollouts": N, "micro_batch": mb, "rows_per_rollout": rows,
+           "config": {"workload": wl.name + " (backward)", "rollouts": N, "micro_batch": mb, "keep_activations": bool(args.backward_keep),
+                      "rows_per_rollout": rows,
                       "lora_rank": rank, "layers": shape.n_layers, "hidden": shape.hidden},
            "phases": {"projection_TFLOPs": flops / (ms * 1e-3) / 1e12, "mfma_frac": flops / (ms * 1e-3) / 1e12 / MI355X_BF16_TFLOPS},
            "kernels": {k: {"n": v["count"], "ms": round(v["ms"], 3)} for k, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"])}}
@@ -274,6 +278,9 @@ def main():
     ap.add_argument("--backward-rollouts", type=int, default=64)
     ap.add_argument("--backward-micro-batch", type=int, default=32)
     ap.add_argument("--lora-rank", type=int, default=32)
+    ap.add_argument("--backward-keep", action="store_true",
+                    help="--backward: keep every layer's activations in the first pass (larger workspace) instead of "
+                         "running each layer a second time")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one 1 GiB plain copy kernel (reference for rocprofv3 --pmc traffic counters)")
     args = ap.parse_args()

@@ -273,17 +273,22 @@ int vla_logp_aggregate(const float *logp, size_t n_out, int inner, float *out, v
  *   differences of two evaluations).  Rollouts are processed in
  *   micro-batches of max_batch; gradients are summed over micro-batches in order, every sum in a fixed order, so the
  *   result is reproducible bit for bit.  Gradient operands of the GEMMs are rounded to the storage dtype.
- *   ws: DEVICE, at least vla_backward_workspace_bytes(cfg, N, P + T, A, rank) bytes (it grows with max_batch: the
- *   residual stream of every layer is kept for one micro-batch; 11.7 GB at the 7B shape with max_batch 32). */
+ *   keep_activations = 0: the first pass is the forward of vla_logprob_recompute keeping the residual stream at every
+ *   layer input, and every layer is run a second time for its backward; ws: DEVICE, at least
+ *   vla_backward_workspace_bytes(cfg, N, P + T, A, rank) bytes (grows with max_batch; 11.7 GB at the 7B shape with
+ *   max_batch 32).  keep_activations = 1: the first pass keeps what every layer's backward reads for one micro-batch
+ *   and no layer is run twice; ws at least vla_backward_keep_workspace_bytes(...) bytes (78 GB there): for GPUs with
+ *   memory to spare.  Same gradients up to rounding (the first pass then uses the unfused kernels). */
 typedef struct { const void *a, *b; } vla_lora_factor;
 typedef struct { vla_lora_factor q, k, v, o, gate, up, down; } vla_lora_layer;
 typedef struct { float *da, *db; } vla_lora_grad;
 typedef struct { vla_lora_grad q, k, v, o, gate, up, down; } vla_lora_layer_grads;
 size_t vla_backward_workspace_bytes(const vla_config *cfg, int N, int S, int A, int rank);
+size_t vla_backward_keep_workspace_bytes(const vla_config *cfg, int N, int S, int A, int rank);
 int vla_logprob_backward(vla_model *model, void *ws, size_t ws_bytes, const void *patch, const int32_t *ids,
                          const int32_t *bins, const float *coef, int N, int P, int T, int A, int mode,
-                         const void *slot_embed, float temperature, int rank, float scale, const vla_lora_layer *lora,
-                         const vla_lora_layer_grads *grads, float *logp, void *stream);
+                         const void *slot_embed, float temperature, int rank, float scale, int keep_activations,
+                         const vla_lora_layer *lora, const vla_lora_layer_grads *grads, float *logp, void *stream);
 
 /* vla_policy_objective_noalloc -- vla_policy_objective for callers that cannot allocate device memory (code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace,

@@ -98,7 +98,9 @@ def lib() -> C.CDLL:
                                             vp, vp, vp, vp, vp]
         L.vla_backward_workspace_bytes.argtypes = [C.POINTER(vla_config), i32, i32, i32, i32]
         L.vla_backward_workspace_bytes.restype = sz
-        L.vla_logprob_backward.argtypes = [vp, vp, sz, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, f32, i32, f32,
+        L.vla_backward_keep_workspace_bytes.argtypes = [C.POINTER(vla_config), i32, i32, i32, i32]
+        L.vla_backward_keep_workspace_bytes.restype = sz
+        L.vla_logprob_backward.argtypes = [vp, vp, sz, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, f32, i32, f32, i32,
                                            C.POINTER(vla_lora_layer), C.POINTER(vla_lora_layer_grads), vp, vp]
         L.vla_debug_force_generic.argtypes = [i32]
         L.vla_profile_enable.argtypes = [i32]
@@ -207,8 +209,15 @@ def vla_backward_workspace_bytes(cfg: vla_config, N: int, S: int, A: int, rank: 
     return n
 
 
+def vla_backward_keep_workspace_bytes(cfg: vla_config, N: int, S: int, A: int, rank: int) -> int:
+    n = lib().vla_backward_keep_workspace_bytes(C.byref(cfg), N, S, A, rank)
+    if n == 0:
+        raise VlaError(VLA_EINVAL, vla_last_error())
+    return n
+
+
 def vla_logprob_backward(model, ws, patch, ids, bins, coef, N, P, T, A, mode, slot_embed, temperature, rank, scale,
-                         lora, grads, logp=None, stream=None) -> None:
+                         keep_activations, lora, grads, logp=None, stream=None) -> None:
     """lora[l][p] = (a, b) and grads[l][p] = (da, db): device tensors per layer and projection name."""
     n_layers = len(lora)
     la = (vla_lora_layer * n_layers)()
@@ -219,7 +228,7 @@ def vla_logprob_backward(model, ws, patch, ids, bins, coef, N, P, T, A, mode, sl
             f.a, f.b = lora[l][p][0].data_ptr(), lora[l][p][1].data_ptr()
             g.da, g.db = grads[l][p][0].data_ptr(), grads[l][p][1].data_ptr()
     _check(lib().vla_logprob_backward(model, _ptr(ws), ws.numel() * ws.element_size(), _ptr(patch), _ptr(ids), _ptr(bins),
-                                      _ptr(coef), N, P, T, A, mode, _ptr(slot_embed), temperature, rank, scale, la, ga,
+                                      _ptr(coef), N, P, T, A, mode, _ptr(slot_embed), temperature, rank, scale, int(bool(keep_activations)), la, ga,
                                       _ptr(logp), _stream(stream)))
 
 

@@ -553,9 +553,24 @@ __global__ void unpack_grads_kernel(LoraGroup g, const float *Cb, const float *C
 inline unsigned blocks_for(size_t n) { size_t b = (n + 255) / 256; return (unsigned)(b > 65535 * 16 ? 65535 * 16 : (b ? b : 1)); }
 
 // ---------------------------------------------------------------------------------------------- workspace
+// What the backward of one layer reads of that layer's forward: its input and the stream after the attention block
+// (fp32 [M, H]), the norm outputs, the rotated q | k | v rows, the attention probabilities
+// ([rollouts * heads][rows, rows padded to 4] fp32), the attention output, the gate | up pre-activations (fp32) and the
+// SwiGLU output.
+struct Acts {
+    float *x_in, *x_mid, *GU, *SP;
+    void *Nrm, *QKVr, *AO, *Nrm2, *ACT;
+};
+
 struct BwSpace {
-    float *X, *dX, *ckpt, *QKV, *GU, *Tmp, *SP, *dP, *UV, *Cab;
-    void *Nrm, *Nrm2, *AO, *ACT, *QKVr, *dGU, *dXb, *dQKVb, *Wt, *Wa, *Wb, *UVt, *Xt, *dYt;
+    float *X, *dX, *ckpt, *QKV, *Tmp, *dP, *UV, *Cab;
+    void *dGU, *dXb, *dQKVb, *Wt, *Wa, *Wb, *UVt, *Xt, *dYt;
+    // keep = false: one Acts set, refilled per layer by running the layer again from ckpt[l] (the first pass is the
+    // recompute's fused forward, its scratch is fw).  keep = true: one set per layer, filled by the first pass.
+    bool keep;
+    Acts one;
+    char *acts_base;
+    size_t acts_stride;
     void *fw;        // scratch of the first forward pass (vla_forward_streams)
     void *split;     // partial products of the split-K LoRA GEMMs
     size_t split_bytes;
@@ -567,21 +582,37 @@ struct BwSpace {
 
 size_t al(size_t v) { return (v + 255) & ~(size_t)255; }
 
-BwSpace plan_bw(const vla_config &c, char *base, int mb, int R, int /*rank*/) {
+// One Acts set laid out from `base` (NULL: only sized); with_streams: the set owns x_in and x_mid.
+Acts plan_acts(const vla_config &c, char *base, size_t M, size_t Mp, int mb, int R, bool with_streams, size_t *bytes) {
+    Acts a{};
+    size_t off = 0;
+    const size_t es = c.dtype == VLA_DTYPE_F32 ? 4 : 2, H = c.hidden, F = c.ffn, Rp = ((size_t)R + 3) & ~(size_t)3;
+    auto take = [&](size_t b) { char *p = base ? base + off : nullptr; off += al(b); return (void *)p; };
+    if (with_streams) { a.x_in = (float *)take(M * H * 4); a.x_mid = (float *)take(M * H * 4); }
+    a.GU = (float *)take(M * 2 * F * 4);
+    a.SP = (float *)take((size_t)mb * c.n_heads * R * Rp * 4);     // score rows start 16-byte aligned
+    a.Nrm = take(Mp * H * es);
+    a.QKVr = take(Mp * 3 * H * es);
+    a.AO = take(Mp * H * es);
+    a.Nrm2 = take(Mp * H * es);
+    a.ACT = take(Mp * F * es);
+    *bytes = off;
+    return a;
+}
+
+BwSpace plan_bw(const vla_config &c, char *base, int mb, int R, int /*rank*/, bool keep) {
     BwSpace w;
     size_t off = 0;
     const size_t es = c.dtype == VLA_DTYPE_F32 ? 4 : 2, M = (size_t)mb * R, H = c.hidden, F = c.ffn, L = c.n_layers;
     const size_t Mp = (M + 255) / 256 * 256 + VLA_KB_PAD_ROWS;
+    const size_t Rp = ((size_t)R + 3) & ~(size_t)3;
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += al(bytes); return (void *)p; };
     w.a_rows = (int)Mp;
+    w.keep = keep;
     w.X = (float *)take(M * H * 4);
     w.dX = (float *)take(M * H * 4);
-    w.ckpt = (float *)take(L * M * H * 4);
     w.QKV = (float *)take(M * 3 * H * 4);
-    w.GU = (float *)take(M * 2 * F * 4);
     w.Tmp = (float *)take(M * (F > 3 * H ? F : 3 * H) * 4);
-    const size_t Rp = ((size_t)R + 3) & ~(size_t)3;             // score rows start 16-byte aligned
-    w.SP = (float *)take((size_t)mb * c.n_heads * R * Rp * 4);
     w.dP = (float *)take((size_t)mb * c.n_heads * R * Rp * 4);
     // LoRA products (see lora_group): U | V [2][M, 256] fp32, their rounded transposes [2][256 + pad, kp], the stacked
     // factors, the transposed activations / output gradients and the two [dim, 256] results
@@ -594,19 +625,30 @@ BwSpace plan_bw(const vla_config &c, char *base, int mb, int R, int /*rank*/) {
     w.UVt = take(2 * (size_t)(256 + VLA_KB_PAD_ROWS) * kp * es);
     w.Xt = take(dim_p * kp * es);
     w.dYt = take(dim_p * kp * es);
-    w.Nrm = take(Mp * H * es);
-    w.Nrm2 = take(Mp * H * es);
-    w.AO = take(Mp * H * es);
-    w.ACT = take(Mp * F * es);
-    w.QKVr = take(Mp * 3 * H * es);
     w.dGU = take(Mp * 2 * F * es);
     w.dXb = take(Mp * H * es);
     w.dQKVb = take(Mp * 3 * H * es);
     w.Wt = take((3 * H > 2 * F ? 3 * H : 2 * F) * H * es);      // the widest transposed stack: [H, 3H] or [H, 2F] ([F, H] is smaller)
     w.rope = (float2 *)take((size_t)R * (H / c.n_heads / 2) * sizeof(float2));
-    w.fw = take(vla_forward_streams_bytes(c, mb, R));
     w.split_bytes = (size_t)8 * (M > dim_p ? M : dim_p) * 256 * 4;      // up to 8 parts of the tallest [rows, 256] product
     w.split = take(w.split_bytes);
+    size_t set_bytes = 0;
+    if (keep) {
+        plan_acts(c, nullptr, M, Mp, mb, R, true, &set_bytes);
+        w.acts_stride = set_bytes;
+        w.acts_base = (char *)take(set_bytes * L);
+        w.one = Acts{};
+        w.ckpt = nullptr;
+        w.fw = nullptr;
+    } else {
+        plan_acts(c, nullptr, M, Mp, mb, R, false, &set_bytes);
+        char *b = (char *)take(set_bytes);
+        w.one = plan_acts(c, b, M, Mp, mb, R, false, &set_bytes);
+        w.acts_base = nullptr;
+        w.acts_stride = 0;
+        w.ckpt = (float *)take(L * M * H * 4);
+        w.fw = take(vla_forward_streams_bytes(c, mb, R));
+    }
     w.total = off;
     return w;
 }
@@ -622,6 +664,7 @@ struct Backward {
     hipStream_t st;
     int n, R, M, H, F, d, nh, full_from, rank;
     float scale;
+    int ws_mb;       // rollouts per micro-batch the workspace is laid out for
     static constexpr bool MF = sizeof(T) == 2;      // bf16 storage: attention matrices on the matrix cores
 
     int gemm(const void *A, const void *W0, const void *W1, const void *W2, int n_seg, int segN, float *C, int K, int epilogue = EPI_STORE) {
@@ -655,34 +698,55 @@ struct Backward {
         return g;
     }
 
-    // Layer l again from its input in ws.X, up to the SwiGLU output, leaving in the workspace what the backward needs:
-    // Nrm, QKVr, SP (the attention probabilities), AO, X = x_mid (the stream after the attention block), Nrm2, GU and
-    // ACT.  The down projection is not run: nothing in the backward reads the layer's output.
-    int layer_recompute(int l) {
+    // The activation set of layer l: its own (keep) or the shared one, whose streams are ckpt[l] and ws.X.
+    Acts acts(int l) const {
+        if (ws.keep) {
+            size_t bytes;
+            return plan_acts(c, ws.acts_base + (size_t)l * ws.acts_stride, (size_t)ws_mb * R, (size_t)ws.a_rows, ws_mb, R, true, &bytes);
+        }
+        Acts a = ws.one;
+        a.x_in = ws.ckpt + (size_t)l * M * H;        // (the first pass packs the streams of the current micro-batch)
+        a.x_mid = ws.X;
+        return a;
+    }
+    int copy_stream(float *dst, const float *src) {
+        if (dst == src) return 0;
+        if (hipMemcpyAsync(dst, src, (size_t)M * H * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) { vla_set_error("backward: copy failed"); return VLA_EHIP; }
+        return 0;
+    }
+
+    // Layer l forward on the stream in ws.X with unfused kernels that leave in `a` everything its backward reads.
+    // with_down = false stops at the SwiGLU output (a layer run again for its backward: nothing reads its output) and
+    // leaves ws.X = the stream after the attention block.
+    int layer_forward(int l, const Acts &a, bool with_down) {
         const vla_layer_weights &lw = m->layers[l];
-        const T *Q = (const T *)ws.QKVr;
+        const T *Q = (const T *)a.QKVr;
         const int Rp = (R + 3) & ~3;
         const long RR = (long)R * Rp, rowsH3 = (long)R * 3 * H;
         const bool causal = full_from >= R;
         int rc;
-        if ((rc = launch_rmsnorm<T>((T *)ws.Nrm, ws.X, (const float *)lw.attn_norm, M, H, c.rms_eps, st))) return rc;
-        if ((rc = gemm(ws.Nrm, lw.wq, lw.wk, lw.wv, 3, H, ws.QKV, H))) return rc;
-        rope_rows_kernel<T><<<blocks_for((size_t)M * 3 * (H / 2)), 256, 0, st>>>((T *)ws.QKVr, ws.QKV, ws.rope, (size_t)M, R, H, d, 1.0f);
+        if (ws.keep && (rc = copy_stream(a.x_in, ws.X))) return rc;          // (otherwise ws.X was loaded from there)
+        if ((rc = launch_rmsnorm<T>((T *)a.Nrm, ws.X, (const float *)lw.attn_norm, M, H, c.rms_eps, st))) return rc;
+        if ((rc = gemm(a.Nrm, lw.wq, lw.wk, lw.wv, 3, H, ws.QKV, H))) return rc;
+        rope_rows_kernel<T><<<blocks_for((size_t)M * 3 * (H / 2)), 256, 0, st>>>((T *)a.QKVr, ws.QKV, ws.rope, (size_t)M, R, H, d, 1.0f);
         if ((rc = vla_check_launch("rope_rows"))) return rc;
         // scores = q k^T / sqrt(d) per (sequence, head); softmax under the mask; output = P v
-        BgemmArgs g = heads(Q, 3 * H, rowsH3, d, Q + H, 3 * H, rowsH3, d, ws.SP, Rp, RR * nh, RR, R, R, d, 0, 1, 1.0f / sqrtf((float)d), causal ? 2 : 0);
+        BgemmArgs g = heads(Q, 3 * H, rowsH3, d, Q + H, 3 * H, rowsH3, d, a.SP, Rp, RR * nh, RR, R, R, d, 0, 1, 1.0f / sqrtf((float)d), causal ? 2 : 0);
         if ((rc = bgemm<T, T, MF>(g, n * nh, st))) return rc;
-        attn_softmax_kernel<<<(unsigned)(((size_t)n * nh * R + 3) / 4), 256, 0, st>>>(ws.SP, (size_t)n * nh * R, R, Rp, full_from);
+        attn_softmax_kernel<<<(unsigned)(((size_t)n * nh * R + 3) / 4), 256, 0, st>>>(a.SP, (size_t)n * nh * R, R, Rp, full_from);
         if ((rc = vla_check_launch("attn_softmax"))) return rc;
-        g = heads(ws.SP, Rp, RR * nh, RR, Q + 2 * H, 3 * H, rowsH3, d, MF ? (float *)ws.AO : ws.Tmp, H, (long)R * H, d, R, d, R, 0, 0, 1.0f, causal ? 1 : 0);
+        g = heads(a.SP, Rp, RR * nh, RR, Q + 2 * H, 3 * H, rowsH3, d, MF ? (float *)a.AO : ws.Tmp, H, (long)R * H, d, R, d, R, 0, 0, 1.0f, causal ? 1 : 0);
         g.c_bf16 = MF;                               // the matrix-core kernel rounds the output to the storage type itself
         if ((rc = bgemm<float, T, MF>(g, n * nh, st))) return rc;
-        if (!MF && (rc = cast(ws.AO, ws.Tmp, H, H, H))) return rc;
-        if ((rc = gemm(ws.AO, lw.wo, nullptr, nullptr, 1, H, ws.X, H, EPI_RESIDUAL))) return rc;     // x_mid = x_in + O(...)
-        if ((rc = launch_rmsnorm<T>((T *)ws.Nrm2, ws.X, (const float *)lw.ffn_norm, M, H, c.rms_eps, st))) return rc;
-        if ((rc = gemm(ws.Nrm2, lw.w_gate, lw.w_up, nullptr, 2, F, ws.GU, H))) return rc;
-        swiglu_fwd_kernel<T><<<blocks_for((size_t)M * F), 256, 0, st>>>((T *)ws.ACT, ws.GU, (size_t)M, F);
-        return vla_check_launch("swiglu_fwd");
+        if (!MF && (rc = cast(a.AO, ws.Tmp, H, H, H))) return rc;
+        if ((rc = gemm(a.AO, lw.wo, nullptr, nullptr, 1, H, ws.X, H, EPI_RESIDUAL))) return rc;     // x_mid = x_in + O(...)
+        if ((rc = copy_stream(a.x_mid, ws.X))) return rc;
+        if ((rc = launch_rmsnorm<T>((T *)a.Nrm2, ws.X, (const float *)lw.ffn_norm, M, H, c.rms_eps, st))) return rc;
+        if ((rc = gemm(a.Nrm2, lw.w_gate, lw.w_up, nullptr, 2, F, a.GU, H))) return rc;
+        swiglu_fwd_kernel<T><<<blocks_for((size_t)M * F), 256, 0, st>>>((T *)a.ACT, a.GU, (size_t)M, F);
+        if ((rc = vla_check_launch("swiglu_fwd"))) return rc;
+        if (!with_down) return 0;
+        return gemm(a.ACT, lw.w_down, nullptr, nullptr, 1, H, ws.X, F, EPI_RESIDUAL);
     }
 
     // LoRA gradients of a group of projections that share their input X [M, in] (storage type, contiguous rows) and
@@ -736,42 +800,44 @@ struct Backward {
         return lg;
     }
 
-    // Backward of layer l: on entry ws.dX = d L / d x_out; on exit d L / d x_in.  x_in is ckpt[l].
+    // Backward of layer l: on entry ws.dX (and ws.dXb, its copy in the storage type) = d L / d x_out; on exit
+    // d L / d x_in.
     int layer_backward(int l, const vla_lora_layer &lo, const vla_lora_layer_grads &gr, bool first) {
         const vla_layer_weights &lw = m->layers[l];
-        float *x_in = ws.ckpt + (size_t)l * M * H;
-        const float *x_mid = ws.X;                   // layer_recompute leaves the stream after the attention block there
-        const T *Q = (const T *)ws.QKVr;
+        const Acts a = acts(l);
+        const T *Q = (const T *)a.QKVr;
         const int Rp = (R + 3) & ~3;
         const long RR = (long)R * Rp, rowsH3 = (long)R * 3 * H;
         const bool causal = full_from >= R;
         const float isd = 1.0f / sqrtf((float)d);
         int rc;
-        if (hipMemcpyAsync(ws.X, x_in, (size_t)M * H * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) { vla_set_error("backward: copy failed"); return VLA_EHIP; }
-        if ((rc = layer_recompute(l))) return rc;
+        if (!ws.keep) {                              // run the layer again from its kept input
+            if ((rc = copy_stream(ws.X, a.x_in))) return rc;
+            if ((rc = layer_forward(l, a, false))) return rc;
+        }
         // ---- down projection and SwiGLU (ws.dXb: ws.dX in the storage type, left by the head or the layer above)
-        if ((rc = lora_group(group_of(1, &lo.down, &gr.down, F, H), ws.ACT, ws.dXb, first))) return rc;
+        if ((rc = lora_group(group_of(1, &lo.down, &gr.down, F, H), a.ACT, ws.dXb, first))) return rc;
         if ((rc = transpose(lw.w_down, H, F, H, 0))) return rc;                               // [F, H]
         if ((rc = gemm(ws.dXb, ws.Wt, nullptr, nullptr, 1, F, ws.Tmp, H))) return rc;          // d act [M, F]
-        swiglu_bwd_kernel<T><<<blocks_for((size_t)M * F), 256, 0, st>>>((T *)ws.dGU, ws.Tmp, ws.GU, (size_t)M, F);
+        swiglu_bwd_kernel<T><<<blocks_for((size_t)M * F), 256, 0, st>>>((T *)ws.dGU, ws.Tmp, a.GU, (size_t)M, F);
         if ((rc = vla_check_launch("swiglu_bwd"))) return rc;
-        if ((rc = lora_group(group_of(2, &lo.gate, &gr.gate, H, F), ws.Nrm2, ws.dGU, first))) return rc;   // gate, up adjacent in the structs
+        if ((rc = lora_group(group_of(2, &lo.gate, &gr.gate, H, F), a.Nrm2, ws.dGU, first))) return rc;   // gate, up adjacent in the structs
         if ((rc = transpose(lw.w_gate, F, H, 2 * F, 0)) || (rc = transpose(lw.w_up, F, H, 2 * F, F))) return rc;   // [H, 2F]
         if ((rc = gemm(ws.dGU, ws.Wt, nullptr, nullptr, 1, H, ws.Tmp, 2 * F))) return rc;      // d n2 [M, H]
-        rmsnorm_bwd_kernel<T><<<M, 256, 0, st>>>(ws.dX, (T *)ws.dXb, x_mid, (const float *)lw.ffn_norm, ws.Tmp, H, c.rms_eps);
+        rmsnorm_bwd_kernel<T><<<M, 256, 0, st>>>(ws.dX, (T *)ws.dXb, a.x_mid, (const float *)lw.ffn_norm, ws.Tmp, H, c.rms_eps);
         if ((rc = vla_check_launch("rmsnorm_bwd"))) return rc;
         // ---- O projection and attention (ws.dX, ws.dXb are now d L / d x_mid)
-        if ((rc = lora_group(group_of(1, &lo.o, &gr.o, H, H), ws.AO, ws.dXb, first))) return rc;
+        if ((rc = lora_group(group_of(1, &lo.o, &gr.o, H, H), a.AO, ws.dXb, first))) return rc;
         if ((rc = transpose(lw.wo, H, H, H, 0))) return rc;
-        float *d_ao = ws.GU;                         // [M, H] fp32; the gate / up projection is no longer needed
+        float *d_ao = a.GU;                          // [M, H] fp32; the gate / up pre-activations are no longer needed
         if ((rc = gemm(ws.dXb, ws.Wt, nullptr, nullptr, 1, H, d_ao, H))) return rc;
         float *dqkv = ws.Tmp;                        // [M, 3H] fp32: d q | d k | d v (q, k still in the rotated frame)
         // dP = dO v^T ; dV = P^T dO ; dS = P (dP - rowsum(P dP)) ; dQ = dS k / sqrt(d) ; dK = dS^T q / sqrt(d)
         BgemmArgs g = heads(d_ao, H, (long)R * H, d, Q + 2 * H, 3 * H, rowsH3, d, ws.dP, Rp, RR * nh, RR, R, R, d, 0, 1, 1.0f, causal ? 2 : 0);
         if ((rc = bgemm<float, T, MF>(g, n * nh, st))) return rc;
-        g = heads(ws.SP, Rp, RR * nh, RR, d_ao, H, (long)R * H, d, dqkv + 2 * H, 3 * H, rowsH3, d, R, d, R, 1, 0, 1.0f, 0);
+        g = heads(a.SP, Rp, RR * nh, RR, d_ao, H, (long)R * H, d, dqkv + 2 * H, 3 * H, rowsH3, d, R, d, R, 1, 0, 1.0f, 0);
         if ((rc = bgemm<float, float, MF>(g, n * nh, st))) return rc;
-        attn_ds_kernel<<<(unsigned)(((size_t)n * nh * R + 3) / 4), 256, 0, st>>>(ws.dP, ws.SP, (size_t)n * nh * R, R, Rp, full_from);
+        attn_ds_kernel<<<(unsigned)(((size_t)n * nh * R + 3) / 4), 256, 0, st>>>(ws.dP, a.SP, (size_t)n * nh * R, R, Rp, full_from);
         if ((rc = vla_check_launch("attn_ds"))) return rc;
         g = heads(ws.dP, Rp, RR * nh, RR, Q + H, 3 * H, rowsH3, d, dqkv, 3 * H, rowsH3, d, R, d, R, 0, 0, isd, causal ? 1 : 0);
         if ((rc = bgemm<float, T, MF>(g, n * nh, st))) return rc;
@@ -780,17 +846,17 @@ struct Backward {
         rope_rows_kernel<T><<<blocks_for((size_t)M * 3 * (H / 2)), 256, 0, st>>>((T *)ws.dQKVb, dqkv, ws.rope, (size_t)M, R, H, d, -1.0f);
         if ((rc = vla_check_launch("rope_rows (transpose)"))) return rc;
         // ---- Q / K / V projections and the attention norm
-        if ((rc = lora_group(group_of(3, &lo.q, &gr.q, H, H), ws.Nrm, ws.dQKVb, first))) return rc;       // q, k, v adjacent
+        if ((rc = lora_group(group_of(3, &lo.q, &gr.q, H, H), a.Nrm, ws.dQKVb, first))) return rc;       // q, k, v adjacent
         if ((rc = transpose(lw.wq, H, H, 3 * H, 0)) || (rc = transpose(lw.wk, H, H, 3 * H, H)) || (rc = transpose(lw.wv, H, H, 3 * H, 2 * H))) return rc;
-        if ((rc = gemm(ws.dQKVb, ws.Wt, nullptr, nullptr, 1, H, ws.GU, 3 * H))) return rc;     // d n [M, H]
-        rmsnorm_bwd_kernel<T><<<M, 256, 0, st>>>(ws.dX, (T *)ws.dXb, x_in, (const float *)lw.attn_norm, ws.GU, H, c.rms_eps);
+        if ((rc = gemm(ws.dQKVb, ws.Wt, nullptr, nullptr, 1, H, a.GU, 3 * H))) return rc;      // d n [M, H]
+        rmsnorm_bwd_kernel<T><<<M, 256, 0, st>>>(ws.dX, (T *)ws.dXb, a.x_in, (const float *)lw.attn_norm, a.GU, H, c.rms_eps);
         return vla_check_launch("rmsnorm_bwd");
     }
 };
 
 template <typename T>
-int backward_impl(vla_model *m, void *wsbuf, const void *patch, const int32_t *ids, const int32_t *bins, const float *coef, int N, int P,
-                  int T_, int A, int mode, const void *slot_embed, float temperature, int rank, float scale,
+int backward_impl(vla_model *m, void *wsbuf, bool keep, const void *patch, const int32_t *ids, const int32_t *bins, const float *coef, int N,
+                  int P, int T_, int A, int mode, const void *slot_embed, float temperature, int rank, float scale,
                   const vla_lora_layer *lora, const vla_lora_layer_grads *grads, float *logp, hipStream_t st) {
     const vla_config &c = m->cfg;
     const int S = P + T_, H = c.hidden, L = c.n_layers;
@@ -799,19 +865,30 @@ int backward_impl(vla_model *m, void *wsbuf, const void *patch, const int32_t *i
     const int mb = bw_micro_batch(c, N);
     const T *head = (const T *)m->w.lm_head + (size_t)(c.vocab - VLA_N_BINS) * H;
     int rc;
-    Backward<T> bw{m, c, plan_bw(c, (char *)wsbuf, mb, R, rank), st, 0, R, 0, H, c.ffn, H / c.n_heads, c.n_heads,
-                   mode == VLA_MODE_AR ? 0x7fffffff : S, rank, scale};
+    Backward<T> bw{m, c, plan_bw(c, (char *)wsbuf, mb, R, rank, keep), st, 0, R, 0, H, c.ffn, H / c.n_heads, c.n_heads,
+                   mode == VLA_MODE_AR ? 0x7fffffff : S, rank, scale, mb};
     if ((rc = launch_rope_table(bw.ws.rope, R, 0, bw.d, c.rope_theta, st))) return rc;
     bool first = true;
     for (int n0 = 0; n0 < N; n0 += mb, first = false) {
         const int n = (N - n0 < mb) ? N - n0 : mb;
         bw.n = n; bw.M = n * R;
         const size_t MH = (size_t)bw.M * H;
-        // (1) the forward pass of the recompute itself (its fused kernels), keeping every layer's input
         const T *pp = patch ? (const T *)patch + (size_t)n0 * P * H : nullptr;
+        const int32_t *ii = ids ? ids + (size_t)n0 * T_ : nullptr;
         const float *x_final = nullptr;
-        if ((rc = vla_forward_streams(m, bw.ws.fw, mb, pp, ids ? ids + (size_t)n0 * T_ : nullptr, bins + (size_t)n0 * A, n, P, T_, A, mode,
-                                      slot_embed, bw.ws.ckpt, &x_final, st))) return rc;
+        if (keep) {
+            // (1) forward with the unfused kernels, every layer leaving what its backward reads in a set of its own
+            if ((rc = launch_embed_prefix<T>(bw.ws.X, pp, ii, (const T *)m->w.embed, n, P, T_, R, H, c.vocab, st))) return rc;
+            if (mode == VLA_MODE_AR) {
+                if ((rc = launch_embed_tokens<T>(bw.ws.X, bins + (size_t)n0 * A, A, A - 1, (const T *)m->w.embed, n, R, S, H, c.vocab, st))) return rc;
+            } else if ((rc = launch_embed_slots<T>(bw.ws.X, (const T *)slot_embed, n, A, R, S, H, st))) return rc;
+            for (int l = 0; l < L; l++)
+                if ((rc = bw.layer_forward(l, bw.acts(l), true))) return rc;
+            x_final = bw.ws.X;
+        } else {
+            // (1) the forward pass of the recompute itself (its fused kernels), keeping every layer's input
+            if ((rc = vla_forward_streams(m, bw.ws.fw, mb, pp, ii, bins + (size_t)n0 * A, n, P, T_, A, mode, slot_embed, bw.ws.ckpt, &x_final, st))) return rc;
+        }
         fill_kernel<<<blocks_for(MH), 256, 0, st>>>(bw.ws.dX, MH, 0.f);
         if ((rc = vla_check_launch("fill"))) return rc;
         head_bwd_kernel<T><<<n * A, 256, (size_t)(H + VLA_N_BINS) * sizeof(float), st>>>(
@@ -842,13 +919,21 @@ size_t vla_backward_workspace_bytes(const vla_config *cfg, int N, int S, int A, 
     if (N <= 0 || S <= 0 || A <= 0 || rank <= 0) { vla_set_error("N, S, A and rank must be positive"); return 0; }
     if (S + A > cfg->max_seq + 1) { vla_set_error("S + A exceeds capacity"); return 0; }
     const int R = (S + A <= cfg->max_seq) ? S + A : S + A - 1;
-    return plan_bw(*cfg, nullptr, bw_micro_batch(*cfg, N), R, rank).total;
+    return plan_bw(*cfg, nullptr, bw_micro_batch(*cfg, N), R, rank, false).total;
+}
+
+size_t vla_backward_keep_workspace_bytes(const vla_config *cfg, int N, int S, int A, int rank) {
+    if (vla_check_config(cfg)) return 0;
+    if (N <= 0 || S <= 0 || A <= 0 || rank <= 0) { vla_set_error("N, S, A and rank must be positive"); return 0; }
+    if (S + A > cfg->max_seq + 1) { vla_set_error("S + A exceeds capacity"); return 0; }
+    const int R = (S + A <= cfg->max_seq) ? S + A : S + A - 1;
+    return plan_bw(*cfg, nullptr, bw_micro_batch(*cfg, N), R, rank, true).total;
 }
 
 int vla_logprob_backward(vla_model *m, void *ws, size_t ws_bytes, const void *patch, const int32_t *ids, const int32_t *bins,
                          const float *coef, int N, int P, int T, int A, int mode, const void *slot_embed, float temperature,
-                         int rank, float scale, const vla_lora_layer *lora, const vla_lora_layer_grads *grads, float *logp,
-                         void *stream) {
+                         int rank, float scale, int keep_activations, const vla_lora_layer *lora,
+                         const vla_lora_layer_grads *grads, float *logp, void *stream) {
     if (!m || !ws || !bins || !coef || !lora || !grads) { vla_set_error("model, ws, bins, coef, lora or grads is NULL"); return VLA_EINVAL; }
     if (mode != VLA_MODE_AR && mode != VLA_MODE_PARALLEL_CHUNK) { vla_set_error("unknown mode %d", mode); return VLA_EINVAL; }
     if (N <= 0 || P < 0 || T < 0 || P + T < 1 || A <= 0 || rank <= 0) { vla_set_error("need N, A, rank >= 1, P, T >= 0, P + T >= 1"); return VLA_EINVAL; }
@@ -864,12 +949,13 @@ int vla_logprob_backward(vla_model *m, void *ws, size_t ws_bytes, const void *pa
     if ((size_t)mb * R * (size_t)(c.ffn > 3 * c.hidden ? 2 * c.ffn : 3 * c.hidden) * 4 >= ((size_t)1 << 40)) { vla_set_error("micro-batch too large"); return VLA_ESHAPE; }
     if (3 * rank > 256) { vla_set_error("rank %d unsupported (at most 85: three stacked factors fill 256 rows)", rank); return VLA_ESHAPE; }
     if (int rc = vla_check_rows_per_pass(c, mb, R)) return rc;
-    const size_t need = plan_bw(c, nullptr, mb, R, rank).total;
+    const bool keep = keep_activations != 0;
+    const size_t need = plan_bw(c, nullptr, mb, R, rank, keep).total;
     if (ws_bytes < need) { vla_set_error("workspace %zu bytes, need %zu", ws_bytes, need); return VLA_EWORKSPACE; }
     hipStream_t st = (hipStream_t)stream;
     return c.dtype == VLA_DTYPE_F32
-               ? backward_impl<float>(m, ws, patch, ids, bins, coef, N, P, T, A, mode, slot_embed, temperature, rank, scale, lora, grads, logp, st)
-               : backward_impl<bf16_t>(m, ws, patch, ids, bins, coef, N, P, T, A, mode, slot_embed, temperature, rank, scale, lora, grads, logp, st);
+               ? backward_impl<float>(m, ws, keep, patch, ids, bins, coef, N, P, T, A, mode, slot_embed, temperature, rank, scale, lora, grads, logp, st)
+               : backward_impl<bf16_t>(m, ws, keep, patch, ids, bins, coef, N, P, T, A, mode, slot_embed, temperature, rank, scale, lora, grads, logp, st);
 }
 
 }  // extern "C"

@@ -85,18 +85,21 @@ class Rollout:
         return logp, ent, value, logits
 
 
-    def backward(self, patch, ids, bins, coef, A, lora, rank, scale, mode=0, slot_embed=None, temperature=1.0, stream=None):
+    def backward(self, patch, ids, bins, coef, A, lora, rank, scale, mode=0, slot_embed=None, temperature=1.0, stream=None,
+                 keep_activations=False):
         """LoRA gradients of sum(coef * logp): lora[l][p] = (a, b) device tensors in the storage dtype.  Returns
-        (grads, logp) with grads[l][p] = (da, db) fp32 device tensors."""
+        (grads, logp) with grads[l][p] = (da, db) fp32 device tensors.  keep_activations: hand the library the larger
+        workspace with which it keeps every layer's activations instead of running each layer a second time."""
         N, P = patch.shape[0], patch.shape[1]
         T = ids.shape[1]
-        ws = self._buf("ws_bw", vb.vla_backward_workspace_bytes(self.cfg, N, P + T, A, rank))
+        size = vb.vla_backward_keep_workspace_bytes if keep_activations else vb.vla_backward_workspace_bytes
+        ws = self._buf("ws_bw", size(self.cfg, N, P + T, A, rank))
         grads = [{p: (torch.empty(f[0].shape, dtype=torch.float32, device=self.device),
                       torch.empty(f[1].shape, dtype=torch.float32, device=self.device)) for p, f in layer.items()}
                  for layer in lora]
         logp = torch.empty(N, A, dtype=torch.float32, device=self.device)
         vb.vla_logprob_backward(self.model.handle, ws, patch, ids, bins, coef, N, P, T, A, mode, slot_embed, temperature,
-                                rank, scale, lora, grads, logp, stream)
+                                rank, scale, keep_activations, lora, grads, logp, stream)
         return grads, logp
 
 

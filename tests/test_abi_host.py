@@ -148,7 +148,7 @@ def test_backward_rejects_bad_arguments_without_a_device():
             f, g = getattr(lora[l], name), getattr(grads[l], name)
             f.a = f.b = g.da = g.db = 0x1000
     b = lambda **k: [h, p, k.get("ws", big), p, p, k.get("bins", p), k.get("coef", p), k.get("N", 4), 48, 16, k.get("A", 7),
-                     k.get("mode", 0), None, k.get("tau", 1.0), k.get("rank", 8), 0.5, k.get("lora", lora), grads, None, None]
+                     k.get("mode", 0), None, k.get("tau", 1.0), k.get("rank", 8), 0.5, k.get("keep", 0), k.get("lora", lora), grads, None, None]
     assert L.vla_logprob_backward(*b(coef=None)) == vb.VLA_EINVAL
     assert L.vla_logprob_backward(*b(lora=None)) == vb.VLA_EINVAL
     assert L.vla_logprob_backward(*b(tau=0.0)) == vb.VLA_EINVAL
@@ -157,6 +157,10 @@ def test_backward_rejects_bad_arguments_without_a_device():
     assert L.vla_logprob_backward(*b(A=30)) == vb.VLA_ESHAPE             # 64 + 30 - 1 rows > max_seq 80
     assert L.vla_logprob_backward(*b(rank=100)) == vb.VLA_ESHAPE         # three stacked factors exceed 256 rows
     assert L.vla_logprob_backward(*b(ws=100)) == vb.VLA_EWORKSPACE
+    small, large = vb.vla_backward_workspace_bytes(cfg, 4, 64, 7, 8), vb.vla_backward_keep_workspace_bytes(cfg, 4, 64, 7, 8)
+    # (the size queries cover the longer of the two modes' rows, so only clearly smaller buffers are certain to fail)
+    assert L.vla_logprob_backward(*b(ws=small // 2)) == vb.VLA_EWORKSPACE
+    assert L.vla_logprob_backward(*b(ws=large // 2, keep=1)) == vb.VLA_EWORKSPACE
     lora[1].gate.b = None
     assert L.vla_logprob_backward(*b()) == vb.VLA_EINVAL and "layer 1" in vb.vla_last_error()
     assert vb.vla_backward_workspace_bytes(cfg, 4, 64, 7, 8) > 4 * 70 * 256 * 4 * cfg.n_layers

@@ -38,7 +38,7 @@ def _lora(shape, rank, seed, sigma=0.05):
     return out
 
 
-def _run(wl, seed, rank, scale, n=None, max_batch=None):
+def _run(wl, seed, rank, scale, n=None, max_batch=None, keep=False):
     n = wl.batch if n is None else n
     case = GpuCase(wl, seed, max_batch=max_batch or wl.batch)
     lora = _lora(wl.shape, rank, seed + 50)
@@ -48,7 +48,7 @@ def _run(wl, seed, rank, scale, n=None, max_batch=None):
     dev_lora = [{p: (a.to(DEV), b.to(DEV)) for p, (a, b) in layer.items()} for layer in lora]
     slot = case.synth.slot_embed(wl.n_action) if wl.mode == 1 else None
     grads, logp = case.run.backward(patch, ids, bins.to(DEV), coef.to(DEV), wl.n_action, dev_lora, rank, scale, wl.mode, slot,
-                                    wl.temperature)
+                                    wl.temperature, keep_activations=keep)
     torch.cuda.synchronize()
     return case, lora, bins.numpy(), coef.numpy().astype(np.float64), grads, logp.cpu().numpy()
 
@@ -85,10 +85,12 @@ def _compare(grads, ref, rel_max, rel_rms=None):
     return worst
 
 
+@pytest.mark.parametrize("keep", [False, True])
 @pytest.mark.parametrize("mode,tau", [(0, 1.0), (0, 1.6), (1, 1.0)])
-def test_tiny_fp32_lora_gradients(mode, tau):
+def test_tiny_fp32_lora_gradients(mode, tau, keep):
+    """keep: the first pass keeps every layer's activations (larger workspace) instead of running each layer twice."""
     wl = vi.scaled(vi.WORKLOADS["cfg1_tiny_fp32"], batch=4, mode=mode, temperature=tau)
-    _, lora, bins, coef, grads, logp = _run(wl, 3, rank=8, scale=0.5)
+    _, lora, bins, coef, grads, logp = _run(wl, 3, rank=8, scale=0.5, keep=keep)
     ref, ref_logp = _oracle(wl, 3, lora, bins, coef, 4, 0.5)
     assert np.max(np.abs(logp - ref_logp)) < 1e-4
     print(f"\n[parity] backward tiny fp32 mode={mode} tau={tau}: {_compare(grads, ref, 2e-4)}", flush=True)
@@ -104,11 +106,12 @@ def test_degenerate_sizes_lora_gradients(B, P, T, A):
     _compare(grads, ref, 2e-4)
 
 
-def test_micro_batches_sum_to_the_whole_and_runs_are_bit_identical():
+@pytest.mark.parametrize("keep", [False, True])
+def test_micro_batches_sum_to_the_whole_and_runs_are_bit_identical(keep):
     wl = vi.scaled(vi.WORKLOADS["cfg1_tiny_fp32"], batch=5)
-    _, lora, bins, coef, g_all, _ = _run(wl, 4, rank=4, scale=1.0)
-    _, _, _, _, g_again, _ = _run(wl, 4, rank=4, scale=1.0)
-    _, _, _, _, g_mb, _ = _run(wl, 4, rank=4, scale=1.0, max_batch=2)            # passes of 2, 2 and 1 rollouts
+    _, lora, bins, coef, g_all, _ = _run(wl, 4, rank=4, scale=1.0, keep=keep)
+    _, _, _, _, g_again, _ = _run(wl, 4, rank=4, scale=1.0, keep=keep)
+    _, _, _, _, g_mb, _ = _run(wl, 4, rank=4, scale=1.0, max_batch=2, keep=keep)   # passes of 2, 2 and 1 rollouts
     for l in range(wl.shape.n_layers):
         for p in bo.PROJ:
             for i in (0, 1):
@@ -117,22 +120,24 @@ def test_micro_batches_sum_to_the_whole_and_runs_are_bit_identical():
                 assert np.max(np.abs(a - c)) <= 2e-5 * max(np.max(np.abs(a)), 1e-30)
 
 
+@pytest.mark.parametrize("keep", [False, True])
 @pytest.mark.parametrize("mode", [0, 1])
-def test_aligned_bf16_lora_gradients_mfma_gemms(mode):
+def test_aligned_bf16_lora_gradients_mfma_gemms(mode, keep):
     """hidden 256 / ffn 512 / head_dim 128: the forward and input-gradient GEMMs, the attention matrices and the LoRA
     products take the MFMA kernels; autoregressive rows and the parallel chunk (slot rows see every key)."""
     wl = vi.Workload("aligned_bw", vi.ModelShape(n_layers=2, hidden=256, n_heads=2, ffn=512, vocab=640, dtype="bf16"),
                      batch=5, n_patches=40, n_instr=9, n_action=4, mode=mode)
-    _, lora, bins, coef, grads, logp = _run(wl, 5, rank=16, scale=0.25)
+    _, lora, bins, coef, grads, logp = _run(wl, 5, rank=16, scale=0.25, keep=keep)
     ref, ref_logp = _oracle(wl, 5, lora, bins, coef, 5, 0.25, operand_dtype="bf16")
     _assert_logp_bf16(logp, ref_logp)
     print(f"\n[parity] backward aligned bf16 mode {mode}: {_compare(grads, ref, 2e-2, 1e-2)}", flush=True)
 
 
-def test_one_layer_7b_width_lora_gradients():
+@pytest.mark.parametrize("keep", [False, True])
+def test_one_layer_7b_width_lora_gradients(keep):
     wl = vi.scaled(vi.WORKLOADS["cfg5_7b_recompute_n512"], n_layers=1, batch=2)
-    print("\n[7b] backward: 1 layer of 7B width, 2 rollouts x 294 rows, rank 32", flush=True)
-    _, lora, bins, coef, grads, logp = _run(wl, 6, rank=32, scale=0.5)
+    print(f"\n[7b] backward: 1 layer of 7B width, 2 rollouts x 294 rows, rank 32, keep={keep}", flush=True)
+    _, lora, bins, coef, grads, logp = _run(wl, 6, rank=32, scale=0.5, keep=keep)
     ref, ref_logp = _oracle(wl, 6, lora, bins, coef, 2, 0.5, operand_dtype="bf16")
     _assert_logp_bf16(logp, ref_logp)
     print(f"[parity] backward 1-layer 7B width: {_compare(grads, ref, 2e-2, 1e-2)}", flush=True)

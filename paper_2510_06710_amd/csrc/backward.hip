@@ -8,7 +8,8 @@
 // tokens; (3) layers in reverse: the layer's forward is run again from its kept input, this time with unfused
 // kernels that leave every intermediate the chain rule needs, then the chain rule walks back through the
 // down projection, SwiGLU, gate / up, the FFN norm, the O projection, attention, the rotation, Q / K / V and the
-// attention norm.  Every large contraction -- the seven forward projections and the four input-gradient products
+// attention norm.  With keep_activations, (1) is instead a forward with the unfused kernels that leaves every layer's
+// intermediates in a set of its own (one per layer, for one micro-batch), and (3) runs no layer a second time.  Every large contraction -- the seven forward projections and the four input-gradient products
 // dY . W, which run as the same "activation x weight^T" GEMM on a transposed copy of the weights made per layer --
 // goes through the library's GEMM dispatch (MFMA kernels for bf16 shapes they cover).  Attention (scores, softmax,
 // its backward) runs on materialised [rows x rows] matrices per (rollout, head) with a batched tile kernel (matrix

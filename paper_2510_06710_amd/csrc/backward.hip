@@ -25,7 +25,6 @@
 namespace {
 
 template <typename T> __device__ __forceinline__ float ld(const T *p) { return (float)*p; }
-template <typename T> __device__ __forceinline__ float ld_elem(const T *p) { return (float)*p; }
 template <typename T> __device__ __forceinline__ T cvt(float v) { return (T)v; }
 
 __device__ __forceinline__ float bsum256(float v, float *red) {
@@ -154,18 +153,18 @@ template <> __device__ __forceinline__ void bg_load8<bf16_t>(const bf16_t *p, fl
 }
 
 // Stages op(X)[row0 .. row0 + 63][k0 .. k0 + 31] into tile[0] (bf16 heads) and, for fp32 operands, tile[1] (tails).
-// k_contig: X is stored [row][k] (leading dimension ld), else [k][row].  Elements outside rows < lim, k < kend are 0.
+// k_contig: X is stored [row][k] (leading dimension ldx), else [k][row].  Elements outside rows < lim, k < kend are 0.
 template <typename T, bool SPLIT>
-__device__ __forceinline__ void bg_stage(bf16_t (*tile)[64][BG_LD], const T *X, bool k_contig, int ld, int row0, int lim, int k0, int kend) {
+__device__ __forceinline__ void bg_stage(bf16_t (*tile)[64][BG_LD], const T *X, bool k_contig, int ldx, int row0, int lim, int k0, int kend) {
     const int t = threadIdx.x;
     float v[8];
     if (k_contig) {
         const int row = t >> 2, kk = (t & 3) * 8, gi = row0 + row, gk = k0 + kk;
-        const T *p = X + (size_t)gi * ld + gk;
+        const T *p = X + (size_t)gi * ldx + gk;
         if (gi < lim && gk + 8 <= kend && ((size_t)p & 15) == 0) bg_load8<T>(p, v);
         else {
 #pragma unroll
-            for (int e = 0; e < 8; e++) v[e] = (gi < lim && gk + e < kend) ? ld_elem(p + e) : 0.f;
+            for (int e = 0; e < 8; e++) v[e] = (gi < lim && gk + e < kend) ? ld(p + e) : 0.f;
         }
         bf16x8_t hi, lo;
 #pragma unroll
@@ -174,11 +173,11 @@ __device__ __forceinline__ void bg_stage(bf16_t (*tile)[64][BG_LD], const T *X, 
         if constexpr (SPLIT) *(bf16x8_t *)&tile[1][row][bg_col(row, kk)] = lo;
     } else {
         const int kk = t >> 3, r0 = (t & 7) * 8, gk = k0 + kk, gi = row0 + r0;
-        const T *p = X + (size_t)gk * ld + gi;
+        const T *p = X + (size_t)gk * ldx + gi;
         if (gk < kend && gi + 8 <= lim && ((size_t)p & 15) == 0) bg_load8<T>(p, v);
         else {
 #pragma unroll
-            for (int e = 0; e < 8; e++) v[e] = (gk < kend && gi + e < lim) ? ld_elem(p + e) : 0.f;
+            for (int e = 0; e < 8; e++) v[e] = (gk < kend && gi + e < lim) ? ld(p + e) : 0.f;
         }
 #pragma unroll
         for (int e = 0; e < 8; e++) {

@@ -400,10 +400,13 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
         }
         if (!have_nrm && (rc = run_rmsnorm<T>(c, ws.Nrm, ws.X, lw.attn_norm, M, 0, st))) return rc;
         have_nrm = false;
+        // single-row forwards stream the weights from HBM: hand the GEMMs the repacked copies as well, where they exist
+        const vla_layer_weights *pk = (ra.R == 1 && !m->packed.empty() && kblocked_shape_ok(c)) ? &m->packed[l] : nullptr;
         int ds = 0;
         GemmArgs g{};
         g.A = ws.Nrm; g.W[0] = lw.wq; g.W[1] = lw.wk; g.W[2] = lw.wv; g.n_seg = 3; g.segN = H;
         g.C = ws.QKV; g.M = M; g.K = H; g.epilogue = EPI_STORE; g.a_rows = ws.a_rows;
+        if (pk) { g.Wkb[0] = pk->wq; g.Wkb[1] = pk->wk; g.Wkb[2] = pk->wv; }
         // multi-row bf16 forwards at head_dim 128: rotation and KV write ride the projection's epilogue
         int fused = 0;
         if (c.dtype == VLA_DTYPE_BF16 && ra.R > 1 && d == 128 && !(force_generic() & (1 | 16))) {
@@ -444,6 +447,7 @@ static int run_layers(const vla_model *m, const Workspace &ws, const RowsArgs &r
         g = GemmArgs{};
         g.A = ws.Nrm; g.W[0] = lw.w_gate; g.W[1] = lw.w_up; g.n_seg = 2; g.segN = F; g.C = ws.ACT; g.M = M; g.K = H;
         g.epilogue = EPI_SWIGLU; g.a_rows = ws.a_rows;
+        if (pk) { g.Wkb[0] = pk->w_gate; g.Wkb[1] = pk->w_up; }
         if ((rc = run_gemm<T>(c, g, ws.skinny, st))) return rc;
         g = GemmArgs{};
         g.A = ws.ACT; g.W[0] = lw.w_down; g.n_seg = 1; g.segN = H; g.C = ws.X; g.M = M; g.K = F; g.epilogue = EPI_RESIDUAL; g.a_rows = ws.a_rows;

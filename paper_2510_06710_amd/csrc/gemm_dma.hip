@@ -66,6 +66,8 @@ struct DmaGemmParams {
     int group;
     int splits;      // > 1: K is cut into `splits` equal ranges; item = range * tiles + tile, and range r of an
                      // EPI_STORE launch writes its fp32 partial product to C + r * M * N
+    int wkb;         // row-major activations with k-blocked (repacked) weights: the decode forwards, whose weight
+                     // stream comes from HBM and then moves as whole cache lines (w_rows as in the k-blocked layout)
 };
 
 template <int OFF>
@@ -264,12 +266,14 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
     // instructions each; SwiGLU tiles interleave 64 gate and 64 up rows per wave of the multiply side, so
     // loading wave w takes 64 rows of W0 (w even) or W1 (w odd).
     const int chunk_off = ((lane & 3) ^ ((lane >> 3) & 3)) << 4;
+    const bool WKB = KB ? true : (p.wkb != 0);   // the weights' layout (a compile-time constant in the k-blocked kernels)
     const int row_bytes = KB ? 64 : K * 2;       // distance of consecutive tile rows of one half tile
+    const int w_row_bytes = WKB ? 64 : K * 2;
     const int a_thread_off = (wave * 64 + (lane >> 2)) * row_bytes + chunk_off;
-    const int w_thread_off = (((EPI == EPI_SWIGLU) ? (wave >> 1) * 64 : wave * 64) + (lane >> 2)) * row_bytes + chunk_off;
+    const int w_thread_off = (((EPI == EPI_SWIGLU) ? (wave >> 1) * 64 : wave * 64) + (lane >> 2)) * w_row_bytes + chunk_off;
     const int tile_bytes = BM * K * 2;
     // distance of consecutive half tiles: 64 bytes along the row, or one 32-column block of all rows
-    const unsigned a_half = KB ? (unsigned)p.a_rows * 64u : 64u, w_half = KB ? (unsigned)p.w_rows * 64u : 64u;
+    const unsigned a_half = KB ? (unsigned)p.a_rows * 64u : 64u, w_half = WKB ? (unsigned)p.w_rows * 64u : 64u;
     __amdgpu_buffer_rsrc_t a_rsrc, w_rsrc;
     int ld_item, ld_h;
     int nx_tm, nx_tn, nx_split;
@@ -279,18 +283,18 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
         vla_tile_of_block(it - split * n_tiles, p.tiles_m, p.tiles_n, tm, tn, p.group);
         // first element of this item's K range within a row panel: k-blocked, whole 32-column blocks; row-major, columns
         const size_t a_k0 = KB ? (size_t)split * nh * (a_half / 2) : (size_t)split * nh * HK;
-        const size_t w_k0 = KB ? (size_t)split * nh * (w_half / 2) : (size_t)split * nh * HK;
+        const size_t w_k0 = WKB ? (size_t)split * nh * (w_half / 2) : (size_t)split * nh * HK;
         if (KB) a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * 32 + a_k0), (short)0, (int)((unsigned)(nh - 1) * a_half + 16384u), 0x00020000);
         else a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(p.A + (size_t)tm * BM * K + a_k0), (short)0, tile_bytes, 0x00020000);
         if (EPI == EPI_SWIGLU) {
             const bf16_t *Wp = (wave & 1) ? p.W1 : p.W0;
-            if (KB) w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(tn * 128) * 32 + w_k0), (short)0, (int)((unsigned)(nh - 1) * w_half + 8192u), 0x00020000);
+            if (WKB) w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(tn * 128) * 32 + w_k0), (short)0, (int)((unsigned)(nh - 1) * w_half + 8192u), 0x00020000);
             else w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(tn * 128) * K + w_k0), (short)0, tile_bytes / 2, 0x00020000);
         } else {
             const int n = tn * BN;
             const int seg = __builtin_amdgcn_readfirstlane(n / p.segN);
             const bf16_t *Wp = seg == 0 ? p.W0 : (seg == 1 ? p.W1 : p.W2);
-            if (KB) w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * 32 + w_k0), (short)0, (int)((unsigned)(nh - 1) * w_half + 16384u), 0x00020000);
+            if (WKB) w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * 32 + w_k0), (short)0, (int)((unsigned)(nh - 1) * w_half + 16384u), 0x00020000);
             else w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(Wp + (size_t)(n - seg * p.segN) * K + w_k0), (short)0, tile_bytes, 0x00020000);
         }
         ld_item = it;
@@ -300,9 +304,9 @@ __global__ void __launch_bounds__(256) gemm_bf16_dma_kernel(DmaGemmParams p) {
     // instruction pair i (0..3) of the cursor's half tile into LDS stage `stage`
     auto dma = [&](int stage, int i) {
         char *base = lds + stage * STAGE + wave * 4096 + i * 1024;
-        const int blk = i * 16 * row_bytes;
+        const int blk = i * 16 * row_bytes, w_blk = i * 16 * w_row_bytes;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_void *)base, 16, a_thread_off, (int)((unsigned)ld_h * a_half) + blk, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (lds_void *)(base + REGION), 16, w_thread_off, (int)((unsigned)ld_h * w_half) + blk, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (lds_void *)(base + REGION), 16, w_thread_off, (int)((unsigned)ld_h * w_half) + w_blk, 0, 0);
     };
     // next half tile, else the next item's first, else stay (the last half tile is fetched again, never used)
     auto advance = [&]() {
@@ -657,6 +661,13 @@ int try_gemm_bf16_dma_splitk(const GemmArgs &g, void *scratch, size_t scratch_by
     p.C = scratch; p.M = g.M; p.K = g.K; p.segN = g.segN;
     p.a_rows = g.a_rows; p.w_rows = 0; p.group = 4; p.splits = splits;
     p.tiles_m = 1; p.N = N; p.tiles_n = tiles;
+    // repacked copies of the weights, where the caller has them and the 32-bit offsets of the loads cover a segment
+    bool have_kb = g.Wkb[0] && (size_t)(g.segN + VLA_KB_PAD_ROWS) * g.K * 2 < ((size_t)1 << 31);
+    for (int i = 1; i < n_seg; i++) have_kb = have_kb && g.Wkb[i];
+    if (have_kb) {
+        p.W0 = (const bf16_t *)g.Wkb[0]; p.W1 = (const bf16_t *)g.Wkb[1]; p.W2 = (const bf16_t *)g.Wkb[2];
+        p.w_rows = g.segN + VLA_KB_PAD_ROWS; p.wkb = 1;
+    }
     int rc;
     {
         ProfScope ps(g.epilogue == EPI_SWIGLU ? "gemm_dma_splitk<swiglu>" : "gemm_dma_splitk<store>", 2.0 * g.M * g.K * (double)N, st);

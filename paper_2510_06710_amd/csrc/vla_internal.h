@@ -54,6 +54,8 @@ constexpr int VLA_KB_PAD_ROWS = 32;
 struct GemmArgs {
     const void *A;          // [M, K] row-major (lda = K), storage dtype (or fp32 for fp32 models)
     const void *W[3];       // up to three weight segments, each [segN, K] row-major
+    const void *Wkb[3];     // the same segments repacked k-blocked ([K / 32][segN + pad][32]) or NULL: kernels that stream
+                            // the weights from HBM with row-major activations (decode forwards) prefer these
     int n_seg, segN;        // N = n_seg * segN (EPI_SWIGLU: W[0] = gate, W[1] = up, N = segN)
     void *C;                // EPI_STORE: fp32 [M, N]; EPI_SWIGLU: storage dtype [M, N]; EPI_RESIDUAL: fp32 [M, N] +=
     int M, K;
